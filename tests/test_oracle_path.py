@@ -1,0 +1,237 @@
+"""Pins for the oracle's forward, backward and optimizer step.
+
+Forward and backward are checked against the explicit sketching matrix of
+Section 4 (one +-1 per row) built with arbitrary-precision integers on tiny
+inputs, against direct circular reads, and against invariants that hold at
+any size.  The optimizer step is checked against torch.optim.Adagrad on CPU.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from tests import brute
+
+P = 2**31 - 1
+
+
+def _tiny_case(seed, m, d, Z, sign, B, F, card=50):
+    H = oracle.init_hash(seed, m, d, Z, sign)
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(0, card, size=(B, F))
+    M = rng.standard_normal(m).astype(np.float32)
+    return H, ids, M
+
+
+CASES = [(1, 37, 16, 8, 1), (2, 37, 16, 8, 0), (3, 64, 16, 4, 1), (4, 16, 16, 16, 1),
+         (5, 101, 12, 1, 1), (6, 8, 16, 8, 0), (7, 1000, 6, 3, 1)]
+
+
+@pytest.mark.parametrize("seed,m,d,Z,sign", CASES)
+def test_single_hot_forward_equals_direct_circular_reads(seed, m, d, Z, sign):
+    B, F = 4, 3
+    H, ids, M = _tiny_case(seed, m, d, Z, sign, B, F)
+    out = oracle.forward(H, M, ids, None, B, F)
+    for b in range(B):
+        for f in range(F):
+            want = brute.embedding(H.coef, P, M, d, Z, sign, f, int(ids[b, f]))
+            assert out[b, f].tobytes() == np.array(want, dtype=np.float32).tobytes()
+
+
+def test_forward_of_identity_array_is_the_index_map():
+    # M[j] = j is exact in float32 for j < 2^24, so the output IS idx(e,x,i)
+    m, d, Z, B, F = 4099, 16, 4, 8, 5
+    H = oracle.init_hash(17, m, d, Z, 0)
+    ids = np.random.default_rng(0).integers(0, 10**6, size=(B, F))
+    out = oracle.forward(H, np.arange(m, dtype=np.float32), ids, None, B, F)
+    for b in range(B):
+        for f in range(F):
+            assert out[b, f].astype(np.int64).tolist() == brute.position_map(H.coef, P, m, d, Z, f, int(ids[b, f]))
+
+
+def test_negative_zero_and_sign_flip_are_exact():
+    m, d, Z = 16, 16, 16
+    H = oracle.init_hash(4, m, d, Z, 1)
+    M = np.zeros(m, dtype=np.float32)
+    M[::2] = -0.0
+    out = oracle.forward(H, M, np.array([[3]]), None, 1, 1)[0, 0]
+    pos = brute.position_map(H.coef, P, m, d, Z, 0, 3)
+    for i in range(d):
+        neg_in = np.signbit(M[pos[i]])
+        flip = brute.g(H.coef, P, 1, 0, 3, i) < 0
+        assert np.signbit(out[i]) == (neg_in != flip)
+
+
+def _random_bags(rng, rows, card, mean=3.0):
+    sizes = rng.poisson(mean, size=rows)
+    sizes[0] = 0                         # always include an empty bag
+    off = np.zeros(rows + 1, dtype=np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ids = rng.integers(0, card, size=int(off[-1]))
+    return ids, off
+
+
+@pytest.mark.parametrize("seed,m,d,Z,sign", CASES)
+def test_forward_and_backward_equal_the_sketching_matrix(seed, m, d, Z, sign):
+    # forward = S M (bag rows summed), backward = S^T G, S built by brute force
+    B, F = 3, 4
+    rng = np.random.default_rng(100 + seed)
+    H = oracle.init_hash(seed, m, d, Z, sign)
+    M = rng.standard_normal(m).astype(np.float32)
+    ids, off = _random_bags(rng, B * F, 40)
+    tokens = []
+    bag_of = []
+    for k in range(B * F):
+        for t in range(off[k], off[k + 1]):
+            tokens.append((k % F, int(ids[t])))
+            bag_of.append(k)
+    S = brute.sketch_matrix(H.coef, P, m, d, Z, sign, tokens)
+    assert np.all((S != 0).sum(axis=1) == 1)                  # exactly one +-1 per row
+    per_token = (S @ M.astype(np.float64)).reshape(len(tokens), d)
+    want = np.zeros((B * F, d))
+    for t, k in enumerate(bag_of):
+        want[k] += per_token[t]
+    out = oracle.forward(H, M, ids, off, B, F).reshape(B * F, d)
+    np.testing.assert_allclose(out, want.astype(np.float32), rtol=0, atol=0)
+    assert not out[0].any() and not np.signbit(out[0]).any()    # empty bag -> +0.0
+
+    G = rng.standard_normal((B, F, d)).astype(np.float32)
+    g_tok = G.reshape(B * F, d)[bag_of].astype(np.float64).ravel()
+    want_ga = S.T @ g_tok
+    ga, ab = oracle.backward(H, G, ids, off, B, F)
+    np.testing.assert_allclose(ga, want_ga, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(ab, np.abs(S).T @ np.abs(g_tok), rtol=1e-13, atol=1e-13)
+    # adjoint identity <S M, G> = <M, S^T G>
+    lhs = float((want * G.reshape(B * F, d)).sum())
+    assert abs(lhs - float(M.astype(np.float64) @ ga)) <= 1e-9 * (1 + abs(lhs))
+
+
+def test_single_hot_backward_equals_transposed_jacobian():
+    B, F, m, d, Z = 5, 3, 53, 8, 4
+    H = oracle.init_hash(77, m, d, Z, 1)
+    rng = np.random.default_rng(3)
+    ids = rng.integers(0, 6, size=(B, F))                      # few tokens: many duplicates
+    tokens = [(f, int(ids[b, f])) for b in range(B) for f in range(F)]
+    S = brute.sketch_matrix(H.coef, P, m, d, Z, 1, tokens)
+    G = rng.standard_normal((B, F, d)).astype(np.float32)
+    ga, _ = oracle.backward(H, G, ids, None, B, F)
+    np.testing.assert_allclose(ga, S.T @ G.astype(np.float64).ravel(), rtol=1e-13, atol=1e-13)
+
+
+def test_bag_of_one_equals_single_hot_and_bag_sum_equals_sum_of_rows():
+    w = workloads.get("tiny")
+    H = oracle.init_hash(5, 4096, 16, 4, 1)
+    M = workloads.make_array(4096, 0)
+    B, F = 6, w.n_features
+    rng = np.random.default_rng(8)
+    ids1 = rng.integers(0, 1000, size=(B, F))
+    single = oracle.forward(H, M, ids1, None, B, F)
+    as_bags = oracle.forward(H, M, ids1.ravel(), np.arange(B * F + 1), B, F)
+    assert single.tobytes() == as_bags.tobytes()
+
+    ids, off = _random_bags(rng, B * F, 1000, mean=4.0)
+    pooled = oracle.forward(H, M, ids, off, B, F).reshape(B * F, 16)
+    for k in range(B * F):
+        toks = ids[off[k]:off[k + 1]]
+        if toks.size == 0:
+            assert not pooled[k].any()
+            continue
+        # each token looked up on its own, as feature k % F: put it in column k % F of a 1-sample batch
+        acc = np.zeros(16)
+        for x in toks:
+            row = np.zeros((1, F), dtype=np.int64)
+            row[0, k % F] = x
+            acc += oracle.forward(H, M, row, None, 1, F)[0, k % F].astype(np.float64)
+        assert np.array_equal(pooled[k], acc.astype(np.float32))
+        # order inside a bag does not matter beyond rounding
+        perm = ids.copy()
+        perm[off[k]:off[k + 1]] = toks[::-1]
+        again = oracle.forward(H, M, perm, off, B, F).reshape(B * F, 16)[k]
+        np.testing.assert_allclose(again, pooled[k], rtol=1e-6, atol=1e-9)
+
+
+def test_backward_mass_conservation_without_sign():
+    # sign off: every gradient element lands in exactly one slot
+    w = workloads.get("tiny")
+    H = oracle.init_hash(w.hash_seed, w.m, w.d, w.Z, 0)
+    ids, _ = workloads.make_indices(w, 1)
+    G = workloads.make_grad_out(w, 2)
+    ga, ab = oracle.backward(H, G, ids, None, w.batch, w.n_features)
+    assert abs(ga.sum() - G.astype(np.float64).sum()) < 1e-8
+    assert abs(ab.sum() - np.abs(G.astype(np.float64)).sum()) < 1e-8
+    # bags: a row's gradient is delivered once per token of its bag
+    rng = np.random.default_rng(1)
+    idsb, off = _random_bags(rng, w.rows, 1000)
+    gab, _ = oracle.backward(H, G, idsb, off, w.batch, w.n_features)
+    sizes = np.diff(off).astype(np.float64)
+    want = (G.reshape(w.rows, w.d).astype(np.float64).sum(axis=1) * sizes).sum()
+    assert abs(gab.sum() - want) < 1e-7
+
+
+def test_backward_threads_do_not_change_the_result_beyond_rounding():
+    H = oracle.init_hash(1, 5000, 16, 4, 1)
+    rng = np.random.default_rng(2)
+    ids = rng.integers(0, 30, size=(64, 4))
+    G = rng.standard_normal((64, 4, 16)).astype(np.float32)
+    a, _ = oracle.backward(H, G, ids, None, 64, 4, threads=1)
+    b, _ = oracle.backward(H, G, ids, None, 64, 4, threads=4)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-12)
+
+
+def test_adagrad_matches_torch_cpu_and_touches_only_nonzero_gradients():
+    rng = np.random.default_rng(0)
+    n = 4096
+    M0 = rng.standard_normal(n).astype(np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(M0.astype(np.float64)))
+    opt = torch.optim.Adagrad([p], lr=0.01, eps=1e-8, initial_accumulator_value=0.0, lr_decay=0.0)
+    M, s = M0.copy(), np.zeros(n, dtype=np.float32)
+    ref_M = M0.astype(np.float64)
+    for step in range(3):
+        g = rng.standard_normal(n).astype(np.float32)
+        g[rng.random(n) < 0.5] = 0.0                 # half the slots untouched this step
+        before_M, before_s = M.copy(), s.copy()
+        p.grad = torch.from_numpy(g.astype(np.float64))
+        opt.step()
+        grad = g.copy()
+        oracle.adagrad(M, s, grad, 0.01, 1e-8)
+        assert not grad.any()                         # consumed and zeroed
+        untouched = g == 0
+        assert np.array_equal(M[untouched], before_M[untouched])
+        assert np.array_equal(s[untouched], before_s[untouched])
+        # torch keeps float64 state; ours is stored in float32 after every step
+        np.testing.assert_allclose(M, p.detach().numpy(), rtol=2e-6, atol=2e-7)
+        np.testing.assert_allclose(s, opt.state[p]["sum"].numpy(), rtol=1e-6)
+    assert not np.array_equal(M, M0)
+    del ref_M
+
+
+def test_adagrad_first_step_closed_form():
+    # from s = 0: M' = M - lr * g / (|g| + eps)
+    g = np.array([0.5, -2.0, 0.0, 1e-3], dtype=np.float32)
+    M = np.array([1.0, 1.0, 1.0, 1.0], dtype=np.float32)
+    s = np.zeros(4, dtype=np.float32)
+    oracle.adagrad(M, s, g.copy(), 0.01, 1e-8)
+    want = 1.0 - 0.01 * g.astype(np.float64) / (np.abs(g.astype(np.float64)) + 1e-8)
+    np.testing.assert_allclose(M, want.astype(np.float32), rtol=0, atol=0)
+    np.testing.assert_allclose(s, (g.astype(np.float64) ** 2).astype(np.float32), rtol=0, atol=0)
+
+
+def test_inner_product_estimator_is_unbiased_over_hash_draws():
+    # Theorem 1 (Section 4.1): E<x^, y^> = <x, y> for the signed projection.
+    # Loose Monte-Carlo check over seeds; it fails if the sign or the block
+    # placement were systematically wrong.
+    n_tok, d, Z, m = 6, 8, 4, 64
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((n_tok, d)).astype(np.float32)
+    Y = (X + 0.5 * rng.standard_normal((n_tok, d))).astype(np.float32)
+    true = float((X.astype(np.float64) * Y).sum())
+    ids = np.arange(n_tok).reshape(n_tok, 1)
+    est = []
+    for seed in range(400):
+        H = oracle.init_hash(seed, m, d, Z, 1)
+        xh, _ = oracle.backward(H, X.reshape(n_tok, 1, d), ids, None, n_tok, 1, want_abs=False)
+        yh, _ = oracle.backward(H, Y.reshape(n_tok, 1, d), ids, None, n_tok, 1, want_abs=False)
+        est.append(float(xh @ yh))
+    est = np.array(est)
+    assert abs(est.mean() - true) < 4 * est.std() / np.sqrt(len(est)) + 1e-9
