@@ -1,0 +1,163 @@
+/*
+ * robe.h - C ABI of the MI355X (gfx950) ROBE-Z embedding library.
+ *
+ * ROBE ("Random Offset Block Embedding Array", arXiv 2108.02191) replaces all
+ * embedding tables of a recommendation model by ONE circular array M of m
+ * floats.  The d-element embedding of token x of table e is the
+ * concatenation of d/Z blocks of Z consecutive array elements (wrapping past
+ * the end), block c starting at a universally hashed offset h(e,x,c); each
+ * element may be multiplied by a hashed sign g(e,x,i).  Gradients flow back
+ * by a signed sum into the same array.
+ *
+ * Equation numbers below count the paper's displayed equations in order:
+ *   Eq. 1  ROBE-D forward            (Section 3.1)
+ *   Eq. 2  h, idx and g for ROBE-D   (Section 3.1)
+ *   Eq. 3  backward pass             (Section 3.1)
+ *   Eq. 4  ROBE-Z forward            (Section 3.2)
+ *   Eq. 5  h and idx for ROBE-Z      (Section 3.2)
+ *
+ * General rules of this interface
+ *   - Plain C: pointers and sizes only.  "device" pointers are HIP device
+ *     memory of the current device, "host" pointers are ordinary memory.
+ *   - The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing and never synchronises: all GPU work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream) and the
+ *     call returns at once.  Buffers must stay valid until that work is done.
+ *   - Every function returns ROBE_OK (0) or a negative error code and never
+ *     aborts.  robe_last_error() gives the text of the calling thread's most
+ *     recent failure.  Arguments are validated on the host before anything is
+ *     launched; a failed call launches nothing.
+ *   - Token ids are int64 and are read as unsigned 64-bit integers in the hash
+ *     formulas (a negative id is the integer id + 2^64).  No cardinality is
+ *     needed: hashing accepts any id.
+ *   - Index conventions are 0-based: table id e = feature column, element
+ *     i in [0,d), chunk c = i / Z, position in chunk j = i mod Z.
+ *   - Layouts: single-hot ids `indices[batch][n_features]`; bags in (b,f)
+ *     row-major order, bag k = b*n_features + f, CSR `offsets[batch*n_features+1]`
+ *     with offsets[0] = 0 and offsets[last] = n_indices, `indices[n_indices]`;
+ *     `out` / `grad_out` are `[batch][n_features][d]` float32, row-major.
+ */
+#ifndef ROBE_H
+#define ROBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROBE_OK       0
+#define ROBE_EINVAL  (-1)  /* bad argument: null pointer, bad shape, value out of range */
+#define ROBE_EHIP    (-2)  /* a HIP runtime call or kernel launch failed                 */
+
+#define ROBE_PRIME 2147483647u /* P = 2^31 - 1, the "large prime" of Eq. 2 / Eq. 5 */
+
+/*
+ * One ROBE-Z instance (Eq. 5 and the text under it; g from Eq. 2).
+ * Plain data, owned by the caller, copied by value into kernel arguments.
+ *   m          array length in floats, 1 <= m <= 2^31 - 1
+ *   d, Z       embedding size and block size, Z >= 1, Z divides d, Z <= m
+ *   use_sign   0: g == +1 everywhere; non-zero: g as in Eq. 2
+ *   P          must be ROBE_PRIME
+ *   Ah,Bh,Ch   multipliers of h in [1, P-1];  Dh additive constant in [0, P-1]
+ *   Ag,Bg,Cg   multipliers of g in [1, P-1];  Dg additive constant in [0, P-1]
+ *
+ *   h(e,x,c)   = ((Ah*e + Bh*x + Ch*c + Dh) mod P) mod m
+ *   idx(e,x,i) = (h(e,x,i / Z) + i mod Z) mod m
+ *   g(e,x,i)   = 2*(((Ag*e + Bg*x + Cg*i + Dg) mod P) mod 2) - 1
+ * all evaluated over the integers.
+ */
+typedef struct robe_hash_t {
+    uint64_t m;
+    uint32_t d, Z;
+    uint32_t use_sign;
+    uint32_t P;
+    uint32_t Ah, Bh, Ch, Dh;
+    uint32_t Ag, Bg, Cg, Dg;
+} robe_hash_t;
+
+/*
+ * Draw the hash coefficients from a seed (host only; Section 3.2: "randomly
+ * chosen values").  The stream is SplitMix64 (Steele, Lea, Flood 2014) started
+ * at state `seed`; eight successive outputs r give, in this order,
+ * Ah,Bh,Ch = 1 + r mod (P-1), Dh = r mod P, Ag,Bg,Cg = 1 + r mod (P-1),
+ * Dg = r mod P.  `out` (host) receives the complete struct.
+ * Errors: ROBE_EINVAL for out == NULL or shapes that violate the rules above.
+ */
+int robe_init_hash(uint64_t seed, uint64_t m, uint32_t d, uint32_t Z, int use_sign, robe_hash_t *out);
+
+/*
+ * Testing aid: the integer maps alone (Eq. 5 for h, Eq. 2 for g).
+ *   indices      device int64[n]; lookup k belongs to table k mod n_features
+ *   out_offsets  device int64[n * d/Z] or NULL:  out_offsets[k*(d/Z) + c] = h(e,x,c)
+ *   out_signs    device int8 [n * d]   or NULL:  out_signs[k*d + i] = g(e,x,i)
+ * Errors: ROBE_EINVAL (null hash/indices with n > 0, n < 0, n_features < 1,
+ * invalid hash); ROBE_EHIP on launch failure.  n == 0 is a no-op.
+ */
+int robe_offsets(const robe_hash_t *hash, const int64_t *indices, int64_t n, int32_t n_features,
+                 int64_t *out_offsets, int8_t *out_signs, void *stream);
+
+/*
+ * Forward lookup (Eq. 4 with idx from Eq. 5, E = G o P).
+ *   array      device float[m], read only
+ *   indices    device int64[n_indices]
+ *   offsets    NULL: single-hot, n_indices must equal batch*n_features and
+ *                    out[k][i] = g(f,x_k,i) * array[idx(f,x_k,i)]   (a copy with an exact sign flip)
+ *              device int64[batch*n_features + 1]: bag-sum,
+ *                    out[k][i] = sum over t in [offsets[k], offsets[k+1]) of g(f,x_t,i) * array[idx(f,x_t,i)],
+ *                    duplicates counted each time, empty bag -> +0.0, summed in
+ *                    float32 in token order.  Bag bounds are clamped to
+ *                    [0, n_indices] on the device, so a malformed CSR cannot
+ *                    read outside `indices`.
+ *   out        device float[batch][n_features][d], fully overwritten
+ * Errors: ROBE_EINVAL, ROBE_EHIP.  batch == 0 is a no-op.
+ */
+int robe_forward(const robe_hash_t *hash, const float *array,
+                 const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                 int64_t batch, int32_t n_features, float *out, void *stream);
+
+/*
+ * Bytes of device workspace robe_backward needs for this problem size
+ * (0 when none is needed).  Returns 0 on invalid arguments as well.
+ */
+size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices);
+
+/*
+ * Backward scatter-add (Eq. 3):
+ *   grad_array[j] += sum over (k, t, i) with idx(f,x_t,i) == j of g(f,x_t,i) * grad_out[k][i]
+ * where every token t of bag k receives row k of grad_out (single-hot: one
+ * token per row).  Accumulates onto the caller's grad_array (device float[m]);
+ * the order of the float32 additions is not fixed, so results agree with an
+ * exact sum only to rounding.
+ *   workspace  device buffer of at least robe_workspace_bytes(...) bytes,
+ *              256-byte aligned, contents undefined before and after; may be
+ *              NULL when that size is 0
+ * Errors: ROBE_EINVAL (also: workspace too small), ROBE_EHIP.
+ */
+int robe_backward(const robe_hash_t *hash, const float *grad_out,
+                  const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                  int64_t batch, int32_t n_features, float *grad_array,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Sparse Adagrad step on the touched slots (Duchi, Hazan, Singer 2011; the
+ * optimizer is named by the workload, not by the paper).  For every j with
+ * grad_array[j] != 0, in float32 with each operation rounded on its own:
+ *   state[j] += grad_array[j]^2
+ *   array[j] -= lr * grad_array[j] / (sqrt(state[j]) + eps)
+ *   grad_array[j] = 0
+ * Slots with a zero gradient are left bit-for-bit unchanged, which is what a
+ * dense Adagrad step does to them too.  All three are device float[m].
+ * Errors: ROBE_EINVAL (null pointers, eps <= 0, non-finite lr/eps), ROBE_EHIP.
+ */
+int robe_adagrad_update(const robe_hash_t *hash, float *array, float *state, float *grad_array,
+                        float lr, float eps, void *stream);
+
+/* Text of the calling thread's most recent error ("" if none).  Never NULL. */
+const char *robe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROBE_H */

@@ -1,0 +1,163 @@
+"""ROBE-Z embedding lookup for MI355X (gfx950): thin Python binding of ``librobe.so``.
+
+The functions here have the names and semantics of the C ABI in
+``include/robe.h`` (arXiv 2108.02191, Section 3: Eq. 4/5 forward, Eq. 3
+backward, Eq. 2 sign hash).  They only marshal arguments: every step of the
+path runs in the HIP kernels of the library.  PyTorch supplies device memory
+and the current stream, nothing else.  There is no CPU fallback: if the
+library is not built, importing a function's result fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # loads the HIP runtime the library binds to
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librobe.so")
+
+ROBE_OK, ROBE_EINVAL, ROBE_EHIP = 0, -1, -2
+ROBE_PRIME = 2**31 - 1
+
+
+class RobeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"robe error {code}: {msg}")
+        self.code = code
+
+
+class RobeHash(ctypes.Structure):
+    """Mirror of ``robe_hash_t``."""
+    _fields_ = [("m", ctypes.c_uint64), ("d", ctypes.c_uint32), ("Z", ctypes.c_uint32),
+                ("use_sign", ctypes.c_uint32), ("P", ctypes.c_uint32),
+                ("Ah", ctypes.c_uint32), ("Bh", ctypes.c_uint32), ("Ch", ctypes.c_uint32), ("Dh", ctypes.c_uint32),
+                ("Ag", ctypes.c_uint32), ("Bg", ctypes.c_uint32), ("Cg", ctypes.c_uint32), ("Dg", ctypes.c_uint32)]
+
+    @property
+    def coef(self):
+        return (self.Ah, self.Bh, self.Ch, self.Dh, self.Ag, self.Bg, self.Cg, self.Dg)
+
+    @property
+    def chunks(self) -> int:
+        return self.d // self.Z
+
+
+EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
+           "robe_adagrad_update", "robe_last_error")
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built (``python -m paper_2108_02191_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2108_02191_amd.build` "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        HP = ctypes.POINTER(RobeHash)
+        vp, i64, i32, u64, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_uint32
+        L.robe_init_hash.restype = ctypes.c_int
+        L.robe_init_hash.argtypes = [u64, u64, u32, u32, ctypes.c_int, HP]
+        L.robe_offsets.restype = ctypes.c_int
+        L.robe_offsets.argtypes = [HP, vp, i64, i32, vp, vp, vp]
+        L.robe_forward.restype = ctypes.c_int
+        L.robe_forward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp]
+        L.robe_workspace_bytes.restype = ctypes.c_size_t
+        L.robe_workspace_bytes.argtypes = [HP, i64, i32, i64]
+        L.robe_backward.restype = ctypes.c_int
+        L.robe_backward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_size_t, vp]
+        L.robe_adagrad_update.restype = ctypes.c_int
+        L.robe_adagrad_update.argtypes = [HP, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp]
+        L.robe_last_error.restype = ctypes.c_char_p
+        L.robe_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != ROBE_OK:
+        raise RobeError(rc, lib().robe_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: Optional[torch.Tensor], dtype: torch.dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+def robe_init_hash(seed: int, m: int, d: int, Z: int, use_sign: int) -> RobeHash:
+    h = RobeHash()
+    _check(lib().robe_init_hash(seed & (2**64 - 1), m, d, Z, int(bool(use_sign)), ctypes.byref(h)))
+    return h
+
+
+def robe_offsets(h: RobeHash, indices: torch.Tensor, n_features: int, want_signs: bool = False):
+    """Testing aid: chunk offsets int64[n, d/Z] (and element signs int8[n, d])."""
+    n = indices.numel()
+    off = torch.empty((n, h.chunks), dtype=torch.int64, device=indices.device)
+    sg = torch.empty((n, h.d), dtype=torch.int8, device=indices.device) if want_signs else None
+    _check(lib().robe_offsets(ctypes.byref(h), _dev(indices, torch.int64, "indices"), n, n_features,
+                              off.data_ptr(), None if sg is None else sg.data_ptr(), _stream()))
+    return (off, sg) if want_signs else off
+
+
+def robe_forward(h: RobeHash, array: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                 batch: int, n_features: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if array.numel() != h.m:
+        raise ValueError("array length differs from hash.m")
+    if offsets is not None and offsets.numel() != batch * n_features + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    if out is None:
+        out = torch.empty((batch, n_features, h.d), dtype=torch.float32, device=array.device)
+    elif out.numel() != batch * n_features * h.d:
+        raise ValueError("out has the wrong size")
+    _check(lib().robe_forward(ctypes.byref(h), _dev(array, torch.float32, "array"),
+                              _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                              indices.numel(), batch, n_features, _dev(out, torch.float32, "out"), _stream()))
+    return out
+
+
+def robe_workspace_bytes(h: RobeHash, batch: int, n_features: int, n_indices: int) -> int:
+    return int(lib().robe_workspace_bytes(ctypes.byref(h), batch, n_features, n_indices))
+
+
+def robe_backward(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                  batch: int, n_features: int, grad_array: torch.Tensor,
+                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """grad_array += scatter of grad_out (in place); returns grad_array."""
+    if grad_array.numel() != h.m:
+        raise ValueError("grad_array length differs from hash.m")
+    if grad_out.numel() != batch * n_features * h.d:
+        raise ValueError("grad_out has the wrong size")
+    if offsets is not None and offsets.numel() != batch * n_features + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    need = robe_workspace_bytes(h, batch, n_features, indices.numel())
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=grad_array.device)
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_len = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().robe_backward(ctypes.byref(h), _dev(grad_out, torch.float32, "grad_out"),
+                               _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                               indices.numel(), batch, n_features, _dev(grad_array, torch.float32, "grad_array"),
+                               ws_ptr, ws_len, _stream()))
+    return grad_array
+
+
+def robe_adagrad_update(h: RobeHash, array: torch.Tensor, state: torch.Tensor, grad_array: torch.Tensor,
+                        lr: float, eps: float) -> None:
+    for t, name in ((array, "array"), (state, "state"), (grad_array, "grad_array")):
+        if t.numel() != h.m:
+            raise ValueError(f"{name} length differs from hash.m")
+    _check(lib().robe_adagrad_update(ctypes.byref(h), _dev(array, torch.float32, "array"),
+                                     _dev(state, torch.float32, "state"),
+                                     _dev(grad_array, torch.float32, "grad_array"), lr, eps, _stream()))

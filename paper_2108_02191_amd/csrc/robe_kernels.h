@@ -1,0 +1,440 @@
+// HIP kernels of the ROBE-Z path for gfx950 (wave64).
+//
+// Work decomposition shared by the forward gather and the backward scatter:
+//
+//   * A wavefront owns a tile of rows (single-hot: TL consecutive lookups;
+//     bags: 64/G consecutive bags).  In a first pass every lane hashes ONE
+//     token of the tile - the part of h and g that depends on the token and on
+//     the table id, (B*x + A*e + D) mod P - so the 64-bit modular work is done
+//     once per token instead of once per lane that touches the token.
+//   * In a second pass a group of G = d/V lanes walks the tile's tokens.  A
+//     lane fetches the staged token term from the lane that hashed it
+//     (wavefront shuffle), adds its own chunk term (C*c) mod P, which is a
+//     per-lane constant, and finishes with one reciprocal-multiply `mod m`.
+//   * A lane owns V elements of a row.  CONSEC layout: V consecutive elements
+//     of one chunk (one hash, one unaligned 4V-byte load).  STRIDED layout:
+//     elements grp + k*G, k < V (lanes of a group touch consecutive addresses,
+//     which is what coalesces float atomics, and what Z < V needs).
+//
+// The integer maps are those of Eq. 5 (h, idx) and Eq. 2 (g) of the paper; the
+// gather is Eq. 4, the scatter Eq. 3.
+#pragma once
+#include "robe_device.h"
+
+namespace robe {
+
+constexpr int kBlock = 256;           // 4 wavefronts
+constexpr int kWavesPerBlock = kBlock / 64;
+constexpr int kUnroll = 4;            // tokens in flight per lane group
+
+// Launch geometry, filled on the host.
+struct Geom {
+    uint32_t F;        // number of tables (features)
+    uint32_t G;        // lanes per row, power of two, <= 64; d = G * V
+    uint32_t g_shift;  // log2(G)
+    uint32_t TL;       // rows per wavefront tile (single-hot kernels), multiple of 64/G, <= 64
+};
+
+template <int V>
+struct Vec {
+    typedef float A __attribute__((ext_vector_type(V)));  // V floats at natural vector alignment
+    typedef A U __attribute__((aligned(4)));              // the same at 4-byte alignment
+};
+
+// Per-lane constants: which elements this lane owns and their chunk terms.
+template <int V, bool CONSEC, bool SIGN>
+struct Lane {
+    static constexpr int NH = CONSEC ? 1 : V;   // distinct (chunk, position) pairs
+    uint32_t cc[NH];                             // (Ch * c) mod P
+    uint32_t jj[NH];                             // position inside the chunk
+    uint32_t cg[SIGN ? V : 1];                   // (Cg * i) mod P per owned element
+
+    __device__ __forceinline__ void init(const Params &p, const Geom &q, uint32_t grp)
+    {
+#pragma unroll
+        for (int k = 0; k < NH; ++k) {
+            const uint32_t i = CONSEC ? grp * V : grp + (uint32_t)k * q.G;
+            const uint32_t c = i / p.Z;
+            jj[k] = i - c * p.Z;
+            cc[k] = mod_p((uint64_t)p.Ch * c);
+        }
+        if constexpr (SIGN) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                const uint32_t i = CONSEC ? grp * V + k : grp + (uint32_t)k * q.G;
+                cg[k] = mod_p((uint64_t)p.Cg * i);
+            }
+        }
+    }
+
+    // Array position of pair k for a token whose staged term is th.
+    __device__ __forceinline__ uint32_t position(const Params &p, uint32_t th, int k) const
+    {
+        return wrap(offset_of(p, th, cc[k]) + jj[k], p.m);
+    }
+
+    __device__ __forceinline__ uint32_t mask(uint32_t tg, int k) const
+    {
+        return SIGN ? sign_mask(add_p(tg, cg[k])) : 0u;
+    }
+
+    // v[k] = g * M[idx] for the V owned elements of one token.
+    __device__ __forceinline__ void gather(const Params &p, const float *__restrict__ array,
+                                           uint32_t th, uint32_t tg, float (&v)[V]) const
+    {
+        if constexpr (CONSEC) {
+            const uint32_t pos = position(p, th, 0);
+            if (V == 1 || pos + V <= p.m) {
+                const typename Vec<V>::A u = *reinterpret_cast<const typename Vec<V>::U *>(array + pos);
+#pragma unroll
+                for (int k = 0; k < V; ++k) v[k] = u[k];
+            } else {  // the lane's own span crosses the end of the circular array
+#pragma unroll
+                for (int k = 0; k < V; ++k) v[k] = array[wrap(pos + k, p.m)];
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < V; ++k) v[k] = array[position(p, th, k)];
+        }
+        if constexpr (SIGN) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) v[k] = apply_sign(v[k], mask(tg, k));
+        }
+    }
+
+    // grad_array[idx] += g * v[k] for the V owned elements of one token.
+    __device__ __forceinline__ void scatter(const Params &p, float *__restrict__ grad_array,
+                                            uint32_t th, uint32_t tg, const float (&v)[V]) const
+    {
+        const uint32_t pos0 = CONSEC ? position(p, th, 0) : 0u;
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            // CONSEC: every element wraps on its own
+            const uint32_t pos = CONSEC ? wrap(pos0 + (uint32_t)k, p.m) : position(p, th, k);
+            const float val = SIGN ? apply_sign(v[k], mask(tg, k)) : v[k];
+            __hip_atomic_fetch_add(grad_array + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+};
+
+// Load / store the V owned elements of one output row.
+template <int V, bool CONSEC>
+__device__ __forceinline__ void store_row(float *__restrict__ row, const Geom &q, uint32_t grp, const float (&v)[V])
+{
+    if constexpr (CONSEC) {
+        typename Vec<V>::A a;
+#pragma unroll
+        for (int k = 0; k < V; ++k) a[k] = v[k];
+        __builtin_nontemporal_store(a, reinterpret_cast<typename Vec<V>::A *>(row + grp * V));
+    } else {
+#pragma unroll
+        for (int k = 0; k < V; ++k) __builtin_nontemporal_store(v[k], row + grp + (uint32_t)k * q.G);
+    }
+}
+
+template <int V, bool CONSEC>
+__device__ __forceinline__ void load_row(const float *__restrict__ row, const Geom &q, uint32_t grp, float (&v)[V])
+{
+    if constexpr (CONSEC) {
+        const typename Vec<V>::A a = __builtin_nontemporal_load(reinterpret_cast<const typename Vec<V>::A *>(row + grp * V));
+#pragma unroll
+        for (int k = 0; k < V; ++k) v[k] = a[k];
+    } else {
+#pragma unroll
+        for (int k = 0; k < V; ++k) v[k] = __builtin_nontemporal_load(row + grp + (uint32_t)k * q.G);
+    }
+}
+
+// Token-and-table part of h (and of g) for one token.
+__device__ __forceinline__ uint32_t staged_h(const Params &p, int64_t x, uint32_t e)
+{
+    return add_p(token_term(p.Bh, x), mod_p((uint64_t)p.Ah * e + p.Dh));
+}
+__device__ __forceinline__ uint32_t staged_g(const Params &p, int64_t x, uint32_t e)
+{
+    return add_p(token_term(p.Bg, x), mod_p((uint64_t)p.Ag * e + p.Dg));
+}
+
+// ---------------------------------------------------------------------------
+// Single-hot forward / backward: one wavefront per tile of TL lookups.
+// ---------------------------------------------------------------------------
+template <int V, bool CONSEC, bool SIGN, bool BWD>
+__global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
+                                                            const float *__restrict__ src,   // fwd: array; bwd: grad_out
+                                                            const int64_t *__restrict__ indices,
+                                                            int64_t rows,
+                                                            float *__restrict__ dst)         // fwd: out; bwd: grad_array
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t row0 = wave * (int64_t)q.TL;
+    if (row0 >= rows) return;  // uniform over the wavefront
+    const uint32_t n = (uint32_t)((rows - row0) < (int64_t)q.TL ? (rows - row0) : (int64_t)q.TL);
+
+    // pass 1: lane l hashes lookup row0 + l
+    uint32_t th = 0, tg = 0;
+    {
+        const uint32_t e0 = (uint32_t)(row0 % (int64_t)q.F);
+        if (lane < n) {
+            const int64_t x = indices[row0 + lane];
+            const uint32_t e = (e0 + lane) % q.F;
+            th = staged_h(p, x, e);
+            if constexpr (SIGN) tg = staged_g(p, x, e);
+        }
+    }
+
+    // pass 2: groups of G lanes walk the tile, 64/G rows per step
+    const uint32_t grp = lane & (q.G - 1u);
+    const uint32_t sub = lane >> q.g_shift;
+    const uint32_t step = 64u >> q.g_shift;
+    Lane<V, CONSEC, SIGN> L;
+    L.init(p, q, grp);
+
+    for (uint32_t r = 0; r < n; r += step * kUnroll) {  // trip count uniform over the wavefront
+        uint32_t rl[kUnroll], thr[kUnroll], tgr[kUnroll];
+        bool live[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            rl[u] = r + (uint32_t)u * step + sub;
+            live[u] = rl[u] < n;
+            const uint32_t srcl = live[u] ? rl[u] : 0u;
+            thr[u] = __shfl(th, (int)srcl);
+            tgr[u] = SIGN ? __shfl(tg, (int)srcl) : 0u;
+        }
+        if constexpr (!BWD) {
+            float v[kUnroll][V];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u]);  // lookup 0 stands in for dead slots
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (live[u]) store_row<V, CONSEC>(dst + (row0 + rl[u]) * (int64_t)p.d, q, grp, v[u]);
+        } else {
+            float v[kUnroll][V];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint32_t safe = live[u] ? rl[u] : 0u;
+                load_row<V, CONSEC>(src + (row0 + safe) * (int64_t)p.d, q, grp, v[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (live[u]) L.scatter(p, dst, thr[u], tgr[u], v[u]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Bag-sum forward / bag backward: one group of G lanes per bag, 64/G bags per
+// wavefront.  A group stages up to G of its bag's tokens at a time.
+// ---------------------------------------------------------------------------
+template <int V, bool CONSEC, bool SIGN, bool BWD>
+__global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
+                                                     const float *__restrict__ src,      // fwd: array; bwd: grad_out
+                                                     const int64_t *__restrict__ indices,
+                                                     const int64_t *__restrict__ offsets,
+                                                     int64_t rows, int64_t n_indices,
+                                                     float *__restrict__ dst)            // fwd: out; bwd: grad_array
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const uint32_t step = 64u >> q.g_shift;                 // bags per wavefront
+    const int64_t bag0 = wave * (int64_t)step;
+    if (bag0 >= rows) return;                               // uniform over the wavefront
+    const uint32_t grp = lane & (q.G - 1u);
+    const uint32_t sub = lane >> q.g_shift;
+    const uint32_t base_lane = lane - grp;                  // first lane of this group
+    const int64_t bag = bag0 + sub;
+    const bool have_bag = bag < rows;
+
+    int64_t t0 = 0, t1 = 0;
+    if (have_bag) {
+        t0 = offsets[bag];
+        t1 = offsets[bag + 1];
+        t0 = t0 < 0 ? 0 : (t0 > n_indices ? n_indices : t0);
+        t1 = t1 < t0 ? t0 : (t1 > n_indices ? n_indices : t1);
+    }
+    const uint32_t e = ((uint32_t)(bag0 % (int64_t)q.F) + sub) % q.F;
+
+    Lane<V, CONSEC, SIGN> L;
+    L.init(p, q, grp);
+
+    float acc[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+    if constexpr (BWD) {
+        if (have_bag) load_row<V, CONSEC>(src + bag * (int64_t)p.d, q, grp, acc);
+    }
+
+    for (int64_t tb = t0; __any(tb < t1); tb += q.G) {
+        // stage: lane `grp` of the group hashes token tb + grp
+        const int64_t left = t1 - tb;                       // <= 0 once this group is done
+        const uint32_t cnt = left <= 0 ? 0u : (left < (int64_t)q.G ? (uint32_t)left : q.G);
+        uint32_t th = 0, tg = 0;
+        if (grp < cnt) {
+            const int64_t x = indices[tb + grp];
+            th = staged_h(p, x, e);
+            if constexpr (SIGN) tg = staged_g(p, x, e);
+        }
+        for (uint32_t u0 = 0; __any(u0 < cnt); u0 += kUnroll) {
+            uint32_t thr[kUnroll], tgr[kUnroll];
+            bool live[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                live[u] = u0 + u < cnt;
+                const uint32_t srcl = base_lane + (live[u] ? u0 + u : 0u);
+                thr[u] = __shfl(th, (int)srcl);
+                tgr[u] = SIGN ? __shfl(tg, (int)srcl) : 0u;
+            }
+            if constexpr (!BWD) {
+                float v[kUnroll][V];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u]);
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    if (live[u]) {
+#pragma unroll
+                        for (int k = 0; k < V; ++k) acc[k] += v[u][k];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u)
+                    if (live[u]) L.scatter(p, dst, thr[u], tgr[u], acc);
+            }
+        }
+    }
+    if constexpr (!BWD) {
+        if (have_bag) store_row<V, CONSEC>(dst + bag * (int64_t)p.d, q, grp, acc);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Shape-generic fallback (any d, Z with Z | d): one thread per (row, element),
+// every hash evaluated in full by the thread that needs it.
+// ---------------------------------------------------------------------------
+template <bool SIGN, bool BWD>
+__global__ __launch_bounds__(kBlock) void generic_kernel(Params p, uint32_t F, uint32_t rows_per_block,
+                                                         const float *__restrict__ src,
+                                                         const int64_t *__restrict__ indices,
+                                                         const int64_t *__restrict__ offsets,  // NULL: single-hot
+                                                         int64_t rows, int64_t n_indices,
+                                                         float *__restrict__ dst)
+{
+    const int64_t row_base = (int64_t)blockIdx.x * rows_per_block;
+    const uint32_t e_base = (uint32_t)(row_base % (int64_t)F);
+    const uint64_t items = (uint64_t)rows_per_block * p.d;
+    for (uint64_t local = threadIdx.x; local < items; local += kBlock) {
+        const uint32_t rl = (uint32_t)(local / p.d);
+        const uint32_t i = (uint32_t)(local - (uint64_t)rl * p.d);
+        const int64_t row = row_base + rl;
+        if (row >= rows) break;
+        const uint32_t e = (e_base + rl) % F;
+        const uint32_t c = i / p.Z, j = i - c * p.Z;
+        const uint32_t cc = mod_p((uint64_t)p.Ch * c);
+        const uint32_t cg = SIGN ? mod_p((uint64_t)p.Cg * i) : 0u;
+        int64_t t0 = row, t1 = row + 1;
+        if (offsets != nullptr) {
+            t0 = offsets[row];
+            t1 = offsets[row + 1];
+            t0 = t0 < 0 ? 0 : (t0 > n_indices ? n_indices : t0);
+            t1 = t1 < t0 ? t0 : (t1 > n_indices ? n_indices : t1);
+        }
+        float acc = BWD ? src[row * (int64_t)p.d + i] : 0.0f;
+        for (int64_t t = t0; t < t1; ++t) {
+            const int64_t x = indices[t];
+            const uint32_t pos = wrap(offset_of(p, staged_h(p, x, e), cc) + j, p.m);
+            const uint32_t msk = SIGN ? sign_mask(add_p(staged_g(p, x, e), cg)) : 0u;
+            if constexpr (BWD) {
+                __hip_atomic_fetch_add(dst + pos, apply_sign(acc, msk), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                const float v = apply_sign(src[pos], msk);
+                acc = (offsets == nullptr) ? v : acc + v;   // single-hot keeps the sign of zero
+            }
+        }
+        if constexpr (!BWD) dst[row * (int64_t)p.d + i] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Integer maps alone (testing aid): one thread per (lookup, chunk) / (lookup, element).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void offsets_kernel(Params p, uint32_t F, const int64_t *__restrict__ indices,
+                                                         int64_t n, int64_t *__restrict__ out)
+{
+    const int64_t total = n * (int64_t)p.C;
+    for (int64_t it = (int64_t)blockIdx.x * kBlock + threadIdx.x; it < total; it += (int64_t)gridDim.x * kBlock) {
+        const int64_t k = it / p.C;
+        const uint32_t c = (uint32_t)(it - k * p.C);
+        const uint32_t e = (uint32_t)(k % (int64_t)F);
+        out[it] = (int64_t)offset_of(p, staged_h(p, indices[k], e), mod_p((uint64_t)p.Ch * c));
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void signs_kernel(Params p, uint32_t F, uint32_t use_sign,
+                                                       const int64_t *__restrict__ indices, int64_t n,
+                                                       int8_t *__restrict__ out)
+{
+    const int64_t total = n * (int64_t)p.d;
+    for (int64_t it = (int64_t)blockIdx.x * kBlock + threadIdx.x; it < total; it += (int64_t)gridDim.x * kBlock) {
+        const int64_t k = it / p.d;
+        const uint32_t i = (uint32_t)(it - k * p.d);
+        const uint32_t e = (uint32_t)(k % (int64_t)F);
+        const uint32_t res = add_p(staged_g(p, indices[k], e), mod_p((uint64_t)p.Cg * i));
+        out[it] = (!use_sign || (res & 1u)) ? (int8_t)1 : (int8_t)-1;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Adagrad on touched slots.  Explicitly rounded float32 steps (no contraction).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void adagrad_one(float &w, float &s, float g, float lr, float eps)
+{
+    s = __fadd_rn(s, __fmul_rn(g, g));
+    w = __fsub_rn(w, __fdiv_rn(__fmul_rn(lr, g), __fadd_rn(__fsqrt_rn(s), eps)));
+}
+
+template <int V>
+__global__ __launch_bounds__(kBlock) void adagrad_kernel(float *__restrict__ array, float *__restrict__ state,
+                                                         float *__restrict__ grad, uint64_t m, float lr, float eps)
+{
+    const uint64_t nvec = m / V;
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    for (uint64_t it = (uint64_t)blockIdx.x * kBlock + threadIdx.x; it < nvec; it += stride) {
+        typedef typename Vec<V>::A VT;
+        VT g = *reinterpret_cast<const VT *>(grad + it * V);
+        bool any = false;
+#pragma unroll
+        for (int k = 0; k < V; ++k) any |= (g[k] != 0.0f);
+        if (!any) continue;  // untouched: nothing read beyond the gradient, nothing written
+        VT w = *reinterpret_cast<const VT *>(array + it * V);
+        VT s = *reinterpret_cast<const VT *>(state + it * V);
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            if (g[k] != 0.0f) {
+                float wk = w[k], sk = s[k];
+                adagrad_one(wk, sk, g[k], lr, eps);
+                w[k] = wk;
+                s[k] = sk;
+            }
+            g[k] = 0.0f;
+        }
+        *reinterpret_cast<VT *>(array + it * V) = w;
+        *reinterpret_cast<VT *>(state + it * V) = s;
+        *reinterpret_cast<VT *>(grad + it * V) = g;
+    }
+    // tail (m not a multiple of V): first threads of block 0
+    if (V > 1 && blockIdx.x == 0) {
+        const uint64_t j = nvec * V + threadIdx.x;
+        if (threadIdx.x < V && j < m) {
+            const float g = grad[j];
+            if (g != 0.0f) {
+                float w = array[j], s = state[j];
+                adagrad_one(w, s, g, lr, eps);
+                array[j] = w;
+                state[j] = s;
+                grad[j] = 0.0f;
+            }
+        }
+    }
+}
+
+}  // namespace robe

@@ -1,0 +1,84 @@
+"""Host-side checks of the C-ABI library: it loads, exports what the header
+declares, draws the documented coefficients, and turns bad arguments into
+error codes before anything touches a GPU.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2108_02191_amd as robe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "robe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(robe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = robe.lib()
+    names = _declared_symbols()
+    assert set(names) == set(robe.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_struct_layout_matches_header():
+    # uint64 m; uint32 d, Z, use_sign, P; 8 x uint32 coefficients
+    assert ctypes.sizeof(robe.RobeHash) == 8 + 4 * 4 + 8 * 4
+    assert robe.RobeHash.m.offset == 0 and robe.RobeHash.d.offset == 8 and robe.RobeHash.Ah.offset == 24
+
+
+@pytest.mark.parametrize("seed", [0, 1, 7, 2**40 + 3, 2**64 - 1])
+def test_init_hash_draws_the_same_coefficients_as_the_oracle(seed):
+    h = robe.robe_init_hash(seed, 25_000_000, 128, 32, 1)
+    o = oracle.init_hash(seed, 25_000_000, 128, 32, 1)
+    assert tuple(h.coef) == o.coef
+    assert (h.m, h.d, h.Z, h.use_sign, h.P) == (o.m, o.d, o.Z, 1, o.P)
+
+
+@pytest.mark.parametrize("m,d,Z", [(0, 16, 4), (2**31, 16, 4), (100, 16, 5), (100, 0, 1), (100, 16, 0), (8, 16, 16)])
+def test_init_hash_rejects_bad_shapes(m, d, Z):
+    with pytest.raises(robe.RobeError) as ei:
+        robe.robe_init_hash(0, m, d, Z, 0)
+    assert ei.value.code == robe.ROBE_EINVAL
+
+
+def test_entry_points_reject_bad_arguments_without_a_gpu():
+    L = robe.lib()
+    h = robe.robe_init_hash(1, 1000, 16, 4, 0)
+    ref = ctypes.byref(h)
+    fake = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    EINVAL = robe.ROBE_EINVAL
+    # null hash
+    assert L.robe_forward(None, fake, fake, None, 4, 2, 2, fake, None) == EINVAL
+    assert b"hash" in L.robe_last_error()
+    # negative batch, bad feature count, single-hot size mismatch
+    assert L.robe_forward(ref, fake, fake, None, 4, -1, 2, fake, None) == EINVAL
+    assert L.robe_forward(ref, fake, fake, None, 4, 2, 0, fake, None) == EINVAL
+    assert L.robe_forward(ref, fake, fake, None, 5, 2, 2, fake, None) == EINVAL
+    # null buffers
+    assert L.robe_forward(ref, None, fake, None, 4, 2, 2, fake, None) == EINVAL
+    assert L.robe_forward(ref, fake, None, None, 4, 2, 2, fake, None) == EINVAL
+    assert L.robe_forward(ref, fake, fake, None, 4, 2, 2, None, None) == EINVAL
+    assert L.robe_backward(ref, None, fake, None, 4, 2, 2, fake, None, 0, None) == EINVAL
+    assert L.robe_backward(ref, fake, fake, None, 4, 2, 2, None, None, 0, None) == EINVAL
+    assert L.robe_adagrad_update(ref, None, fake, fake, 0.01, 1e-8, None) == EINVAL
+    assert L.robe_adagrad_update(ref, fake, fake, fake, 0.01, 0.0, None) == EINVAL
+    assert L.robe_adagrad_update(ref, fake, fake, fake, float("nan"), 1e-8, None) == EINVAL
+    assert L.robe_offsets(ref, None, 3, 2, fake, None, None) == EINVAL
+    assert L.robe_offsets(ref, fake, -3, 2, fake, None, None) == EINVAL
+    # corrupted hash structs
+    for field, val in [("P", 101), ("Ah", 0), ("Bh", 2**31 - 1), ("Dh", 2**31 - 1), ("Z", 3), ("m", 2**31), ("m", 2)]:
+        bad = robe.robe_init_hash(1, 1000, 16, 4, 0)
+        setattr(bad, field, val)
+        assert L.robe_forward(ctypes.byref(bad), fake, fake, None, 4, 2, 2, fake, None) == EINVAL, field
+    # empty problems are no-ops that succeed
+    assert L.robe_forward(ref, None, None, None, 0, 0, 2, None, None) == robe.ROBE_OK
+    assert L.robe_backward(ref, None, None, None, 0, 0, 2, None, None, 0, None) == robe.ROBE_OK
+    assert L.robe_offsets(ref, None, 0, 2, None, None, None) == robe.ROBE_OK
+    assert L.robe_workspace_bytes(ref, 4, 2, 8) >= 0

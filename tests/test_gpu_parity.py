@@ -1,0 +1,271 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Bars (from the workload statement): hash offsets, signs and single-hot forward
+are bit-exact; pooled forward and the atomic backward agree within
+1e-5 * S + tiny, where S is the sum of |term| over the terms of that output
+element (a backward-error bound: plain relative error is ill-posed where
+terms cancel); Adagrad on identical inputs agrees within 1e-6 of the
+magnitudes involved.  Integer-valued gradients make float32 sums exact in any
+order, which gives a bit-exact backward test as well.
+"""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+import paper_2108_02191_amd as robe
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+THREADS = max(1, min(16, os.cpu_count() or 1))
+TINY = 1e-30
+
+
+def to_dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def both_hashes(seed, m, d, Z, sign):
+    h = robe.robe_init_hash(seed, m, d, Z, sign)
+    H = oracle.init_hash(seed, m, d, Z, sign)
+    assert tuple(h.coef) == H.coef
+    return h, H
+
+
+def bits_equal(a, b):
+    a = np.ascontiguousarray(a, dtype=np.float32).ravel().view(np.int32)
+    b = np.ascontiguousarray(b, dtype=np.float32).ravel().view(np.int32)
+    return np.array_equal(a, b)
+
+
+def random_bags(rng, rows, card, mean, long_bag=0):
+    sizes = rng.poisson(mean, size=rows).astype(np.int64)
+    sizes[0] = 0
+    if rows > 3:
+        sizes[rows // 2] = 0
+        sizes[3] = long_bag or sizes[3]
+    off = np.zeros(rows + 1, dtype=np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ids = rng.integers(0, card, size=int(off[-1]), dtype=np.int64)
+    return ids, off
+
+
+# (m, d, Z): every lane layout (vector width 4/2/1, consecutive and strided,
+# the shape-generic kernel), arrays small enough that blocks wrap, Z = m, Z = 1, Z = d.
+SHAPES = [
+    (2**20, 16, 4), (1_000_003, 128, 32), (999_983, 128, 8), (500_000, 128, 128), (300_007, 128, 1),
+    (37, 16, 8), (16, 16, 16), (64, 64, 64), (101, 8, 2), (50, 4, 1), (1000, 6, 2),
+    (70_001, 96, 32), (4099, 12, 3), (9973, 256, 32), (100_000, 512, 128), (5, 5, 5), (1, 1, 1), (2**31 - 1, 32, 16),
+]
+
+
+@pytest.mark.parametrize("m,d,Z", SHAPES)
+def test_offsets_and_signs_are_bit_exact(m, d, Z):
+    h, H = both_hashes(m + d, m, d, Z, 1)
+    rng = np.random.default_rng(m)
+    F = 26
+    ids = np.concatenate([
+        rng.integers(0, 4 * 10**7, size=3000, dtype=np.int64),
+        rng.integers(0, 2**63 - 1, size=500, dtype=np.int64),
+        np.array([0, 1, 2**31 - 2, 2**31 - 1, 2**31, 2**32 - 1, 2**32, 2**62, 2**63 - 1, -1, -2, -(2**63)], dtype=np.int64),
+    ])
+    off, sg = robe.robe_offsets(h, to_dev(ids), F, want_signs=True)
+    assert np.array_equal(off.cpu().numpy(), oracle.offsets(H, ids, F))
+    assert np.array_equal(sg.cpu().numpy(), oracle.signs(H, ids, F))
+
+
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,d,Z", SHAPES[:-1])
+def test_single_hot_forward_is_bit_exact(m, d, Z, sign):
+    h, H = both_hashes(11 * m + Z, m, d, Z, sign)
+    B, F = 37, 26                                   # 962 rows: several wavefront tiles and a ragged tail
+    rng = np.random.default_rng(d * 7 + Z)
+    ids = rng.integers(0, 5000, size=(B, F), dtype=np.int64)
+    M = workloads.make_array(m, 3)
+    if m > 8:
+        M[::7] = -0.0                               # signed zeros must survive the copy
+    out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F)
+    assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F, threads=THREADS))
+
+
+def test_single_hot_forward_huge_array_bit_exact():
+    m, d, Z = 2**31 - 1, 32, 16                    # largest legal array: 8 GiB of float32
+    h, H = both_hashes(5, m, d, Z, 1)
+    B, F = 64, 26
+    ids = np.random.default_rng(0).integers(0, 2**40, size=(B, F), dtype=np.int64)
+    M = torch.empty(m, dtype=torch.float32, device=DEV)
+    M.copy_(torch.arange(m, device=DEV, dtype=torch.int32).bitwise_and_(0xFFFFF).to(torch.float32))
+    out = robe.robe_forward(h, M, to_dev(ids), None, B, F).cpu().numpy()
+    # oracle on the positions only: value at slot j is (j & 0xFFFFF)
+    off = oracle.offsets(H, ids, F)
+    sg = oracle.signs(H, ids, F)
+    i = np.arange(d)
+    pos = (off[:, i // Z] + (i % Z)[None, :]) % m
+    want = (pos & 0xFFFFF).astype(np.float32) * sg
+    assert bits_equal(out.reshape(-1, d), want)
+    del M
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,d,Z", SHAPES[:-1])
+def test_bag_forward_within_tolerance(m, d, Z, sign):
+    h, H = both_hashes(13 * m + Z, m, d, Z, sign)
+    B, F = 19, 26
+    rng = np.random.default_rng(d + Z)
+    ids, off = random_bags(rng, B * F, 3000, 6.0, long_bag=333)
+    M = workloads.make_array(m, 4)
+    out = robe.robe_forward(h, to_dev(M), to_dev(ids), to_dev(off), B, F).cpu().numpy()
+    want = oracle.forward(H, M, ids, off, B, F, threads=THREADS)
+    H_abs = oracle.Hash(H.m, H.d, H.Z, 0, H.P, H.coef)
+    S = oracle.forward(H_abs, np.abs(M), ids, off, B, F, threads=THREADS).astype(np.float64)
+    err = np.abs(out.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= 1e-5 * S + TINY), float((err / (S + TINY)).max())
+    empty = np.diff(off) == 0
+    assert empty.any()
+    flat = out.reshape(B * F, d)
+    assert not flat[empty].any() and not np.signbit(flat[empty]).any()
+
+
+def test_bag_of_one_token_equals_single_hot_bitwise():
+    w = workloads.get("tiny")
+    h, H = both_hashes(3, 100_003, 128, 32, 1)
+    B, F = 50, w.n_features
+    ids = np.random.default_rng(1).integers(0, 10**6, size=(B, F), dtype=np.int64)
+    M = to_dev(workloads.make_array(100_003, 1))
+    single = robe.robe_forward(h, M, to_dev(ids), None, B, F)
+    bags = robe.robe_forward(h, M, to_dev(ids.ravel()), to_dev(np.arange(B * F + 1, dtype=np.int64)), B, F)
+    # a bag sum starts from +0.0, so only a -0.0 could differ; the array has none
+    assert bits_equal(single.cpu().numpy(), bags.cpu().numpy())
+
+
+def check_backward(h, H, G, ids, off, B, F):
+    ga = torch.zeros(H.m, dtype=torch.float32, device=DEV)
+    robe.robe_backward(h, to_dev(G), to_dev(ids), to_dev(off), B, F, ga)
+    got = ga.cpu().numpy().astype(np.float64)
+    want, S = oracle.backward(H, G, ids, off, B, F, threads=1)
+    err = np.abs(got - want)
+    assert np.all(err <= 1e-5 * S + TINY), float((err / (S + TINY)).max())
+    assert np.all(got[S == 0] == 0)                  # untouched slots stay zero
+    return got, want
+
+
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,d,Z", SHAPES[:-1])
+def test_backward_single_hot_and_bags(m, d, Z, sign):
+    h, H = both_hashes(17 * m + Z, m, d, Z, sign)
+    B, F = 23, 26
+    rng = np.random.default_rng(d * 3 + Z)
+    G = rng.standard_normal((B, F, d)).astype(np.float32)
+    ids = rng.integers(0, 40, size=(B, F), dtype=np.int64)     # few tokens: heavy collisions
+    check_backward(h, H, G, ids, None, B, F)
+    idsb, off = random_bags(rng, B * F, 200, 5.0, long_bag=150)
+    check_backward(h, H, G, idsb, off, B, F)
+    # small-integer gradients: float32 sums are exact in any order -> bit-exact scatter
+    Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+    got, want = check_backward(h, H, Gi, idsb, off, B, F)
+    assert np.array_equal(got, want)
+
+
+def test_backward_accumulates_onto_existing_values():
+    h, H = both_hashes(2, 50_021, 16, 4, 0)
+    B, F = 8, 26
+    rng = np.random.default_rng(0)
+    ids = rng.integers(0, 1000, size=(B, F), dtype=np.int64)
+    G = rng.integers(-2, 3, size=(B, F, 16)).astype(np.float32)
+    ga = torch.full((H.m,), 5.0, dtype=torch.float32, device=DEV)
+    robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga)
+    robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga)
+    want, _ = oracle.backward(H, G, ids, None, B, F)
+    assert np.array_equal(ga.cpu().numpy().astype(np.float64), 5.0 + 2 * want)
+
+
+@pytest.mark.parametrize("m,shift", [(4096, 0), (4099, 0), (4099, 1), (3, 0), (1, 0), (1_000_001, 3)])
+def test_adagrad_matches_oracle_and_leaves_untouched_slots_alone(m, shift):
+    rng = np.random.default_rng(m + shift)
+    h = robe.robe_init_hash(0, m, 1, 1, 0)
+    M0 = rng.standard_normal(m).astype(np.float32)
+    s0 = (rng.random(m).astype(np.float32)) * (rng.random(m) < 0.7)
+    g0 = rng.standard_normal(m).astype(np.float32) * (rng.random(m) < 0.6)
+    # `shift` floats of padding in front put the buffers off 16-byte alignment (scalar kernel)
+    def dev(a):
+        buf = torch.zeros(m + shift, dtype=torch.float32, device=DEV)
+        view = buf[shift:]
+        view.copy_(torch.from_numpy(a))
+        return view
+    M, s, g = dev(M0), dev(s0), dev(g0)
+    robe.robe_adagrad_update(h, M, s, g, 0.01, 1e-8)
+    Mo, so, go = M0.copy(), s0.copy(), g0.copy()
+    oracle.adagrad(Mo, so, go, 0.01, 1e-8)
+    Mg, sg = M.cpu().numpy(), s.cpu().numpy()
+    assert not g.cpu().numpy().any()
+    untouched = g0 == 0
+    assert bits_equal(Mg[untouched], M0[untouched]) and bits_equal(sg[untouched], s0[untouched])
+    step = np.abs(Mo.astype(np.float64) - M0)
+    assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(M0) + step) + TINY)
+    assert np.all(np.abs(sg.astype(np.float64) - so) <= 1e-6 * np.abs(so) + TINY)
+    assert untouched.all() or not bits_equal(Mg, M0)
+
+
+@pytest.mark.parametrize("env,val", [("ROBE_TUNE_FWD", "4,1"), ("ROBE_TUNE_FWD", "2,1"), ("ROBE_TUNE_FWD", "1,1"),
+                                     ("ROBE_TUNE_FWD", "4,0"), ("ROBE_TUNE_FWD", "2,0"), ("ROBE_TUNE_FWD", "0,0"),
+                                     ("ROBE_TUNE_BWD", "4,1"), ("ROBE_TUNE_BWD", "2,1"), ("ROBE_TUNE_BWD", "4,0"),
+                                     ("ROBE_TUNE_BWD", "2,0"), ("ROBE_TUNE_BWD", "0,0"), ("ROBE_TUNE_TL", "64"),
+                                     ("ROBE_TUNE_TL", "8")])
+def test_every_lane_layout_gives_the_same_result(env, val, monkeypatch):
+    # the library reads the override at call time; d = 64 makes every (V, layout) legal
+    monkeypatch.setenv(env, val)
+    m, d, Z, B, F = 60_013, 64, 16, 41, 26
+    for sign in (0, 1):
+        h, H = both_hashes(99, m, d, Z, sign)
+        rng = np.random.default_rng(5)
+        ids = rng.integers(0, 3000, size=(B, F), dtype=np.int64)
+        M = workloads.make_array(m, 9)
+        out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F)
+        assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F, threads=THREADS))
+        idsb, off = random_bags(rng, B * F, 3000, 7.0, long_bag=100)
+        outb = robe.robe_forward(h, to_dev(M), to_dev(idsb), to_dev(off), B, F).cpu().numpy()
+        np.testing.assert_allclose(outb, oracle.forward(H, M, idsb, off, B, F, threads=THREADS), rtol=0, atol=2e-6)
+        Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+        for (i_, o_) in ((ids, None), (idsb, off)):
+            ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+            robe.robe_backward(h, to_dev(Gi), to_dev(i_), to_dev(o_), B, F, ga)
+            want, _ = oracle.backward(H, Gi, i_, o_, B, F)
+            assert np.array_equal(ga.cpu().numpy().astype(np.float64), want)
+
+
+def test_malformed_csr_is_clamped_not_followed():
+    # every bag's bounds are clamped to [0, n_indices] on their own and a negative length becomes empty
+    h, H = both_hashes(1, 10_007, 16, 4, 0)
+    B, F = 2, 2
+    ids = np.arange(10, dtype=np.int64)
+    bad = np.array([0, 3, 50, 7, 10], dtype=np.int64)           # bags: [0,3) [3,50) [50,7) [7,10)
+    same_ids = np.concatenate([ids[0:3], ids[3:10], ids[7:10]])  # ...which clamp to [0,3) [3,10) [] [7,10)
+    same_off = np.array([0, 3, 10, 10, 13], dtype=np.int64)
+    M = workloads.make_array(10_007, 0)
+    out = robe.robe_forward(h, to_dev(M), to_dev(ids), to_dev(bad), B, F).cpu().numpy()
+    want = oracle.forward(H, M, same_ids, same_off, B, F)
+    np.testing.assert_allclose(out, want, rtol=0, atol=1e-7)
+
+
+def test_runs_on_a_side_stream_and_reports_bad_sizes():
+    h, H = both_hashes(4, 20_011, 16, 4, 1)
+    B, F = 16, 26
+    ids = np.random.default_rng(2).integers(0, 1000, size=(B, F), dtype=np.int64)
+    M = workloads.make_array(20_011, 0)
+    Md, idd = to_dev(M), to_dev(ids)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out = robe.robe_forward(h, Md, idd, None, B, F)
+    s.synchronize()
+    assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F))
+    rc = robe.lib().robe_forward(ctypes.byref(h), Md.data_ptr(), idd.data_ptr(), None,
+                                 B * F + 1, B, F, out.data_ptr(), None)
+    assert rc == robe.ROBE_EINVAL and b"n_indices" in robe.lib().robe_last_error()
