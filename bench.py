@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the ROBE-Z hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic batch that is
+already resident in HBM: forward gather (+ bag-sum), backward scatter-add and
+the Adagrad update, as far as the workload has those phases.  The default
+workload is the beyond-LLC multi-hot configuration (1 GB array, d = 128,
+Z = 32), the one the target statement is quoted on.
+
+Prints ONE JSON line.  `value` is token lookups per second over whole steps.
+`phases` gives forward-only, forward+backward and whole-step rates from
+per-kernel HIP-event times taken inside the same timed region; `roofline`
+describes the kernel that takes the most time; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload on this machine's host
+cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="multihot",
+                    help="multihot | training | inference | sweep_z{1,8,32,128} | tiny")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0: as defined)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
+    ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(w, rows, tokens, touched):
+    """Bytes the method itself must move per launch (d floats per vector, 8-byte ids)."""
+    vec = 4 * w.d
+    bags = w.bag_mean is not None
+    fwd = tokens * (vec + 8) + rows * vec + (rows + 1) * 8 * bags
+    bwd = rows * vec + tokens * (2 * vec + 8) + (rows + 1) * 8 * bags
+    ada = touched * 24
+    return {"fwd": fwd, "bwd": bwd, "adagrad": ada}
+
+
+def cpu_baseline(w, M, ids, off, G, target_s):
+    """The oracle, as it stands, on a bounded sample: the first `bs` samples of the batch."""
+    import numpy as np
+    import oracle
+    H = oracle.init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
+    threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
+    F = w.n_features
+
+    def sub(bs):
+        rows = bs * F
+        if off is None:
+            return ids[:bs], None, G[:bs], rows
+        o = off[:rows + 1]
+        return ids[:int(o[-1])], o, G[:bs], int(o[-1])
+
+    def run(bs):
+        i_, o_, g_, ntok = sub(bs)
+        t0 = time.perf_counter()
+        oracle.forward(H, M, i_, o_, bs, F, threads=threads)
+        t1 = time.perf_counter()
+        tb = 0.0
+        if "bwd" in w.phases:
+            oracle.backward(H, g_, i_, o_, bs, F, threads=threads, want_abs=False)
+            tb = time.perf_counter() - t1
+        return ntok, t1 - t0, tb
+
+    probe = min(w.batch, 32)
+    ntok, tf, tb = run(probe)
+    per_sample = max(tf, tb) / probe
+    bs = int(max(probe, min(w.batch, target_s / max(per_sample, 1e-9))))
+    ntok, tf, tb = run(bs)
+    ta = 0.0
+    if "adagrad" in w.phases:
+        g = np.zeros(w.m, dtype=np.float32)
+        g[::3] = 1.0
+        Mc, s = M.copy(), np.zeros(w.m, dtype=np.float32)
+        t0 = time.perf_counter()
+        oracle.adagrad(Mc, s, g, w.lr, w.eps, threads=threads)
+        ta = time.perf_counter() - t0
+    return {"sample_tokens": ntok, "sample_batch": bs, "t_fwd": tf, "t_bwd": tb, "t_adagrad_dense_full_m": ta,
+            "threads": threads}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU only (got --gpus {args.gpus}): the ROBE-Z path here has no "
+              "multi-GPU part; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    import paper_2108_02191_amd as robe
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    robe.lib()  # fail loudly if the HIP library is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w = workloads.get(args.workload)
+    if args.batch:
+        w = w.scaled(batch=args.batch)
+    B, F = w.batch, w.n_features
+    rows = B * F
+    do_bwd = "bwd" in w.phases
+    do_ada = "adagrad" in w.phases
+
+    t_gen = time.perf_counter()
+    M = workloads.make_array(w.m, 0)
+    batches = [workloads.make_indices(w, 1 + k) for k in range(max(1, args.id_batches))]
+    G = workloads.make_grad_out(w, 2)
+    t_gen = time.perf_counter() - t_gen
+    tokens = [int(i.size) for i, _ in batches]
+
+    h = robe.robe_init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
+    Md = torch.from_numpy(M).to(dev)
+    dev_batches = [(torch.from_numpy(i).to(dev), None if o is None else torch.from_numpy(o).to(dev)) for i, o in batches]
+    Gd = torch.from_numpy(G).to(dev)
+    out = torch.empty((B, F, w.d), dtype=torch.float32, device=dev)
+    ga = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_bwd else None
+    st = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_ada else None
+    ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n) for n in tokens) if do_bwd else 0
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev) if ws_bytes else None
+
+    stream = torch.cuda.current_stream()
+
+    def step(k, ev=None):
+        idd, offd = dev_batches[k % len(dev_batches)]
+        if ev:
+            ev[0].record(stream)
+        robe.robe_forward(h, Md, idd, offd, B, F, out=out)
+        if ev:
+            ev[1].record(stream)
+        if do_bwd:
+            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
+            if ev:
+                ev[2].record(stream)
+            if do_ada:
+                robe.robe_adagrad_update(h, Md, st, ga, w.lr, w.eps)
+            else:
+                ga.zero_()          # a training loop clears the gradient it has consumed
+            if ev:
+                ev[3].record(stream)
+
+    # touched slots per step (for the Adagrad algorithmic bytes): one untimed backward
+    touched = 0
+    if do_bwd:
+        idd, offd = dev_batches[0]
+        robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
+        touched = int((ga != 0).sum().item())
+        ga.zero_()
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k, events[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    k_ms = {"fwd": [], "bwd": [], "adagrad": []}
+    for ev in events:
+        k_ms["fwd"].append(ev[0].elapsed_time(ev[1]))
+        if do_bwd:
+            k_ms["bwd"].append(ev[1].elapsed_time(ev[2]))
+            if do_ada:
+                k_ms["adagrad"].append(ev[2].elapsed_time(ev[3]))
+    avg = {k: (sum(v) / len(v) if v else 0.0) for k, v in k_ms.items()}
+    tok = sum(tokens[k % len(tokens)] for k in range(args.steps)) / args.steps
+    alg = algorithmic_bytes(w, rows, tok, touched)
+
+    def rate(ms):
+        return tok / (ms * 1e-3) if ms > 0 else None
+
+    kernels = {}
+    for name in ("fwd", "bwd", "adagrad"):
+        if avg[name] > 0:
+            gbs = alg[name] / (avg[name] * 1e-3) / 1e9
+            kernels[name] = {"ms": round(avg[name], 4), "algorithmic_GB": round(alg[name] / 1e9, 4),
+                             "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    dominant = max(kernels, key=lambda n: kernels[n]["ms"])
+    phases = {"fwd": {"ms": round(avg["fwd"], 4), "lookups_per_s": rate(avg["fwd"])}}
+    if do_bwd:
+        phases["fwd_bwd"] = {"ms": round(avg["fwd"] + avg["bwd"], 4), "lookups_per_s": rate(avg["fwd"] + avg["bwd"])}
+    if do_ada:
+        t_all = avg["fwd"] + avg["bwd"] + avg["adagrad"]
+        phases["fwd_bwd_adagrad"] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all)}
+    total_alg = sum(alg[n] for n in kernels)
+    result = {
+        "metric": "ROBE lookups/sec, whole step (fwd%s%s), d=%d, Z=%d" % (
+            "+bwd" if do_bwd else "", "+Adagrad" if do_ada else "", w.d, w.Z),
+        "value": tok / (ms_per_step * 1e-3),
+        "unit": "lookups/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "m": w.m, "array_bytes": 4 * w.m, "d": w.d, "Z": w.Z, "batch": B,
+                   "n_features": F, "rows": rows, "tokens_per_step": tok, "bag_mean": w.bag_mean,
+                   "ids": f"{w.id_dist}({w.zipf_alpha})" if w.id_dist == "zipf" else w.id_dist,
+                   "use_sign": w.use_sign, "phases": w.phases, "id_batches": len(batches),
+                   "touched_slots": touched},
+        "effective_GBps_whole_step": total_alg / (ms_per_step * 1e-3) / 1e9,
+        "effective_frac_of_hbm_peak": total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "phases": phases,
+        "kernels": kernels,
+        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": kernels[dominant]["achieved_GBps"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"],
+                     "traffic": None},
+        "input_generation_s": round(t_gen, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        idsh, offh = batches[0]
+        cb = cpu_baseline(w, M, idsh, offh, G, args.cpu_seconds)
+        scale = tok / max(cb["sample_tokens"], 1)
+        t_full = (cb["t_fwd"] + cb["t_bwd"]) * scale + cb["t_adagrad_dense_full_m"]
+        result["cpu_baseline"] = {
+            "value": tok / t_full, "unit": "lookups/s", "cores": cb["threads"], "kind": "oracle",
+            "sample": ("first %d of %d batch samples (%d tokens): oracle fwd %.2f s%s, scaled by tokens; "
+                       "%s") % (cb["sample_batch"], B, cb["sample_tokens"], cb["t_fwd"],
+                                (", bwd %.2f s" % cb["t_bwd"]) if do_bwd else "",
+                                ("dense Adagrad over all m slots %.2f s, unscaled" % cb["t_adagrad_dense_full_m"])
+                                if do_ada else "no optimizer phase"),
+            "fwd_lookups_per_s": cb["sample_tokens"] / cb["t_fwd"] if cb["t_fwd"] > 0 else None,
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
