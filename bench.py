@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
     ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
+    ap.add_argument("--copy-calib-mb", type=int, default=0,
+                    help="before the warm-up, run one plain device copy of this many MiB: a dispatch of known "
+                         "size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters in a --pmc run")
     return ap.parse_args()
 
 
@@ -165,6 +168,15 @@ def main():
         robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
         touched = int((ga != 0).sum().item())
         ga.zero_()
+
+    if args.copy_calib_mb > 0:
+        n = args.copy_calib_mb * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)              # reads and writes copy_calib_mb MiB each
+        torch.cuda.synchronize()
+        del src, dst
 
     for k in range(args.warmup):
         step(k)
