@@ -10,6 +10,9 @@
 
 #include "../../include/robe.h"
 #include "robe_kernels.h"
+#include <rocprim/device/device_radix_sort.hpp>
+
+#include "robe_backward_dedup.h"
 
 namespace {
 
@@ -193,6 +196,128 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
     return check_launch(BWD ? "backward" : "forward");
 }
 
+
+// ---------------------------------------------------------------------------
+// Backward with duplicate tokens combined: plan (shared by robe_workspace_bytes
+// and robe_backward) and launch.
+// ---------------------------------------------------------------------------
+struct BwdPlan {
+    bool dedup;
+    Layout lay;
+    uint32_t key_bits;   // most significant key bits the sort looks at
+    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_tok_bag, off_temp, temp_bytes, bytes;
+};
+
+int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Decide between the direct scatter and the combine-duplicates one, and lay out the workspace.
+// ROBE_TUNE_BWD_MODE = direct | dedup overrides the size heuristic (not the hard limits).
+BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, bool bags, const void *grad_out)
+{
+    BwdPlan pl;
+    memset(&pl, 0, sizeof(pl));
+    const char *mode = getenv("ROBE_TUNE_BWD_MODE");
+    if (mode && strcmp(mode, "direct") == 0) return pl;
+    const bool forced = mode && strcmp(mode, "dedup") == 0;
+    // 32-bit positions and row numbers
+    if (rows < 1 || n_indices < 1 || rows >= 0x7FFFFFFFll || n_indices >= 0x7FFFFFFFll) return pl;
+    pl.lay = pick_layout(h, true, grad_out);
+    if (pl.lay.V == 0 || pl.lay.consec) return pl;   // shapes only the generic kernel handles
+    // sorting costs about 0.1 ms plus 45 ns per thousand tokens: not worth it for small scatters
+    if (!forced && (uint64_t)n_indices * h->d < (1ull << 25)) return pl;
+    pl.key_bits = (uint32_t)env_int("ROBE_TUNE_KEY_BITS", 31);
+    if (pl.key_bits < 8 || pl.key_bits > 31) pl.key_bits = 31;
+
+    const size_t n = (size_t)n_indices;
+    size_t temp = 0;
+    uint32_t *nul = nullptr;
+    if (rocprim::radix_sort_pairs(nullptr, temp, nul, nul, nul, nul, n, 31 - pl.key_bits, 31) != hipSuccess) {
+        (void)hipGetLastError();
+        return pl;                                    // no device to ask: the caller cannot run the scatter either
+    }
+    pl.dedup = true;
+    size_t off = 0;
+    pl.off_keys_in = off;  off = align_up(off + n * 4, 256);
+    pl.off_keys_out = off; off = align_up(off + n * 4, 256);
+    pl.off_vals_in = off;  off = align_up(off + n * 4, 256);
+    pl.off_vals_out = off; off = align_up(off + n * 4, 256);
+    pl.off_tok_bag = off;  if (bags) off = align_up(off + n * 4, 256);
+    pl.off_temp = off;     off = align_up(off + temp, 256);
+    pl.temp_bytes = temp;
+    pl.bytes = off;
+    return pl;
+}
+
+int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *grad_out, const int64_t *indices,
+                          const int64_t *offsets, int64_t n_indices, int64_t rows, uint32_t F,
+                          float *grad_array, void *workspace, hipStream_t stream)
+{
+    const robe::Params p = to_params(h);
+    char *ws = static_cast<char *>(workspace);
+    uint32_t *keys_in = reinterpret_cast<uint32_t *>(ws + pl.off_keys_in);
+    uint32_t *keys_out = reinterpret_cast<uint32_t *>(ws + pl.off_keys_out);
+    uint32_t *vals_in = reinterpret_cast<uint32_t *>(ws + pl.off_vals_in);
+    uint32_t *vals_out = reinterpret_cast<uint32_t *>(ws + pl.off_vals_out);
+    uint32_t *tok_bag = reinterpret_cast<uint32_t *>(ws + pl.off_tok_bag);
+    const bool bags = offsets != nullptr;
+    const bool sign = h->use_sign != 0;
+    const uint32_t n = (uint32_t)n_indices, urows = (uint32_t)rows;
+
+    // S1: keys.  With a well-formed CSR every position is written; the fill keeps stray positions harmless.
+    if (bags) {
+        robe::fill_pairs_kernel<<<dim3(2048), dim3(256), 0, stream>>>(keys_in, vals_in, n);
+        if (int rc = check_launch("backward (clear keys)")) return rc;
+    }
+    uint32_t g_shift = 0;
+    if (bags) {
+        const uint64_t avg = ((uint64_t)n_indices + rows - 1) / rows;
+        while (g_shift < 6 && (1ull << g_shift) < avg) ++g_shift;
+    }
+    const uint64_t key_threads = (uint64_t)rows << g_shift;
+    uint64_t key_blocks = (key_threads + 255) / 256;
+    if (key_blocks > 65536) key_blocks = 65536;
+    if (bags)
+        robe::token_keys_kernel<true><<<dim3((uint32_t)key_blocks), dim3(256), 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    else
+        robe::token_keys_kernel<false><<<dim3((uint32_t)key_blocks), dim3(256), 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    if (int rc = check_launch("backward (keys)")) return rc;
+
+    // S2: sort (key, position) pairs by the top key_bits bits of the 31-bit key
+    size_t temp = pl.temp_bytes;
+    hipError_t st = rocprim::radix_sort_pairs(ws + pl.off_temp, temp, keys_in, keys_out, vals_in, vals_out,
+                                              (size_t)n, 31 - pl.key_bits, 31, stream);
+    if (st != hipSuccess) return fail(ROBE_EHIP, "backward (sort): %s", hipGetErrorString(st));
+
+    // S3: combine runs and scatter
+    robe::Geom q;
+    q.F = F;
+    q.G = pl.lay.G;
+    q.g_shift = log2u(pl.lay.G);
+    q.TL = 0;
+    const uint64_t blocks = ((uint64_t)n + robe::kBlock - 1) / robe::kBlock;   // one lane per sorted position
+    const dim3 grid((uint32_t)blocks), block(robe::kBlock);
+#define ROBE_COMBINE(V_)                                                                                              \
+    do {                                                                                                              \
+        if (sign && bags) robe::combine_scatter_kernel<V_, true, true><<<grid, block, 0, stream>>>(p, q, grad_out, indices, keys_out, vals_out, tok_bag, urows, n, grad_array);   \
+        else if (sign) robe::combine_scatter_kernel<V_, true, false><<<grid, block, 0, stream>>>(p, q, grad_out, indices, keys_out, vals_out, tok_bag, urows, n, grad_array);    \
+        else if (bags) robe::combine_scatter_kernel<V_, false, true><<<grid, block, 0, stream>>>(p, q, grad_out, indices, keys_out, vals_out, tok_bag, urows, n, grad_array);    \
+        else robe::combine_scatter_kernel<V_, false, false><<<grid, block, 0, stream>>>(p, q, grad_out, indices, keys_out, vals_out, tok_bag, urows, n, grad_array);             \
+    } while (0)
+    switch (pl.lay.V) {
+        case 1: ROBE_COMBINE(1); break;
+        case 2: ROBE_COMBINE(2); break;
+        default: ROBE_COMBINE(4); break;
+    }
+#undef ROBE_COMBINE
+    return check_launch("backward (combine and scatter)");
+}
+
 int check_rows(const robe_hash_t *h, const int64_t *indices, const int64_t *offsets, int64_t n_indices,
                int64_t batch, int32_t n_features, int64_t *rows_out)
 {
@@ -276,8 +401,11 @@ int robe_forward(const robe_hash_t *hash, const float *array, const int64_t *ind
 
 size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices)
 {
-    (void)hash; (void)batch; (void)n_features; (void)n_indices;
-    return 0;  // the scatter works in place on grad_array
+    if (hash == nullptr || check_hash(hash) != ROBE_OK || batch < 0 || n_features < 1 || n_indices < 0) return 0;
+    if (batch > (int64_t)0x7FFFFFFFFFFFll / n_features) return 0;
+    // sized for bags and for an aligned grad_out; robe_backward never needs more than this
+    const BwdPlan pl = plan_backward(hash, batch * (int64_t)n_features, n_indices, true, nullptr);
+    return pl.dedup ? pl.bytes : 0;
 }
 
 int robe_backward(const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
@@ -286,13 +414,19 @@ int robe_backward(const robe_hash_t *hash, const float *grad_out, const int64_t 
 {
     int64_t rows = 0;
     if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
-    const size_t need = robe_workspace_bytes(hash, batch, n_features, n_indices);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need))
-        return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    const BwdPlan pl = plan_backward(hash, rows, n_indices, offsets != nullptr, grad_out);
+    if (pl.dedup) {
+        if (workspace == nullptr || workspace_bytes < pl.bytes)
+            return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", pl.bytes, workspace_bytes);
+        if (!aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
+    }
     if (rows == 0) return ROBE_OK;
     if (grad_out == nullptr) return fail(ROBE_EINVAL, "grad_out is NULL");
     if (grad_array == nullptr) return fail(ROBE_EINVAL, "grad_array is NULL");
     if (!aligned(grad_out, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    if (pl.dedup)
+        return launch_dedup_backward(hash, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
+                                      grad_array, workspace, (hipStream_t)stream);
     return launch_rows<true>(hash, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad_array, grad_out, (hipStream_t)stream);
 }
 

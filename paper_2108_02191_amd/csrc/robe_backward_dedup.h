@@ -1,0 +1,152 @@
+// Backward scatter-add (Eq. 3 of the paper) with duplicate tokens combined first.
+//
+// Float atomics on device memory run at a fixed, low rate on this GPU (about one
+// element per clock per memory channel, whatever the footprint; LDS float
+// atomics are no faster), and every token costs d of them.  Recommendation
+// batches repeat their frequent tokens many times, and all copies of a token
+// (same table, same id) hit the same d slots with the same signs.  So:
+//
+//   S1 keys     every token gets the key th = (Bh*x + Ah*e + Dh) mod P - the token
+//               part of its offset hash, equal for equal (e, x) - and its position.
+//   S2 sort     radix sort of (key, position) pairs (rocPRIM device primitive).
+//   S3 combine  a group of G lanes walks G consecutive sorted tokens, adds the
+//               gradient rows of runs of identical tokens in registers, and issues
+//               the d atomics once per run.  Identity is checked on (key, id,
+//               table), so distinct tokens that share a key are merely not merged.
+//               A run longer than a group's stretch is flushed once per stretch,
+//               which also spreads very frequent tokens over many groups.
+//
+// The order of the float additions is not fixed, so results agree with an exact
+// sum to rounding only.
+#pragma once
+#include "robe_kernels.h"
+
+namespace robe {
+
+constexpr uint32_t kNoToken = 0xFFFFFFFFu;
+
+__global__ __launch_bounds__(256) void fill_pairs_kernel(uint32_t *keys, uint32_t *vals, uint32_t n)
+{
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) {
+        keys[i] = 0x7FFFFFFFu;   // sorts last
+        vals[i] = kNoToken;
+    }
+}
+
+// S1.  Bags: a group of G lanes per bag, grid-stride over bags; single-hot: one lane per lookup.
+template <bool BAGS>
+__global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, uint32_t g_shift,
+                                                         const int64_t *__restrict__ indices,
+                                                         const int64_t *__restrict__ offsets,
+                                                         uint32_t rows, uint32_t n_indices,
+                                                         uint32_t *__restrict__ keys, uint32_t *__restrict__ vals,
+                                                         uint32_t *__restrict__ tok_bag)
+{
+    const uint32_t G = 1u << g_shift;
+    const uint32_t lane = threadIdx.x & (G - 1u);
+    const uint64_t groups = ((uint64_t)gridDim.x * 256u) >> g_shift;
+    for (uint64_t bag = ((uint64_t)blockIdx.x * 256u + threadIdx.x) >> g_shift; bag < rows; bag += groups) {
+        int64_t t0 = (int64_t)bag, t1 = (int64_t)bag + 1;
+        if constexpr (BAGS) {
+            t0 = offsets[bag];
+            t1 = offsets[bag + 1];
+            t0 = t0 < 0 ? 0 : (t0 > (int64_t)n_indices ? (int64_t)n_indices : t0);
+            t1 = t1 < t0 ? t0 : (t1 > (int64_t)n_indices ? (int64_t)n_indices : t1);
+        }
+        const uint32_t e = (uint32_t)bag % F;
+        for (int64_t t = t0 + lane; t < t1; t += G) {
+            keys[t] = staged_h(p, indices[t], e);
+            vals[t] = (uint32_t)t;
+            if constexpr (BAGS) tok_bag[t] = (uint32_t)bag;
+        }
+    }
+}
+
+// S3.  Lane layout as in the direct scatter: G lanes per row, lane `grp` owns elements grp + k*G.
+template <int V, bool SIGN, bool BAGS>
+__global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom q,
+                                                                 const float *__restrict__ grad_out,
+                                                                 const int64_t *__restrict__ indices,
+                                                                 const uint32_t *__restrict__ keys,     // sorted
+                                                                 const uint32_t *__restrict__ vals,     // sorted with the keys
+                                                                 const uint32_t *__restrict__ tok_bag,
+                                                                 uint32_t rows, uint32_t n_indices,
+                                                                 float *__restrict__ grad_array)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t grp = lane & (q.G - 1u);
+    const uint32_t base_lane = lane - grp;
+    const uint64_t thread_id = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (thread_id - lane >= n_indices) return;          // the whole wavefront is past the end
+    const uint64_t i0 = thread_id - grp;                // first sorted position of this group's stretch
+
+    // lane l of the group looks at sorted position i0 + l
+    uint32_t my_th = 0, my_tg = 0, my_row = 0, my_e = 0;
+    int64_t my_x = 0;
+    bool my_ok = false;
+    if (i0 + grp < n_indices) {
+        const uint32_t t = vals[i0 + grp];
+        if (t < n_indices) {
+            const uint32_t row = BAGS ? tok_bag[t] : t;
+            if (row < rows) {
+                my_ok = true;
+                my_row = row;
+                my_x = indices[t];
+                my_e = row % q.F;
+                my_th = keys[i0 + grp];
+                if constexpr (SIGN) my_tg = staged_g(p, my_x, my_e);
+            }
+        }
+    }
+    // does this position start a new run?  (first of the stretch, or a different token than the one before)
+    const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
+    const uint32_t p_th = __shfl(my_th, prev), p_e = __shfl(my_e, prev);
+    const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
+    const bool p_ok = __shfl((int)my_ok, prev) != 0;
+    const bool my_head = grp == 0 || !p_ok || p_th != my_th || p_e != my_e ||
+                         p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32);
+
+    Lane<V, false, SIGN> L;
+    L.init(p, q, grp);
+
+    float acc[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+    uint32_t run_th = 0, run_tg = 0;
+    bool open = false;
+
+    for (uint32_t k0 = 0; k0 < q.G; k0 += kUnroll) {     // same trip count for every lane of the wavefront
+        uint32_t row[kUnroll], th[kUnroll], tg[kUnroll];
+        bool ok[kUnroll], head[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
+            ok[u] = (k0 + u < q.G) && __shfl((int)my_ok, from) != 0;
+            row[u] = __shfl(my_row, from);
+            th[u] = __shfl(my_th, from);
+            tg[u] = SIGN ? __shfl(my_tg, from) : 0u;
+            head[u] = __shfl((int)my_head, from) != 0;
+            if (!ok[u]) row[u] = 0;                        // any valid row: its values are discarded
+        }
+        float v[kUnroll][V];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (!ok[u]) continue;
+            if (head[u] && open) {
+                L.scatter(p, grad_array, run_th, run_tg, acc);
+#pragma unroll
+                for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < V; ++k) acc[k] += v[u][k];
+            run_th = th[u];
+            run_tg = tg[u];
+            open = true;
+        }
+    }
+    if (open) L.scatter(p, grad_array, run_th, run_tg, acc);
+}
+
+}  // namespace robe

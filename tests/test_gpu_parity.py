@@ -156,9 +156,12 @@ def check_backward(h, H, G, ids, off, B, F):
     return got, want
 
 
+@pytest.mark.parametrize("mode", ["direct", "dedup"])
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,d,Z", SHAPES[:-1])
-def test_backward_single_hot_and_bags(m, d, Z, sign):
+def test_backward_single_hot_and_bags(m, d, Z, sign, mode, monkeypatch):
+    # both scatter strategies: per-element atomics, and sort-by-destination + LDS accumulation
+    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
     h, H = both_hashes(17 * m + Z, m, d, Z, sign)
     B, F = 23, 26
     rng = np.random.default_rng(d * 3 + Z)
@@ -173,7 +176,9 @@ def test_backward_single_hot_and_bags(m, d, Z, sign):
     assert np.array_equal(got, want)
 
 
-def test_backward_accumulates_onto_existing_values():
+@pytest.mark.parametrize("mode", ["direct", "dedup"])
+def test_backward_accumulates_onto_existing_values(mode, monkeypatch):
+    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
     h, H = both_hashes(2, 50_021, 16, 4, 0)
     B, F = 8, 26
     rng = np.random.default_rng(0)
@@ -184,6 +189,49 @@ def test_backward_accumulates_onto_existing_values():
     robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga)
     want, _ = oracle.backward(H, G, ids, None, B, F)
     assert np.array_equal(ga.cpu().numpy().astype(np.float64), 5.0 + 2 * want)
+
+
+@pytest.mark.parametrize("key_bits", [31, 16, 8])
+@pytest.mark.parametrize("sign", [0, 1])
+def test_dedup_backward_hot_tokens_and_key_collisions(key_bits, sign, monkeypatch):
+    # one token repeated thousands of times (runs far longer than a lane group's stretch), a coarse
+    # sort key so that distinct tokens share keys and interleave, blocks that wrap, unaligned grad_array
+    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", "dedup")
+    monkeypatch.setenv("ROBE_TUNE_KEY_BITS", str(key_bits))
+    m, d, Z, B, F = 100_003, 64, 32, 301, 7
+    h, H = both_hashes(31 + key_bits, m, d, Z, sign)
+    rng = np.random.default_rng(key_bits)
+    ids = rng.integers(0, 5000, size=(B, F), dtype=np.int64)
+    ids[rng.random((B, F)) < 0.6] = 7                            # the hot token
+    Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+    for shift in (0, 1):
+        buf = torch.zeros(m + shift, dtype=torch.float32, device=DEV)
+        ga = buf[shift:]
+        assert robe.robe_workspace_bytes(h, B, F, ids.size) > 0
+        robe.robe_backward(h, to_dev(Gi), to_dev(ids), None, B, F, ga)
+        want, _ = oracle.backward(H, Gi, ids, None, B, F)
+        assert np.array_equal(ga.cpu().numpy().astype(np.float64), want)
+    idsb, off = random_bags(rng, B * F, 30, 9.0, long_bag=5000)
+    G = rng.standard_normal((B, F, d)).astype(np.float32)
+    check_backward(h, H, G, idsb, off, B, F)
+
+
+def test_dedup_backward_needs_its_workspace():
+    w = workloads.get("training").scaled(batch=16384)            # 54 M element updates: above the size where sorting pays
+    h = robe.robe_init_hash(1, w.m, w.d, w.Z, 0)
+    n = w.batch * w.n_features
+    need = robe.robe_workspace_bytes(h, w.batch, w.n_features, n)
+    assert need >= 16 * n                                        # two (key, position) buffers of 4-byte entries
+    ids = torch.zeros((w.batch, w.n_features), dtype=torch.int64, device=DEV)
+    G = torch.zeros((w.batch, w.n_features, w.d), dtype=torch.float32, device=DEV)
+    ga = torch.zeros(w.m, dtype=torch.float32, device=DEV)
+    small = torch.empty(need // 2, dtype=torch.uint8, device=DEV)
+    rc = robe.lib().robe_backward(ctypes.byref(h), G.data_ptr(), ids.data_ptr(), None, n, w.batch, w.n_features,
+                                  ga.data_ptr(), small.data_ptr(), need // 2, None)
+    assert rc == robe.ROBE_EINVAL and b"workspace" in robe.lib().robe_last_error()
+    rc = robe.lib().robe_backward(ctypes.byref(h), G.data_ptr(), ids.data_ptr(), None, n, w.batch, w.n_features,
+                                  ga.data_ptr(), None, 0, None)
+    assert rc == robe.ROBE_EINVAL
 
 
 @pytest.mark.parametrize("m,shift", [(4096, 0), (4099, 0), (4099, 1), (3, 0), (1, 0), (1_000_001, 3)])
