@@ -440,9 +440,9 @@ int robe_adagrad_update(const robe_hash_t *hash, float *array, float *state, flo
     const uint64_t m = hash->m;
     hipStream_t s = (hipStream_t)stream;
     const bool vec = aligned(array, 16) && aligned(state, 16) && aligned(grad_array, 16) && m >= 4;
-    const uint64_t work = vec ? m / 4 : m;
-    uint64_t blocks = (work + robe::kBlock - 1) / robe::kBlock;
-    if (blocks > 16384) blocks = 16384;
+    uint64_t work = vec ? m / 4 : m;   // one thread per vector
+    if (work < 1) work = 1;
+    const uint64_t blocks = (work + robe::kBlock - 1) / robe::kBlock;   // <= 2^23 since m < 2^31
     if (vec)
         robe::adagrad_kernel<4><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, s>>>(array, state, grad_array, m, lr, eps);
     else
