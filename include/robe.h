@@ -33,8 +33,9 @@
  *   - Index conventions are 0-based: table id e = feature column, element
  *     i in [0,d), chunk c = i / Z, position in chunk j = i mod Z.
  *   - Layouts: single-hot ids `indices[batch][n_features]`; bags in (b,f)
- *     row-major order, bag k = b*n_features + f, CSR `offsets[batch*n_features+1]`
- *     with offsets[0] = 0 and offsets[last] = n_indices, `indices[n_indices]`;
+ *     row-major order, bag k = b*n_features + f, CSR `offsets[batch*n_features+1]`,
+ *     non-decreasing with offsets[0] = 0 and offsets[last] = n_indices,
+ *     `indices[n_indices]`;
  *     `out` / `grad_out` are `[batch][n_features][d]` float32, row-major.
  */
 #ifndef ROBE_H
@@ -118,8 +119,11 @@ int robe_forward(const robe_hash_t *hash, const float *array,
                  int64_t batch, int32_t n_features, float *out, void *stream);
 
 /*
- * Bytes of device workspace robe_backward needs for this problem size
- * (0 when none is needed).  Returns 0 on invalid arguments as well.
+ * Bytes of device workspace robe_backward needs for this problem size, for
+ * either kind of input (single-hot or bags); 0 when none is needed (small
+ * problems scatter directly).  Needs the current device (it asks the sort
+ * primitive for its temporary-storage size); returns 0 on invalid arguments
+ * or when no device is present.
  */
 size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices);
 
@@ -129,7 +133,12 @@ size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_fe
  * where every token t of bag k receives row k of grad_out (single-hot: one
  * token per row).  Accumulates onto the caller's grad_array (device float[m]);
  * the order of the float32 additions is not fixed, so results agree with an
- * exact sum only to rounding.
+ * exact sum only to rounding.  Large scatters first combine the gradient rows
+ * of repeated tokens (sort by the token part of the hash, run-wise sums) and
+ * issue the atomics once per run; that path needs the workspace and rows,
+ * n_indices below 2^31 - 1.  With a CSR that is not non-decreasing, bag bounds
+ * are clamped to [0, n_indices] so nothing outside the buffers is touched, but
+ * which tokens such bags hold is unspecified here.
  *   workspace  device buffer of at least robe_workspace_bytes(...) bytes,
  *              256-byte aligned, contents undefined before and after; may be
  *              NULL when that size is 0
