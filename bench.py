@@ -54,6 +54,22 @@ def algorithmic_bytes(w, rows, tokens, touched):
     return {"fwd": fwd, "bwd": bwd, "adagrad": ada}
 
 
+def measured_traffic(workload, kernel):
+    """HBM-side bytes per launch from the committed rocprofv3 counter summary, if there is one.
+
+    profiles/<workload>_step.md carries lines `traffic <kernel> <bytes>` (FETCH_SIZE and WRITE_SIZE
+    of separate --pmc runs of this same script, scaled by the calibration copy)."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_step.md")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic" and parts[1] == kernel:
+                return int(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, M, ids, off, G, target_s):
     """The oracle, as it stands, on a bounded sample: the first `bs` samples of the batch."""
     import numpy as np
@@ -80,7 +96,8 @@ def cpu_baseline(w, M, ids, off, G, target_s):
             tb = time.perf_counter() - t1
         return ntok, t1 - t0, tb
 
-    probe = min(w.batch, 32)
+    # size the sample from a probe of 1/8 of the batch so that each phase takes about target_s seconds
+    probe = max(1, min(w.batch, w.batch // 8))
     ntok, tf, tb = run(probe)
     per_sample = max(tf, tb) / probe
     bs = int(max(probe, min(w.batch, target_s / max(per_sample, 1e-9))))
@@ -219,6 +236,10 @@ def main():
         t_all = avg["fwd"] + avg["bwd"] + avg["adagrad"]
         phases["fwd_bwd_adagrad"] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all)}
     total_alg = sum(alg[n] for n in kernels)
+    # the timed unit of each phase is one entry-point call; backward is several kernels when it sorts
+    entry_names = {"fwd": "robe_forward", "adagrad": "robe_adagrad_update",
+                   "bwd": "robe_backward (" + ("token_keys + radix sort + combine_scatter kernels" if ws_bytes
+                                               else "direct scatter kernel") + ")"}
     result = {
         "metric": "ROBE lookups/sec, whole step (fwd%s%s), d=%d, Z=%d" % (
             "+bwd" if do_bwd else "", "+Adagrad" if do_ada else "", w.d, w.Z),
@@ -237,9 +258,9 @@ def main():
         "effective_frac_of_hbm_peak": total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "phases": phases,
         "kernels": kernels,
-        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": kernels[dominant]["achieved_GBps"],
+        "roofline": {"kernel": entry_names[dominant], "bound": "hbm", "achieved": kernels[dominant]["achieved_GBps"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"],
-                     "traffic": None},
+                     "traffic": measured_traffic(w.name, dominant)},
         "input_generation_s": round(t_gen, 1),
     }
 

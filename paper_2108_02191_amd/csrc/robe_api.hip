@@ -231,7 +231,9 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     if (pl.lay.V == 0 || pl.lay.consec) return pl;   // shapes only the generic kernel handles
     // sorting costs about 0.1 ms plus 45 ns per thousand tokens: not worth it for small scatters
     if (!forced && (uint64_t)n_indices * h->d < (1ull << 25)) return pl;
-    pl.key_bits = (uint32_t)env_int("ROBE_TUNE_KEY_BITS", 31);
+    // Sorting on the top 24 key bits is one radix pass cheaper; tokens that share those bits merely
+    // interleave and are merged less often, which stays rare while there are far fewer tokens than 2^24.
+    pl.key_bits = (uint32_t)env_int("ROBE_TUNE_KEY_BITS", n_indices <= (1ll << 24) ? 24 : 31);
     if (pl.key_bits < 8 || pl.key_bits > 31) pl.key_bits = 31;
 
     const size_t n = (size_t)n_indices;

@@ -24,6 +24,7 @@
 namespace robe {
 
 constexpr uint32_t kNoToken = 0xFFFFFFFFu;
+constexpr int kRowsInFlight = 8;   // gradient rows a lane group loads before it adds them
 
 __global__ __launch_bounds__(256) void fill_pairs_kernel(uint32_t *keys, uint32_t *vals, uint32_t n)
 {
@@ -115,11 +116,11 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
     uint32_t run_th = 0, run_tg = 0;
     bool open = false;
 
-    for (uint32_t k0 = 0; k0 < q.G; k0 += kUnroll) {     // same trip count for every lane of the wavefront
-        uint32_t row[kUnroll], th[kUnroll], tg[kUnroll];
-        bool ok[kUnroll], head[kUnroll];
+    for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsInFlight) {     // same trip count for every lane of the wavefront
+        uint32_t row[kRowsInFlight], th[kRowsInFlight], tg[kRowsInFlight];
+        bool ok[kRowsInFlight], head[kRowsInFlight];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (int u = 0; u < kRowsInFlight; ++u) {
             const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
             ok[u] = (k0 + u < q.G) && __shfl((int)my_ok, from) != 0;
             row[u] = __shfl(my_row, from);
@@ -128,11 +129,11 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
             head[u] = __shfl((int)my_head, from) != 0;
             if (!ok[u]) row[u] = 0;                        // any valid row: its values are discarded
         }
-        float v[kUnroll][V];
+        float v[kRowsInFlight][V];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+        for (int u = 0; u < kRowsInFlight; ++u) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (int u = 0; u < kRowsInFlight; ++u) {
             if (!ok[u]) continue;
             if (head[u] && open) {
                 L.scatter(p, grad_array, run_th, run_tg, acc);
