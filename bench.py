@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--workload", default="multihot",
                     help="multihot | training | inference | sweep_z{1,8,32,128} | tiny")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0: as defined)")
+    ap.add_argument("--m", type=int, default=0, help="override the array length in floats (0: as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
     ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
@@ -136,6 +137,8 @@ def main():
     w = workloads.get(args.workload)
     if args.batch:
         w = w.scaled(batch=args.batch)
+    if args.m:
+        w = w.scaled(m=args.m)
     B, F = w.batch, w.n_features
     rows = B * F
     do_bwd = "bwd" in w.phases

@@ -157,7 +157,8 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
     q.G = lay.G;
     q.g_shift = log2u(lay.G);
     const uint32_t step = 64u / lay.G;
-    q.TL = (step * robe::kUnroll >= 64u) ? 64u : 32u;
+    // one pass of the gather loop per wavefront tile measured best (more, shorter wavefronts)
+    q.TL = step * robe::kUnroll >= 64u ? 64u : step * robe::kUnroll;
     if (const char *s = getenv("ROBE_TUNE_TL")) {
         const int tl = atoi(s);
         if (tl >= (int)step && tl <= 64 && tl % (int)step == 0) q.TL = (uint32_t)tl;

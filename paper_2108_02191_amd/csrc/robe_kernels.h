@@ -32,7 +32,7 @@ struct Geom {
     uint32_t F;        // number of tables (features)
     uint32_t G;        // lanes per row, power of two, <= 64; d = G * V
     uint32_t g_shift;  // log2(G)
-    uint32_t TL;       // rows per wavefront tile (single-hot kernels), multiple of 64/G, <= 64
+    uint32_t TL;       // rows per wavefront tile (single-hot kernels), multiple of 64/G, <= 64 (0: unused)
 };
 
 template <int V>
