@@ -131,6 +131,12 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
     return {0, false, 0};
 }
 
+int env_flag(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
 template <bool BWD>
 int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, const int64_t *offsets,
                 int64_t n_indices, int64_t rows, uint32_t F, float *dst, const void *rows_ptr, hipStream_t stream)
@@ -165,7 +171,19 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
     }
     const int64_t rows_per_wave = bags ? (int64_t)step : (int64_t)q.TL;
     const int64_t waves = (rows + rows_per_wave - 1) / rows_per_wave;
-    const int64_t blocks = (waves + robe::kWavesPerBlock - 1) / robe::kWavesPerBlock;
+    int64_t blocks = (waves + robe::kWavesPerBlock - 1) / robe::kWavesPerBlock;
+    // Walk the rows table by table, one eighth of that order per XCD (see RowWalk), unless the launch
+    // is too small to matter.  ROBE_TUNE_XCD=0 keeps the memory order.
+    q.batch = rows / (int64_t)F;
+    q.bpx = 0;
+    // It pays where array reads dominate the traffic: bags (many blocks read per row written) and
+    // blocks of at most one 64-byte sector (several sectors fetched per sector used).  For single-hot
+    // lookups with larger blocks the row writes dominate and the memory order is slightly faster.
+    const int xcd_mode = env_flag("ROBE_TUNE_XCD", (bags || h->Z * 4 <= 64) ? 1 : 0);   // 2: even for tiny launches
+    if (F >= 2 && ((xcd_mode == 1 && blocks >= 64) || xcd_mode == 2)) {
+        q.bpx = (uint32_t)((blocks + robe::kXcds - 1) / robe::kXcds);
+        blocks = (int64_t)q.bpx * robe::kXcds;
+    }
     if (blocks > 0x7FFFFFFFll) return fail(ROBE_EINVAL, "too many rows for one launch");
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
 
@@ -303,6 +321,8 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     q.G = pl.lay.G;
     q.g_shift = log2u(pl.lay.G);
     q.TL = 0;
+    q.bpx = 0;
+    q.batch = 0;
     const uint64_t blocks = ((uint64_t)n + robe::kBlock - 1) / robe::kBlock;   // one lane per sorted position
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
 #define ROBE_COMBINE(V_)                                                                                              \

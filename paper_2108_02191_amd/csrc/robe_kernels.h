@@ -33,7 +33,60 @@ struct Geom {
     uint32_t G;        // lanes per row, power of two, <= 64; d = G * V
     uint32_t g_shift;  // log2(G)
     uint32_t TL;       // rows per wavefront tile (single-hot kernels), multiple of 64/G, <= 64 (0: unused)
+    uint32_t bpx;      // workgroups per XCD when rows are walked table by table (0: walk rows in memory order)
+    int64_t batch;     // rows = batch * F
 };
+
+// Which rows a wavefront works on.
+//
+// Row k = b*F + f of the [batch][F] layout belongs to table f.  Workgroups are handed to the 8 XCDs
+// round-robin, and every XCD has its own L2.  Walking the rows in memory order shows every L2 the
+// frequent tokens of all F tables; walking them table by table (position q = f*batch + b) and giving
+// XCD x the x-th eighth of that order shows each L2 the frequent tokens of about F/8 tables only, so
+// far more of them stay resident.  With bpx == 0 the order is the memory order.
+constexpr uint32_t kXcds = 8;
+
+struct RowWalk {
+    int64_t q0;    // first position of this wavefront in walk order
+    int64_t b0;    // its sample
+    uint32_t f0;   // its table
+};
+
+__device__ __forceinline__ bool start_walk(const Geom &q, int64_t rows, int64_t rows_per_wave, RowWalk &w)
+{
+    uint32_t block = blockIdx.x;
+    if (q.bpx) {
+        const uint32_t x = block % kXcds, j = block / kXcds;
+        block = x * q.bpx + j;
+    }
+    w.q0 = ((int64_t)block * kWavesPerBlock + (threadIdx.x >> 6)) * rows_per_wave;
+    if (w.q0 >= rows) return false;
+    if (q.bpx) {
+        w.f0 = (uint32_t)(w.q0 / q.batch);
+        w.b0 = w.q0 - (int64_t)w.f0 * q.batch;
+    } else {
+        w.b0 = w.q0 / (int64_t)q.F;
+        w.f0 = (uint32_t)(w.q0 - w.b0 * (int64_t)q.F);
+    }
+    return true;
+}
+
+// Row index k and table f of the position `ahead` steps after the wavefront's first one (ahead < 64).
+__device__ __forceinline__ int64_t walk_row(const Geom &q, const RowWalk &w, uint32_t ahead, uint32_t &f)
+{
+    if (q.bpx) {
+        int64_t b = w.b0 + ahead;
+        f = w.f0;
+        while (b >= q.batch) {   // crosses into the next table(s); at most `ahead` rounds
+            b -= q.batch;
+            ++f;
+        }
+        return b * (int64_t)q.F + f;
+    }
+    const uint32_t t = w.f0 + ahead;  // < F + 64
+    f = t % q.F;
+    return w.q0 + ahead;
+}
 
 template <int V>
 struct Vec {
@@ -166,21 +219,18 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
                                                             float *__restrict__ dst)         // fwd: out; bwd: grad_array
 {
     const uint32_t lane = threadIdx.x & 63u;
-    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    const int64_t row0 = wave * (int64_t)q.TL;
-    if (row0 >= rows) return;  // uniform over the wavefront
-    const uint32_t n = (uint32_t)((rows - row0) < (int64_t)q.TL ? (rows - row0) : (int64_t)q.TL);
+    RowWalk w;
+    if (!start_walk(q, rows, (int64_t)q.TL, w)) return;  // uniform over the wavefront
+    const uint32_t n = (uint32_t)((rows - w.q0) < (int64_t)q.TL ? (rows - w.q0) : (int64_t)q.TL);
 
-    // pass 1: lane l hashes lookup row0 + l
+    // pass 1: lane l hashes the l-th lookup of the tile
     uint32_t th = 0, tg = 0;
-    {
-        const uint32_t e0 = (uint32_t)(row0 % (int64_t)q.F);
-        if (lane < n) {
-            const int64_t x = indices[row0 + lane];
-            const uint32_t e = (e0 + lane) % q.F;
-            th = staged_h(p, x, e);
-            if constexpr (SIGN) tg = staged_g(p, x, e);
-        }
+    if (lane < n) {
+        uint32_t e;
+        const int64_t k = walk_row(q, w, lane, e);
+        const int64_t x = indices[k];
+        th = staged_h(p, x, e);
+        if constexpr (SIGN) tg = staged_g(p, x, e);
     }
 
     // pass 2: groups of G lanes walk the tile, 64/G rows per step
@@ -207,13 +257,17 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
             for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u]);  // lookup 0 stands in for dead slots
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
-                if (live[u]) store_row<V, CONSEC>(dst + (row0 + rl[u]) * (int64_t)p.d, q, grp, v[u]);
+                if (live[u]) {
+                    uint32_t f_unused;
+                    store_row<V, CONSEC>(dst + walk_row(q, w, rl[u], f_unused) * (int64_t)p.d, q, grp, v[u]);
+                }
         } else {
             float v[kUnroll][V];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const uint32_t safe = live[u] ? rl[u] : 0u;
-                load_row<V, CONSEC>(src + (row0 + safe) * (int64_t)p.d, q, grp, v[u]);
+                uint32_t f_unused;
+                load_row<V, CONSEC>(src + walk_row(q, w, safe, f_unused) * (int64_t)p.d, q, grp, v[u]);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
@@ -235,15 +289,15 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
                                                      float *__restrict__ dst)            // fwd: out; bwd: grad_array
 {
     const uint32_t lane = threadIdx.x & 63u;
-    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     const uint32_t step = 64u >> q.g_shift;                 // bags per wavefront
-    const int64_t bag0 = wave * (int64_t)step;
-    if (bag0 >= rows) return;                               // uniform over the wavefront
+    RowWalk w;
+    if (!start_walk(q, rows, (int64_t)step, w)) return;     // uniform over the wavefront
     const uint32_t grp = lane & (q.G - 1u);
     const uint32_t sub = lane >> q.g_shift;
     const uint32_t base_lane = lane - grp;                  // first lane of this group
-    const int64_t bag = bag0 + sub;
-    const bool have_bag = bag < rows;
+    const bool have_bag = w.q0 + sub < rows;
+    uint32_t e = 0;
+    const int64_t bag = have_bag ? walk_row(q, w, sub, e) : 0;
 
     int64_t t0 = 0, t1 = 0;
     if (have_bag) {
@@ -252,7 +306,6 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
         t0 = t0 < 0 ? 0 : (t0 > n_indices ? n_indices : t0);
         t1 = t1 < t0 ? t0 : (t1 > n_indices ? n_indices : t1);
     }
-    const uint32_t e = ((uint32_t)(bag0 % (int64_t)q.F) + sub) % q.F;
 
     Lane<V, CONSEC, SIGN> L;
     L.init(p, q, grp);

@@ -265,7 +265,7 @@ def test_adagrad_matches_oracle_and_leaves_untouched_slots_alone(m, shift):
                                      ("ROBE_TUNE_FWD", "4,0"), ("ROBE_TUNE_FWD", "2,0"), ("ROBE_TUNE_FWD", "0,0"),
                                      ("ROBE_TUNE_BWD", "4,1"), ("ROBE_TUNE_BWD", "2,1"), ("ROBE_TUNE_BWD", "4,0"),
                                      ("ROBE_TUNE_BWD", "2,0"), ("ROBE_TUNE_BWD", "0,0"), ("ROBE_TUNE_TL", "64"),
-                                     ("ROBE_TUNE_TL", "8")])
+                                     ("ROBE_TUNE_TL", "8"), ("ROBE_TUNE_XCD", "2"), ("ROBE_TUNE_XCD", "0")])
 def test_every_lane_layout_gives_the_same_result(env, val, monkeypatch):
     # the library reads the override at call time; d = 64 makes every (V, layout) legal
     monkeypatch.setenv(env, val)
@@ -278,6 +278,31 @@ def test_every_lane_layout_gives_the_same_result(env, val, monkeypatch):
         out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F)
         assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F, threads=THREADS))
         idsb, off = random_bags(rng, B * F, 3000, 7.0, long_bag=100)
+        outb = robe.robe_forward(h, to_dev(M), to_dev(idsb), to_dev(off), B, F).cpu().numpy()
+        np.testing.assert_allclose(outb, oracle.forward(H, M, idsb, off, B, F, threads=THREADS), rtol=0, atol=2e-6)
+        Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+        for (i_, o_) in ((ids, None), (idsb, off)):
+            ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+            robe.robe_backward(h, to_dev(Gi), to_dev(i_), to_dev(o_), B, F, ga)
+            want, _ = oracle.backward(H, Gi, i_, o_, B, F)
+            assert np.array_equal(ga.cpu().numpy().astype(np.float64), want)
+
+
+@pytest.mark.parametrize("B,F", [(1, 2), (3, 26), (37, 26), (64, 5), (1000, 3), (5, 64), (129, 1)])
+@pytest.mark.parametrize("xcd", ["0", "2"])
+def test_row_walk_orders_cover_every_row_once(B, F, xcd, monkeypatch):
+    # rows walked in memory order or table by table (an eighth of that order per XCD): same results,
+    # for batches smaller than a tile, tables that end inside a tile, and grids padded to 8 XCDs
+    monkeypatch.setenv("ROBE_TUNE_XCD", xcd)
+    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", "direct")
+    for (m, d, Z) in [(50_021, 128, 32), (9_973, 16, 4), (30_011, 128, 1)]:
+        h, H = both_hashes(B * 131 + F, m, d, Z, 1)
+        rng = np.random.default_rng(B + F)
+        ids = rng.integers(0, 2000, size=(B, F), dtype=np.int64)
+        M = workloads.make_array(m, 2)
+        out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F)
+        assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F, threads=THREADS))
+        idsb, off = random_bags(rng, B * F, 2000, 4.0, long_bag=70)
         outb = robe.robe_forward(h, to_dev(M), to_dev(idsb), to_dev(off), B, F).cpu().numpy()
         np.testing.assert_allclose(outb, oracle.forward(H, M, idsb, off, B, F, threads=THREADS), rtol=0, atol=2e-6)
         Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
