@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="multihot",
-                    help="multihot | training | inference | sweep_z{1,8,32,128} | tiny")
+                    help="multihot | training | inference | sweep_z{1,8,32,128} | kaggle_z{1,2,4,8,16} | tiny")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0: as defined)")
     ap.add_argument("--m", type=int, default=0, help="override the array length in floats (0: as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -51,8 +51,9 @@ def algorithmic_bytes(w, rows, tokens, touched):
     bags = w.bag_mean is not None
     fwd = tokens * (vec + 8) + rows * vec + (rows + 1) * 8 * bags
     bwd = rows * vec + tokens * (2 * vec + 8) + (rows + 1) * 8 * bags
-    ada = touched * 24
-    return {"fwd": fwd, "bwd": bwd, "adagrad": ada}
+    ada = touched * 24          # read g, s, M; write s, M, g = 0
+    sgd = touched * 16          # read g, M; write M, g = 0
+    return {"fwd": fwd, "bwd": bwd, "adagrad": ada, "sgd": sgd}
 
 
 def measured_traffic(workload, kernel):
@@ -104,12 +105,15 @@ def cpu_baseline(w, M, ids, off, G, target_s):
     bs = int(max(probe, min(w.batch, target_s / max(per_sample, 1e-9))))
     ntok, tf, tb = run(bs)
     ta = 0.0
-    if "adagrad" in w.phases:
+    if "adagrad" in w.phases or "sgd" in w.phases:
         g = np.zeros(w.m, dtype=np.float32)
         g[::3] = 1.0
         Mc, s = M.copy(), np.zeros(w.m, dtype=np.float32)
         t0 = time.perf_counter()
-        oracle.adagrad(Mc, s, g, w.lr, w.eps, threads=threads)
+        if "adagrad" in w.phases:
+            oracle.adagrad(Mc, s, g, w.lr, w.eps, threads=threads)
+        else:
+            oracle.sgd(Mc, g, w.lr, threads=threads)
         ta = time.perf_counter() - t0
     return {"sample_tokens": ntok, "sample_batch": bs, "t_fwd": tf, "t_bwd": tb, "t_adagrad_dense_full_m": ta,
             "threads": threads}
@@ -143,6 +147,7 @@ def main():
     rows = B * F
     do_bwd = "bwd" in w.phases
     do_ada = "adagrad" in w.phases
+    do_sgd = "sgd" in w.phases
 
     t_gen = time.perf_counter()
     M = workloads.make_array(w.m, 0)
@@ -176,6 +181,8 @@ def main():
                 ev[2].record(stream)
             if do_ada:
                 robe.robe_adagrad_update(h, Md, st, ga, w.lr, w.eps)
+            elif do_sgd:
+                robe.robe_sgd_update(h, Md, ga, w.lr)
             else:
                 ga.zero_()          # a training loop clears the gradient it has consumed
             if ev:
@@ -211,13 +218,15 @@ def main():
     elapsed = time.perf_counter() - t0
 
     ms_per_step = 1e3 * elapsed / args.steps
-    k_ms = {"fwd": [], "bwd": [], "adagrad": []}
+    k_ms = {"fwd": [], "bwd": [], "adagrad": [], "sgd": []}
     for ev in events:
         k_ms["fwd"].append(ev[0].elapsed_time(ev[1]))
         if do_bwd:
             k_ms["bwd"].append(ev[1].elapsed_time(ev[2]))
             if do_ada:
                 k_ms["adagrad"].append(ev[2].elapsed_time(ev[3]))
+            if do_sgd:
+                k_ms["sgd"].append(ev[2].elapsed_time(ev[3]))
     avg = {k: (sum(v) / len(v) if v else 0.0) for k, v in k_ms.items()}
     tok = sum(tokens[k % len(tokens)] for k in range(args.steps)) / args.steps
     alg = algorithmic_bytes(w, rows, tok, touched)
@@ -226,7 +235,7 @@ def main():
         return tok / (ms * 1e-3) if ms > 0 else None
 
     kernels = {}
-    for name in ("fwd", "bwd", "adagrad"):
+    for name in ("fwd", "bwd", "adagrad", "sgd"):
         if avg[name] > 0:
             gbs = alg[name] / (avg[name] * 1e-3) / 1e9
             kernels[name] = {"ms": round(avg[name], 4), "algorithmic_GB": round(alg[name] / 1e9, 4),
@@ -235,17 +244,18 @@ def main():
     phases = {"fwd": {"ms": round(avg["fwd"], 4), "lookups_per_s": rate(avg["fwd"])}}
     if do_bwd:
         phases["fwd_bwd"] = {"ms": round(avg["fwd"] + avg["bwd"], 4), "lookups_per_s": rate(avg["fwd"] + avg["bwd"])}
-    if do_ada:
-        t_all = avg["fwd"] + avg["bwd"] + avg["adagrad"]
-        phases["fwd_bwd_adagrad"] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all)}
+    if do_ada or do_sgd:
+        opt = "adagrad" if do_ada else "sgd"
+        t_all = avg["fwd"] + avg["bwd"] + avg[opt]
+        phases["fwd_bwd_" + opt] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all)}
     total_alg = sum(alg[n] for n in kernels)
     # the timed unit of each phase is one entry-point call; backward is several kernels when it sorts
-    entry_names = {"fwd": "robe_forward", "adagrad": "robe_adagrad_update",
+    entry_names = {"fwd": "robe_forward", "adagrad": "robe_adagrad_update", "sgd": "robe_sgd_update",
                    "bwd": "robe_backward (" + ("token_keys + radix sort + combine_scatter kernels" if ws_bytes
                                                else "direct scatter kernel") + ")"}
     result = {
         "metric": "ROBE lookups/sec, whole step (fwd%s%s), d=%d, Z=%d" % (
-            "+bwd" if do_bwd else "", "+Adagrad" if do_ada else "", w.d, w.Z),
+            "+bwd" if do_bwd else "", "+Adagrad" if do_ada else ("+SGD" if do_sgd else ""), w.d, w.Z),
         "value": tok / (ms_per_step * 1e-3),
         "unit": "lookups/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -277,8 +287,8 @@ def main():
             "sample": ("first %d of %d batch samples (%d tokens): oracle fwd %.2f s%s, scaled by tokens; "
                        "%s") % (cb["sample_batch"], B, cb["sample_tokens"], cb["t_fwd"],
                                 (", bwd %.2f s" % cb["t_bwd"]) if do_bwd else "",
-                                ("dense Adagrad over all m slots %.2f s, unscaled" % cb["t_adagrad_dense_full_m"])
-                                if do_ada else "no optimizer phase"),
+                                ("dense optimizer sweep over all m slots %.3f s, unscaled" % cb["t_adagrad_dense_full_m"])
+                                if (do_ada or do_sgd) else "no optimizer phase"),
             "fwd_lookups_per_s": cb["sample_tokens"] / cb["t_fwd"] if cb["t_fwd"] > 0 else None,
         }
     print(json.dumps(result))

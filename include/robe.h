@@ -163,6 +163,17 @@ int robe_backward(const robe_hash_t *hash, const float *grad_out,
 int robe_adagrad_update(const robe_hash_t *hash, float *array, float *state, float *grad_array,
                         float lr, float eps, void *stream);
 
+/*
+ * Sparse SGD step on the touched slots, the rule the paper trains DLRM with
+ * (Appendix, hyper-parameter table: SGD, learning rate 1.0).  For every j with
+ * grad_array[j] != 0, in float32 with each operation rounded on its own:
+ *   array[j] -= lr * grad_array[j]
+ *   grad_array[j] = 0
+ * Slots with a zero gradient are left bit-for-bit unchanged.  Both are device float[m].
+ * Errors: ROBE_EINVAL (null pointers, non-finite lr), ROBE_EHIP.
+ */
+int robe_sgd_update(const robe_hash_t *hash, float *array, float *grad_array, float lr, void *stream);
+
 /* Text of the calling thread's most recent error ("" if none).  Never NULL. */
 const char *robe_last_error(void);
 

@@ -65,6 +65,8 @@ def _load():
         L.oracle_backward.argtypes = [vp, u64, u64, u32, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp, vp, ctypes.c_int]
         L.oracle_adagrad.restype = None
         L.oracle_adagrad.argtypes = [vp, vp, vp, u64, ctypes.c_double, ctypes.c_double, ctypes.c_int]
+        L.oracle_sgd.restype = None
+        L.oracle_sgd.argtypes = [vp, vp, u64, ctypes.c_double, ctypes.c_int]
         L.oracle_max_threads.restype = ctypes.c_int
         L.oracle_max_threads.argtypes = []
         _lib = L
@@ -181,6 +183,13 @@ def adagrad(array: np.ndarray, state: np.ndarray, grad: np.ndarray, lr: float, e
     for a in (array, state, grad):
         assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"] and a.size == array.size
     _load().oracle_adagrad(_ptr(array), _ptr(state), _ptr(grad), array.size, lr, eps, threads)
+
+
+def sgd(array: np.ndarray, grad: np.ndarray, lr: float, threads: int = 1) -> None:
+    """In place on two contiguous float32 arrays of equal length; grad is zeroed."""
+    for a in (array, grad):
+        assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"] and a.size == array.size
+    _load().oracle_sgd(_ptr(array), _ptr(grad), array.size, lr, threads)
 
 
 def max_threads() -> int:

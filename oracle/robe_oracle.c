@@ -22,8 +22,8 @@
  * Parity pins live in tests/test_oracle_*.py: arbitrary-precision brute force
  * for h, g and idx; the explicit sketching matrix (Section 4) for forward and
  * backward; the published SplitMix64 vectors for the coefficient stream;
- * torch.optim.Adagrad (CPU, float64) for the optimizer step.  No function
- * here is "parity unpinned".
+ * torch.optim.Adagrad and torch.optim.SGD (CPU, float64) for the optimizer
+ * steps.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -199,6 +199,21 @@ void oracle_adagrad(float *array, float *state, float *grad, uint64_t m, double 
         double w = (double)array[j] - lr * g / (sqrt(s) + eps);
         state[j] = (float)s;
         array[j] = (float)w;
+        grad[j] = 0.0f;
+    }
+}
+
+/*
+ * Plain SGD step, the optimizer the paper trains DLRM with (Appendix, hyper-parameter table:
+ * SGD, learning rate 1.0):  M'[j] = M[j] - lr * g[j] ;  g[j] = 0.  Double arithmetic on
+ * float-stored operands, one rounding.  A slot with g == 0 is left exactly unchanged.
+ */
+void oracle_sgd(float *array, float *grad, uint64_t m, double lr, int threads)
+{
+    (void)threads;
+#pragma omp parallel for schedule(static) num_threads(threads > 0 ? threads : 1)
+    for (int64_t j = 0; j < (int64_t)m; ++j) {
+        array[j] = (float)((double)array[j] - lr * (double)grad[j]);
         grad[j] = 0.0f;
     }
 }

@@ -45,7 +45,7 @@ class RobeHash(ctypes.Structure):
 
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
-           "robe_adagrad_update", "robe_last_error")
+           "robe_adagrad_update", "robe_sgd_update", "robe_last_error")
 
 _lib = None
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.robe_backward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_size_t, vp]
         L.robe_adagrad_update.restype = ctypes.c_int
         L.robe_adagrad_update.argtypes = [HP, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp]
+        L.robe_sgd_update.restype = ctypes.c_int
+        L.robe_sgd_update.argtypes = [HP, vp, vp, ctypes.c_float, vp]
         L.robe_last_error.restype = ctypes.c_char_p
         L.robe_last_error.argtypes = []
         _lib = L
@@ -161,3 +163,11 @@ def robe_adagrad_update(h: RobeHash, array: torch.Tensor, state: torch.Tensor, g
     _check(lib().robe_adagrad_update(ctypes.byref(h), _dev(array, torch.float32, "array"),
                                      _dev(state, torch.float32, "state"),
                                      _dev(grad_array, torch.float32, "grad_array"), lr, eps, _stream()))
+
+
+def robe_sgd_update(h: RobeHash, array: torch.Tensor, grad_array: torch.Tensor, lr: float) -> None:
+    for t, name in ((array, "array"), (grad_array, "grad_array")):
+        if t.numel() != h.m:
+            raise ValueError(f"{name} length differs from hash.m")
+    _check(lib().robe_sgd_update(ctypes.byref(h), _dev(array, torch.float32, "array"),
+                                 _dev(grad_array, torch.float32, "grad_array"), lr, _stream()))

@@ -453,6 +453,26 @@ int robe_backward(const robe_hash_t *hash, const float *grad_out, const int64_t 
     return launch_rows<true>(hash, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad_array, grad_out, (hipStream_t)stream);
 }
 
+static int launch_update(int rule, const robe_hash_t *hash, float *array, float *state, float *grad_array,
+                         float lr, float eps, void *stream)
+{
+    const uint64_t m = hash->m;
+    hipStream_t s = (hipStream_t)stream;
+    const bool vec = aligned(array, 16) && aligned(grad_array, 16) && (rule != 0 || aligned(state, 16)) && m >= 4;
+    uint64_t work = vec ? m / 4 : m;   // one thread per vector
+    if (work < 1) work = 1;
+    const uint64_t blocks = (work + robe::kBlock - 1) / robe::kBlock;   // <= 2^23 since m < 2^31
+    const dim3 grid((uint32_t)blocks), block(robe::kBlock);
+    if (rule == 0) {
+        if (vec) robe::update_kernel<4, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps);
+        else robe::update_kernel<1, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps);
+    } else {
+        if (vec) robe::update_kernel<4, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f);
+        else robe::update_kernel<1, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f);
+    }
+    return check_launch(rule == 0 ? "adagrad" : "sgd");
+}
+
 int robe_adagrad_update(const robe_hash_t *hash, float *array, float *state, float *grad_array,
                         float lr, float eps, void *stream)
 {
@@ -460,17 +480,16 @@ int robe_adagrad_update(const robe_hash_t *hash, float *array, float *state, flo
     if (array == nullptr || state == nullptr || grad_array == nullptr) return fail(ROBE_EINVAL, "array, state or grad_array is NULL");
     if (!std::isfinite(lr) || !std::isfinite(eps) || !(eps > 0.0f)) return fail(ROBE_EINVAL, "need finite lr and eps > 0");
     if (!aligned(array, 4) || !aligned(state, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
-    const uint64_t m = hash->m;
-    hipStream_t s = (hipStream_t)stream;
-    const bool vec = aligned(array, 16) && aligned(state, 16) && aligned(grad_array, 16) && m >= 4;
-    uint64_t work = vec ? m / 4 : m;   // one thread per vector
-    if (work < 1) work = 1;
-    const uint64_t blocks = (work + robe::kBlock - 1) / robe::kBlock;   // <= 2^23 since m < 2^31
-    if (vec)
-        robe::adagrad_kernel<4><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, s>>>(array, state, grad_array, m, lr, eps);
-    else
-        robe::adagrad_kernel<1><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, s>>>(array, state, grad_array, m, lr, eps);
-    return check_launch("adagrad");
+    return launch_update(0, hash, array, state, grad_array, lr, eps, stream);
+}
+
+int robe_sgd_update(const robe_hash_t *hash, float *array, float *grad_array, float lr, void *stream)
+{
+    if (int rc = check_hash(hash)) return rc;
+    if (array == nullptr || grad_array == nullptr) return fail(ROBE_EINVAL, "array or grad_array is NULL");
+    if (!std::isfinite(lr)) return fail(ROBE_EINVAL, "need a finite lr");
+    if (!aligned(array, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    return launch_update(1, hash, array, nullptr, grad_array, lr, 0.0f, stream);
 }
 
 }  // extern "C"

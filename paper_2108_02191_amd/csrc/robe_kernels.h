@@ -437,7 +437,7 @@ __global__ __launch_bounds__(kBlock) void signs_kernel(Params p, uint32_t F, uin
 }
 
 // ---------------------------------------------------------------------------
-// Adagrad on touched slots.  Explicitly rounded float32 steps (no contraction).
+// Optimizer steps on touched slots (Adagrad, SGD).  Explicitly rounded float32 steps (no contraction).
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void adagrad_one(float &w, float &s, float g, float lr, float eps)
 {
@@ -453,9 +453,10 @@ __device__ __forceinline__ void adagrad_one(float &w, float &s, float g, float l
 // memory system far more than the bytes they save.
 constexpr uint32_t kLineLanes = 4;
 
-template <int V>
-__global__ __launch_bounds__(kBlock) void adagrad_kernel(float *__restrict__ array, float *__restrict__ state,
-                                                         float *__restrict__ grad, uint64_t m, float lr, float eps)
+// RULE 0: Adagrad (array, state, grad).  RULE 1: SGD (array, grad; `state` and `eps` unused).
+template <int V, int RULE>
+__global__ __launch_bounds__(kBlock) void update_kernel(float *__restrict__ array, float *__restrict__ state,
+                                                        float *__restrict__ grad, uint64_t m, float lr, float eps)
 {
     typedef typename Vec<V>::A VT;
     const uint64_t nvec = m / V;
@@ -472,31 +473,40 @@ __global__ __launch_bounds__(kBlock) void adagrad_kernel(float *__restrict__ arr
     const uint64_t line_any = (__ballot(any) >> (lane & ~(kLineLanes - 1u))) & ((1ull << kLineLanes) - 1ull);
     if (in_range && line_any != 0) {  // an untouched granule: nothing read beyond the gradient, nothing written
         VT w = __builtin_nontemporal_load(reinterpret_cast<const VT *>(array + it * V));
-        VT s = __builtin_nontemporal_load(reinterpret_cast<const VT *>(state + it * V));
+        VT s;
+        if constexpr (RULE == 0) s = __builtin_nontemporal_load(reinterpret_cast<const VT *>(state + it * V));
 #pragma unroll
         for (int k = 0; k < V; ++k) {
             if (g[k] != 0.0f) {      // slots with a zero gradient are rewritten with the bits they had
-                float wk = w[k], sk = s[k];
-                adagrad_one(wk, sk, g[k], lr, eps);
-                w[k] = wk;
-                s[k] = sk;
+                if constexpr (RULE == 0) {
+                    float wk = w[k], sk = s[k];
+                    adagrad_one(wk, sk, g[k], lr, eps);
+                    w[k] = wk;
+                    s[k] = sk;
+                } else {
+                    w[k] = __fsub_rn(w[k], __fmul_rn(lr, g[k]));
+                }
             }
             g[k] = 0.0f;
         }
         __builtin_nontemporal_store(w, reinterpret_cast<VT *>(array + it * V));
-        __builtin_nontemporal_store(s, reinterpret_cast<VT *>(state + it * V));
+        if constexpr (RULE == 0) __builtin_nontemporal_store(s, reinterpret_cast<VT *>(state + it * V));
         __builtin_nontemporal_store(g, reinterpret_cast<VT *>(grad + it * V));
     }
     // tail (m not a multiple of V): first threads of block 0
     if (V > 1 && blockIdx.x == 0) {
         const uint64_t j = nvec * V + threadIdx.x;
         if (threadIdx.x < V && j < m) {
-            const float g = grad[j];
-            if (g != 0.0f) {
-                float w = array[j], s = state[j];
-                adagrad_one(w, s, g, lr, eps);
-                array[j] = w;
-                state[j] = s;
+            const float gj = grad[j];
+            if (gj != 0.0f) {
+                if constexpr (RULE == 0) {
+                    float wj = array[j], sj = state[j];
+                    adagrad_one(wj, sj, gj, lr, eps);
+                    array[j] = wj;
+                    state[j] = sj;
+                } else {
+                    array[j] = __fsub_rn(array[j], __fmul_rn(lr, gj));
+                }
                 grad[j] = 0.0f;
             }
         }

@@ -261,6 +261,30 @@ def test_adagrad_matches_oracle_and_leaves_untouched_slots_alone(m, shift):
     assert untouched.all() or not bits_equal(Mg, M0)
 
 
+@pytest.mark.parametrize("m,shift", [(4096, 0), (4099, 1), (3, 0), (1_000_001, 2)])
+def test_sgd_matches_oracle_and_leaves_untouched_slots_alone(m, shift):
+    rng = np.random.default_rng(m + shift)
+    h = robe.robe_init_hash(0, m, 1, 1, 0)
+    M0 = rng.standard_normal(m).astype(np.float32)
+    g0 = rng.standard_normal(m).astype(np.float32) * (rng.random(m) < 0.6)
+    def dev(a):
+        buf = torch.zeros(m + shift, dtype=torch.float32, device=DEV)
+        view = buf[shift:]
+        view.copy_(torch.from_numpy(a))
+        return view
+    M, g = dev(M0), dev(g0)
+    robe.robe_sgd_update(h, M, g, 1.0)
+    Mo, go = M0.copy(), g0.copy()
+    oracle.sgd(Mo, go, 1.0)
+    Mg = M.cpu().numpy()
+    assert not g.cpu().numpy().any()
+    assert bits_equal(Mg[g0 == 0], M0[g0 == 0])
+    # float32 multiply then subtract (two roundings) against one rounding of the exact value
+    assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(M0) + np.abs(g0)) + TINY)
+    # with lr = 1 the product is exact, so the result is the correctly rounded difference: bit-exact
+    assert bits_equal(Mg, Mo)
+
+
 @pytest.mark.parametrize("env,val", [("ROBE_TUNE_FWD", "4,1"), ("ROBE_TUNE_FWD", "2,1"), ("ROBE_TUNE_FWD", "1,1"),
                                      ("ROBE_TUNE_FWD", "4,0"), ("ROBE_TUNE_FWD", "2,0"), ("ROBE_TUNE_FWD", "0,0"),
                                      ("ROBE_TUNE_BWD", "4,1"), ("ROBE_TUNE_BWD", "2,1"), ("ROBE_TUNE_BWD", "4,0"),

@@ -91,6 +91,15 @@ def run_workload(name, **scale):
     assert abs(lhs - rhs) <= 1e-5 * float(np.abs(M).astype(np.float64) @ S) + 1e-9
     del err, S
 
+    if "sgd" in w.phases:
+        robe.robe_sgd_update(h, Md, ga, w.lr)
+        Mo, go = M.copy(), got.copy()
+        oracle.sgd(Mo, go, w.lr, threads=THREADS)
+        Mg = Md.cpu().numpy()
+        assert not ga.cpu().numpy().any()
+        assert bits_equal(Mg[got == 0], M[got == 0])
+        assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(M) + np.abs(got)) + TINY)
+        return
     if "adagrad" not in w.phases:
         return
     # same gradient (the GPU's) into both optimizers
@@ -135,6 +144,11 @@ def test_training_config_full_size():
 @pytest.mark.parametrize("Z", [1, 8, 32, 128])
 def test_block_size_sweep_full_size(Z):
     run_workload(f"sweep_z{Z}")
+
+
+@pytest.mark.parametrize("Z", [1, 2, 4, 8, 16])
+def test_kaggle_shaped_workload(Z):
+    run_workload(f"kaggle_z{Z}")
 
 
 def test_multihot_config_full_size():

@@ -217,6 +217,28 @@ def test_adagrad_first_step_closed_form():
     np.testing.assert_allclose(s, (g.astype(np.float64) ** 2).astype(np.float32), rtol=0, atol=0)
 
 
+def test_sgd_matches_torch_cpu_and_closed_form():
+    rng = np.random.default_rng(1)
+    n = 2048
+    M0 = rng.standard_normal(n).astype(np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(M0.astype(np.float64)))
+    opt = torch.optim.SGD([p], lr=1.0)                 # the paper's DLRM setting (Appendix: SGD, lr 1.0)
+    M = M0.copy()
+    for step in range(3):
+        g = rng.standard_normal(n).astype(np.float32)
+        g[rng.random(n) < 0.5] = 0.0
+        before = M.copy()
+        p.grad = torch.from_numpy(g.astype(np.float64))
+        opt.step()
+        grad = g.copy()
+        oracle.sgd(M, grad, 1.0)
+        assert not grad.any()
+        assert np.array_equal(M[g == 0], before[g == 0])
+        want = (before.astype(np.float64) - 1.0 * g.astype(np.float64)).astype(np.float32)
+        assert np.array_equal(M, want)                 # one rounding of the exact result
+        np.testing.assert_allclose(M, p.detach().numpy(), rtol=1e-6, atol=1e-6)
+
+
 def test_inner_product_estimator_is_unbiased_over_hash_draws():
     # Theorem 1 (Section 4.1): E<x^, y^> = <x, y> for the signed projection.
     # Loose Monte-Carlo check over seeds; it fails if the sign or the block

@@ -35,7 +35,7 @@ class Workload:
     zipf_alpha: float
     use_sign: int
     bag_mean: Optional[float]  # None: single-hot; else Poisson mean of the bag size
-    phases: str               # "fwd" | "fwd+bwd" | "fwd+bwd+adagrad"
+    phases: str               # "fwd" | "fwd+bwd" | "fwd+bwd+adagrad" | "fwd+bwd+sgd"
     lr: float = 0.01
     eps: float = 1e-8
     hash_seed: int = 2108_02191
@@ -53,6 +53,12 @@ def log_spaced_cardinalities(lo: float = 10.0, hi: float = 4e7, n: int = N_FEATU
     return tuple(int(round(lo * (hi / lo) ** (f / (n - 1)))) for f in range(n))
 
 
+# Table sizes of the Criteo Kaggle dataset as the paper prints them (Appendix, "Criteo Kaggle
+# Experiment": 26 categorical features, about 33 M values in total).
+KAGGLE_CARDINALITIES = (1460, 583, 10131227, 2202608, 305, 24, 12517, 633, 3, 93145, 5683, 8351593,
+                        3194, 27, 14992, 5461306, 10, 5652, 2173, 4, 7046547, 18, 15, 286181, 105, 142572)
+
+
 def get(name: str) -> Workload:
     ls = log_spaced_cardinalities()
     if name == "tiny":
@@ -64,13 +70,20 @@ def get(name: str) -> Workload:
     if name.startswith("sweep_z"):
         Z = int(name[len("sweep_z"):])
         return Workload(name, 25_000_000, 128, Z, 32768, N_FEATURES, ls, "zipf", 1.05, 0, None, "fwd+bwd")
+    if name.startswith("kaggle_z"):
+        # the paper's second setting (Section 5.3): d = 16, 540 K parameters (1000x compression of
+        # 540 M), Z in {1,2,4,8,16}, batch 2048, SGD for DLRM; ids synthetic (bounded Zipf per table)
+        Z = int(name[len("kaggle_z"):])
+        return Workload(name, 540_000, 16, Z, 2048, N_FEATURES, KAGGLE_CARDINALITIES, "zipf", 1.05, 0, None,
+                        "fwd+bwd+sgd", lr=1.0)
     if name == "multihot":
         return Workload("multihot", 250_000_000, 128, 32, 16384, N_FEATURES, (40_000_000,) * N_FEATURES,
                         "zipf", 1.05, 0, 20.0, "fwd+bwd+adagrad")
     raise KeyError(name)
 
 
-ALL = ("tiny", "inference", "training", "sweep_z1", "sweep_z8", "sweep_z32", "sweep_z128", "multihot")
+ALL = ("tiny", "inference", "training", "sweep_z1", "sweep_z8", "sweep_z32", "sweep_z128", "multihot",
+       "kaggle_z1", "kaggle_z2", "kaggle_z4", "kaggle_z8", "kaggle_z16")
 
 
 def make_array(m: int, seed: int = 0) -> np.ndarray:
