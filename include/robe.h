@@ -138,7 +138,9 @@ size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_fe
  * issue the atomics once per run; that path needs the workspace and rows,
  * n_indices below 2^31 - 1.  With a CSR that is not non-decreasing, bag bounds
  * are clamped to [0, n_indices] so nothing outside the buffers is touched, but
- * which tokens such bags hold is unspecified here.
+ * which tokens such bags hold is unspecified here.  The sort step records
+ * memset nodes on the stream, so a large robe_backward should not be captured
+ * into a HIP graph.
  *   workspace  device buffer of at least robe_workspace_bytes(...) bytes,
  *              256-byte aligned, contents undefined before and after; may be
  *              NULL when that size is 0
