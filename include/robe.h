@@ -58,7 +58,9 @@ extern "C" {
  * One ROBE-Z instance (Eq. 5 and the text under it; g from Eq. 2).
  * Plain data, owned by the caller, copied by value into kernel arguments.
  *   m          array length in floats, 1 <= m <= 2^31 - 1
- *   d, Z       embedding size and block size, Z >= 1, Z divides d, Z <= m
+ *   d, Z       embedding size and block size, Z >= 1, Z <= m, and either Z divides d
+ *              or d divides Z (Section 3.3: r = Z/d consecutive tokens of a table share a
+ *              block; then idx(e,x,i) = (h(e, x / r, 0) + (x mod r)*d + i) mod m)
  *   use_sign   0: g == +1 everywhere; non-zero: g as in Eq. 2
  *   P          must be ROBE_PRIME
  *   Ah,Bh,Ch   multipliers of h in [1, P-1];  Dh additive constant in [0, P-1]
@@ -91,7 +93,8 @@ int robe_init_hash(uint64_t seed, uint64_t m, uint32_t d, uint32_t Z, int use_si
 /*
  * Testing aid: the integer maps alone (Eq. 5 for h, Eq. 2 for g).
  *   indices      device int64[n]; lookup k belongs to table k mod n_features
- *   out_offsets  device int64[n * d/Z] or NULL:  out_offsets[k*(d/Z) + c] = h(e,x,c)
+ *   out_offsets  device int64[n * d/Z] or NULL:  out_offsets[k*(d/Z) + c] = h(e,x,c);
+ *                for Z > d: int64[n], out_offsets[k] = idx(e,x,0)
  *   out_signs    device int8 [n * d]   or NULL:  out_signs[k*d + i] = g(e,x,i)
  * Errors: ROBE_EINVAL (null hash/indices with n > 0, n < 0, n_features < 1,
  * invalid hash); ROBE_EHIP on launch failure.  n == 0 is a no-op.

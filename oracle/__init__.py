@@ -54,7 +54,7 @@ def _load():
         L.oracle_g.restype = ctypes.c_int
         L.oracle_g.argtypes = [vp, u64, ctypes.c_int, u64, u64, u64]
         L.oracle_idx.restype = u64
-        L.oracle_idx.argtypes = [vp, u64, u64, u32, u64, u64, u64]
+        L.oracle_idx.argtypes = [vp, u64, u64, u32, u32, u64, u64, u64]
         L.oracle_offsets.restype = None
         L.oracle_offsets.argtypes = [vp, u64, u64, u32, u32, vp, i64, i32, vp]
         L.oracle_signs.restype = None
@@ -95,8 +95,8 @@ def splitmix64_stream(seed: int, n: int):
 
 
 def init_hash(seed: int, m: int, d: int, Z: int, use_sign: int, P: int = P_DEFAULT) -> Hash:
-    if m < 1 or d < 1 or Z < 1 or d % Z or Z > m:
-        raise ValueError("need m >= 1, Z >= 1, Z | d, Z <= m")
+    if m < 1 or d < 1 or Z < 1 or Z > m or (d % Z if Z <= d else Z % d):
+        raise ValueError("need m >= 1, Z >= 1, Z | d or d | Z, Z <= m")
     L = _load()
     c = (ctypes.c_uint64 * 8)()
     L.oracle_init_hash(seed, P, c)
@@ -112,7 +112,7 @@ def g(H: Hash, e: int, x: int, i: int) -> int:
 
 
 def idx(H: Hash, e: int, x: int, i: int) -> int:
-    return int(_load().oracle_idx(H._c(), H.P, H.m, H.Z, e, x & (2**64 - 1), i))
+    return int(_load().oracle_idx(H._c(), H.P, H.m, H.d, H.Z, e, x & (2**64 - 1), i))
 
 
 def _i64(a) -> np.ndarray:
@@ -129,7 +129,7 @@ def _ptr(a: Optional[np.ndarray]):
 
 def offsets(H: Hash, indices, F: int) -> np.ndarray:
     ind = _i64(indices).ravel()
-    out = np.empty((ind.size, H.d // H.Z), dtype=np.int64)
+    out = np.empty((ind.size, max(1, H.d // H.Z)), dtype=np.int64)
     _load().oracle_offsets(H._c(), H.P, H.m, H.d, H.Z, _ptr(ind), ind.size, F, _ptr(out))
     return out
 

@@ -82,18 +82,36 @@ int oracle_g(const uint64_t coef[8], uint64_t P, int use_sign,
     return 2 * (int)((t % P) % 2) - 1;
 }
 
-/* idx(e,x,i) = (h(e,x,floor(i/Z)) + i mod Z) mod m   (Section 3.2, idx equation) */
-uint64_t oracle_idx(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t Z,
+/*
+ * idx(e,x,i) = (h(e,x,floor(i/Z)) + i mod Z) mod m   (Section 3.2, idx equation), for Z <= d.
+ *
+ * Z > d (Section 3.3; Appendix, "ROBE-Z": the table is flattened row by row and cut into chunks of
+ * Z, each chunk hashed to its place): element i of token x is entry n = x*d + i of table e's
+ * flattened rows, in chunk floor(n / Z) at place n mod Z.  With d | Z a chunk holds r = Z/d whole
+ * embeddings, so the chunk is floor(x / r) and the place is (x mod r)*d + i; the chunk id takes the
+ * token's seat in h and the chunk number c is 0.
+ */
+uint64_t oracle_idx(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t d, uint32_t Z,
                     uint64_t e, uint64_t x, uint64_t i)
 {
-    uint64_t c = i / Z, j = i % Z;
-    return (oracle_h(coef, P, m, e, x, c) + j) % m;
+    if (Z <= d) {
+        uint64_t c = i / Z, j = i % Z;
+        return (oracle_h(coef, P, m, e, x, c) + j) % m;
+    }
+    uint64_t r = Z / d;
+    uint64_t chunk = x / r, place = (x % r) * d + i;
+    return (oracle_h(coef, P, m, e, chunk, 0) + place) % m;
 }
 
-/* Chunk offsets of n lookups; lookup k belongs to feature k mod F.  out[k*C + c]. */
+/* Chunk offsets of n lookups; lookup k belongs to feature k mod F.  out[k*C + c], C = d/Z (Z <= d). */
 void oracle_offsets(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t d, uint32_t Z,
                     const int64_t *indices, int64_t n, int32_t F, int64_t *out)
 {
+    if (Z > d) { /* one entry per lookup: where element 0 of the embedding sits */
+        for (int64_t k = 0; k < n; ++k)
+            out[k] = (int64_t)oracle_idx(coef, P, m, d, Z, (uint64_t)(k % F), (uint64_t)indices[k], 0);
+        return;
+    }
     uint32_t C = d / Z;
     for (int64_t k = 0; k < n; ++k)
         for (uint32_t c = 0; c < C; ++c)
@@ -131,14 +149,14 @@ void oracle_forward(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t d, 
             if (offsets == NULL) {
                 /* single-hot: one term, a copy with an exact sign flip */
                 uint64_t x = (uint64_t)indices[k];
-                float v = array[oracle_idx(coef, P, m, Z, e, x, i)];
+                float v = array[oracle_idx(coef, P, m, d, Z, e, x, i)];
                 out[k * (int64_t)d + i] = oracle_g(coef, P, use_sign, e, x, i) < 0 ? -v : v;
                 continue;
             }
             double acc = 0.0;
             for (int64_t t = t0; t < t1; ++t) {
                 uint64_t x = (uint64_t)indices[t];
-                uint64_t j = oracle_idx(coef, P, m, Z, e, x, i);
+                uint64_t j = oracle_idx(coef, P, m, d, Z, e, x, i);
                 acc += (double)oracle_g(coef, P, use_sign, e, x, i) * (double)array[j];
             }
             out[k * (int64_t)d + i] = (float)acc;
@@ -169,7 +187,7 @@ void oracle_backward(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t d,
         for (int64_t t = t0; t < t1; ++t) {
             uint64_t x = (uint64_t)indices[t];
             for (uint32_t i = 0; i < d; ++i) {
-                uint64_t j = oracle_idx(coef, P, m, Z, e, x, i);
+                uint64_t j = oracle_idx(coef, P, m, d, Z, e, x, i);
                 double term = (double)oracle_g(coef, P, use_sign, e, x, i) * (double)grad_out[k * (int64_t)d + i];
 #pragma omp atomic
                 grad_array[j] += term;

@@ -41,7 +41,7 @@ class RobeHash(ctypes.Structure):
 
     @property
     def chunks(self) -> int:
-        return self.d // self.Z
+        return max(1, self.d // self.Z)
 
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",

@@ -48,7 +48,8 @@ int check_shape(uint64_t m, uint32_t d, uint32_t Z)
 {
     if (m < 1 || m > (uint64_t)ROBE_PRIME) return fail(ROBE_EINVAL, "m = %llu outside [1, 2^31 - 1]", (unsigned long long)m);
     if (d < 1 || Z < 1) return fail(ROBE_EINVAL, "d = %u and Z = %u must be >= 1", d, Z);
-    if (d % Z != 0) return fail(ROBE_EINVAL, "Z = %u does not divide d = %u", Z, d);
+    if (Z <= d ? d % Z != 0 : Z % d != 0)
+        return fail(ROBE_EINVAL, "Z = %u must divide d = %u or be a multiple of it", Z, d);
     if ((uint64_t)Z > m) return fail(ROBE_EINVAL, "Z = %u exceeds m = %llu", Z, (unsigned long long)m);
     return ROBE_OK;
 }
@@ -73,7 +74,8 @@ robe::Params to_params(const robe_hash_t *h)
     p.m_recip = recip > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)recip;
     p.d = h->d;
     p.Z = h->Z;
-    p.C = h->d / h->Z;
+    p.C = h->Z <= h->d ? h->d / h->Z : 1u;
+    p.r = h->Z <= h->d ? 0u : h->Z / h->d;
     p.Ah = h->Ah; p.Bh = h->Bh; p.Ch = h->Ch; p.Dh = h->Dh;
     p.Ag = h->Ag; p.Bg = h->Bg; p.Cg = h->Cg; p.Dg = h->Dg;
     return p;
@@ -97,7 +99,7 @@ bool tuned_layout(const char *var, const robe_hash_t *h, Layout *out)
     if (!s) return false;
     int V = 0, consec = 0;
     if (sscanf(s, "%d,%d", &V, &consec) != 2) return false;
-    if (V == 0) { *out = {0, false, 0}; return true; }
+    if (V == 0 || h->Z > h->d) { *out = {0, false, 0}; return true; }
     if (V != 1 && V != 2 && V != 4) return false;
     if (h->d % V) return false;
     const uint32_t G = h->d / V;
@@ -113,6 +115,7 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
     if (tuned_layout(bwd ? "ROBE_TUNE_BWD" : "ROBE_TUNE_FWD", h, &t)) {
         if (!t.consec || aligned(rows_ptr, 4 * (size_t)t.V)) return t;
     }
+    if (h->Z > h->d) return {0, false, 0};   // embeddings sharing a chunk: shape-generic kernel
     const int vs[3] = {4, 2, 1};
     if (!bwd) {
         // forward: widest per-lane load that stays inside one chunk

@@ -18,7 +18,8 @@ constexpr uint32_t kP = 2147483647u;
 struct Params {
     uint32_t m;        // array length, 1 <= m <= 2^31 - 1
     uint32_t m_recip;  // min(floor(2^32 / m), 2^32 - 1)
-    uint32_t d, Z, C;  // C = d / Z
+    uint32_t d, Z, C;  // C = d / Z chunks per embedding (1 when Z > d)
+    uint32_t r;        // Z / d embeddings per chunk when Z > d, else 0
     uint32_t Ah, Bh, Ch, Dh;
     uint32_t Ag, Bg, Cg, Dg;
 };

@@ -394,7 +394,11 @@ __global__ __launch_bounds__(kBlock) void generic_kernel(Params p, uint32_t F, u
         float acc = BWD ? src[row * (int64_t)p.d + i] : 0.0f;
         for (int64_t t = t0; t < t1; ++t) {
             const int64_t x = indices[t];
-            const uint32_t pos = wrap(offset_of(p, staged_h(p, x, e), cc) + j, p.m);
+            // Z > d (Section 3.3): r = Z/d embeddings share a chunk; the chunk id x / r takes the
+            // token's seat in h and the embedding starts (x mod r) * d places into the chunk
+            const int64_t key = p.r ? (int64_t)((uint64_t)x / p.r) : x;
+            const uint32_t place = p.r ? (uint32_t)((uint64_t)x % p.r) * p.d : 0u;
+            const uint32_t pos = wrap(offset_of(p, staged_h(p, key, e), cc) + j + place, p.m);
             const uint32_t msk = SIGN ? sign_mask(add_p(staged_g(p, x, e), cg)) : 0u;
             if constexpr (BWD) {
                 __hip_atomic_fetch_add(dst + pos, apply_sign(acc, msk), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -418,7 +422,13 @@ __global__ __launch_bounds__(kBlock) void offsets_kernel(Params p, uint32_t F, c
         const int64_t k = it / p.C;
         const uint32_t c = (uint32_t)(it - k * p.C);
         const uint32_t e = (uint32_t)(k % (int64_t)F);
-        out[it] = (int64_t)offset_of(p, staged_h(p, indices[k], e), mod_p((uint64_t)p.Ch * c));
+        const int64_t x = indices[k];
+        if (p.r) {  // Z > d: one entry per lookup, the place of element 0
+            const uint32_t place = (uint32_t)((uint64_t)x % p.r) * p.d;
+            out[it] = (int64_t)wrap(offset_of(p, staged_h(p, (int64_t)((uint64_t)x / p.r), e), 0u) + place, p.m);
+        } else {
+            out[it] = (int64_t)offset_of(p, staged_h(p, x, e), mod_p((uint64_t)p.Ch * c));
+        }
     }
 }
 

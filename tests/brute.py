@@ -43,6 +43,14 @@ def embedding(coef, P, M, d, Z, use_sign, e, x):
     return [g(coef, P, use_sign, e, x, i) * prim[i] for i in range(d)]
 
 
+def position_big_block(coef, P, m, d, Z, e, x, i):
+    """Z > d (Section 3.3, Appendix "ROBE-Z"): table e flattened row by row, cut into chunks of Z.
+    Element i of token x is entry n = x*d + i; its chunk n // Z is hashed (as the key, chunk number 0)
+    and it sits n % Z places into the chunk, circularly."""
+    n = (x & MASK64) * d + i
+    return (h(coef, P, m, e, n // Z, 0) + n % Z) % m
+
+
 def position_map(coef, P, m, d, Z, e, x):
     """Array slot of every element of E_e(x): the embedding of the array M[j] = j."""
     return embedding(coef, P, list(range(m)), d, Z, 0, e, x)

@@ -136,6 +136,27 @@ def test_z_equal_d_is_one_circular_slice():
         assert [oracle.idx(H, e, x, i) for i in range(16)] == [(start + i) % H.m for i in range(16)]
 
 
+def test_block_larger_than_embedding_follows_the_flattened_table():
+    # Z > d (Section 3.3): the flattened table cut into chunks of Z; r = Z/d embeddings share a chunk
+    rnd = random.Random(9)
+    for (m, d, Z) in [(1000, 4, 16), (37, 4, 16), (32, 8, 32), (100_003, 16, 64), (4099, 8, 24), (50, 1, 7)]:
+        H = oracle.init_hash(m + Z, m, d, Z, 0)
+        r = Z // d
+        for x in [0, 1, r - 1, r, r + 1, 12345, 2**40 + 3, 2**63 - 1, -1] + [rnd.randrange(0, 10**7) for _ in range(40)]:
+            e = rnd.randrange(0, 26)
+            got = [oracle.idx(H, e, x, i) for i in range(d)]
+            assert got == [brute.position_big_block(H.coef, P, m, d, Z, e, x, i) for i in range(d)]
+            assert got == [(got[0] + i) % m for i in range(d)]          # an embedding stays contiguous
+        # tokens of one chunk lie side by side, d apart; the next chunk starts somewhere else
+        base = [oracle.idx(H, 3, r * 5 + k, 0) for k in range(r)]
+        assert base == [(base[0] + k * d) % m for k in range(r)]
+    H = oracle.init_hash(1, 1000, 4, 16, 0)
+    flat = np.array([5, 6, 7, 8, 9], dtype=np.int64)
+    off = oracle.offsets(H, flat, 2)
+    assert off.shape == (5, 1)
+    assert off[:, 0].tolist() == [oracle.idx(H, k % 2, int(flat[k]), 0) for k in range(5)]
+
+
 def test_batched_offsets_and_signs_agree_with_scalar_calls():
     H = oracle.init_hash(21, 25_000_000, 128, 32, 1)
     rnd = np.random.default_rng(0)

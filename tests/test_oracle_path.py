@@ -107,6 +107,28 @@ def test_forward_and_backward_equal_the_sketching_matrix(seed, m, d, Z, sign):
     assert abs(lhs - float(M.astype(np.float64) @ ga)) <= 1e-9 * (1 + abs(lhs))
 
 
+def test_forward_and_backward_with_blocks_larger_than_the_embedding():
+    # Z > d: forward reads the brute-force positions, backward is its transpose
+    B, F, m, d, Z = 4, 3, 211, 4, 16
+    for sign in (0, 1):
+        H = oracle.init_hash(5 + sign, m, d, Z, sign)
+        rng = np.random.default_rng(sign)
+        ids = rng.integers(0, 40, size=(B, F))
+        M = rng.standard_normal(m).astype(np.float32)
+        out = oracle.forward(H, M, ids, None, B, F)
+        S = np.zeros((B * F * d, m))
+        for b in range(B):
+            for f in range(F):
+                for i in range(d):
+                    pos = brute.position_big_block(H.coef, P, m, d, Z, f, int(ids[b, f]), i)
+                    sg = brute.g(H.coef, P, sign, f, int(ids[b, f]), i)
+                    S[(b * F + f) * d + i, pos] = sg
+                    assert out[b, f, i] == np.float32(sg) * M[pos]
+        G = rng.standard_normal((B, F, d)).astype(np.float32)
+        ga, _ = oracle.backward(H, G, ids, None, B, F)
+        np.testing.assert_allclose(ga, S.T @ G.astype(np.float64).ravel(), rtol=1e-13, atol=1e-13)
+
+
 def test_single_hot_backward_equals_transposed_jacobian():
     B, F, m, d, Z = 5, 3, 53, 8, 4
     H = oracle.init_hash(77, m, d, Z, 1)
