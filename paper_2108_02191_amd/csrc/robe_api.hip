@@ -1,5 +1,18 @@
 // C ABI of the ROBE-Z library (see include/robe.h): argument validation,
-// launch geometry and kernel selection.  All device work is in robe_kernels.h.
+// launch geometry and kernel selection.  All device work is in robe_kernels.h
+// and robe_backward_dedup.h.
+//
+// Tuning knobs, read from the environment at call time (for experiments and for
+// tests that must reach every kernel variant; the defaults are the measured
+// best choices):
+//   ROBE_TUNE_FWD, ROBE_TUNE_BWD = "V,consec"   lane layout: V in {1,2,4} elements per lane,
+//                                               consec 1 = consecutive elements of one chunk,
+//                                               0 = strided; "0,0" = shape-generic kernel
+//   ROBE_TUNE_TL                                 lookups per wavefront tile (single-hot kernels)
+//   ROBE_TUNE_XCD = 0 | 1 | 2                    row order: memory order / table by table per XCD /
+//                                               the latter even for tiny launches
+//   ROBE_TUNE_BWD_MODE = direct | dedup          backward scatter strategy
+//   ROBE_TUNE_KEY_BITS = 8..31                   key bits the backward sort looks at
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -134,7 +147,7 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
     return {0, false, 0};
 }
 
-int env_flag(const char *name, int dflt)
+int env_int(const char *name, int dflt)
 {
     const char *v = getenv(name);
     return v ? atoi(v) : dflt;
@@ -184,7 +197,7 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
     // lookups with larger blocks the row writes dominate and the memory order is slightly faster.
     // The direct backward scatter keeps the memory order too: table by table, the copies of a frequent
     // token arrive close together in time and their same-address atomics serialise (measured 30 % slower).
-    const int xcd_mode = env_flag("ROBE_TUNE_XCD", (!BWD && (bags || h->Z * 4 <= 64)) ? 1 : 0);   // 2: even for tiny launches
+    const int xcd_mode = env_int("ROBE_TUNE_XCD", (!BWD && (bags || h->Z * 4 <= 64)) ? 1 : 0);   // 2: even for tiny launches
     if (F >= 2 && ((xcd_mode == 1 && blocks >= 64) || xcd_mode == 2)) {
         q.bpx = (uint32_t)((blocks + robe::kXcds - 1) / robe::kXcds);
         blocks = (int64_t)q.bpx * robe::kXcds;
@@ -231,12 +244,6 @@ struct BwdPlan {
     uint32_t key_bits;   // most significant key bits the sort looks at
     size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_tok_bag, off_temp, temp_bytes, bytes;
 };
-
-int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

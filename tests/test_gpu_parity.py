@@ -339,6 +339,29 @@ def test_row_walk_orders_cover_every_row_once(B, F, xcd, monkeypatch):
             assert np.array_equal(ga.cpu().numpy().astype(np.float64), want)
 
 
+def test_empty_problems_and_all_empty_bags():
+    h, H = both_hashes(8, 10_007, 16, 4, 1)
+    M = to_dev(workloads.make_array(10_007, 0))
+    F = 3
+    # batch 0: nothing launched, nothing touched
+    out0 = robe.robe_forward(h, M, torch.empty((0, F), dtype=torch.int64, device=DEV), None, 0, F)
+    assert out0.shape == (0, F, 16)
+    ga = torch.full((10_007,), 2.0, dtype=torch.float32, device=DEV)
+    robe.robe_backward(h, torch.empty((0, F, 16), device=DEV), torch.empty((0, F), dtype=torch.int64, device=DEV),
+                       None, 0, F, ga)
+    assert bool((ga == 2.0).all())
+    # rows exist but every bag is empty: zeros out, gradient array untouched, no index buffer needed
+    B = 5
+    off = torch.zeros(B * F + 1, dtype=torch.int64, device=DEV)
+    none = torch.empty(0, dtype=torch.int64, device=DEV)
+    out = robe.robe_forward(h, M, none, off, B, F)
+    assert not out.cpu().numpy().any() and not np.signbit(out.cpu().numpy()).any()
+    robe.robe_backward(h, torch.ones((B, F, 16), device=DEV), none, off, B, F, ga)
+    assert bool((ga == 2.0).all())
+    rc = robe.lib().robe_forward(ctypes.byref(h), M.data_ptr(), None, off.data_ptr(), 0, B, F, out.data_ptr(), None)
+    assert rc == robe.ROBE_OK
+
+
 def test_malformed_csr_is_clamped_not_followed():
     # every bag's bounds are clamped to [0, n_indices] on their own and a negative length becomes empty
     h, H = both_hashes(1, 10_007, 16, 4, 0)
