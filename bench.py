@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0: as defined)")
     ap.add_argument("--m", type=int, default=0, help="override the array length in floats (0: as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="time robe_backward and robe_adagrad_update as separate calls inside the step "
+                         "(default: the fused robe_backward_adagrad; the separate calls are then timed beside it)")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
     ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
     ap.add_argument("--copy-calib-mb", type=int, default=0,
@@ -53,7 +56,7 @@ def algorithmic_bytes(w, rows, tokens, touched):
     bwd = rows * vec + tokens * (2 * vec + 8) + (rows + 1) * 8 * bags
     ada = touched * 24          # read g, s, M; write s, M, g = 0
     sgd = touched * 16          # read g, M; write M, g = 0
-    return {"fwd": fwd, "bwd": bwd, "adagrad": ada, "sgd": sgd}
+    return {"fwd": fwd, "bwd": bwd, "adagrad": ada, "sgd": sgd, "bwd_adagrad": bwd + ada}
 
 
 def measured_traffic(workload, kernel):
@@ -164,7 +167,9 @@ def main():
     ga = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_bwd else None
     st = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_ada else None
     ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n) for n in tokens) if do_bwd else 0
-    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev) if ws_bytes else None
+    fused = do_ada and not args.unfused
+    fws_bytes = max(robe.robe_fused_workspace_bytes(h, B, F, n) for n in tokens) if fused else 0
+    ws = torch.empty(max(ws_bytes, fws_bytes, 1), dtype=torch.uint8, device=dev) if max(ws_bytes, fws_bytes) else None
 
     stream = torch.cuda.current_stream()
 
@@ -175,7 +180,11 @@ def main():
         robe.robe_forward(h, Md, idd, offd, B, F, out=out)
         if ev:
             ev[1].record(stream)
-        if do_bwd:
+        if fused:
+            robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Md, st, w.lr, w.eps, workspace=ws)
+            if ev:
+                ev[3].record(stream)
+        elif do_bwd:
             robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
             if ev:
                 ev[2].record(stream)
@@ -218,15 +227,31 @@ def main():
     elapsed = time.perf_counter() - t0
 
     ms_per_step = 1e3 * elapsed / args.steps
-    k_ms = {"fwd": [], "bwd": [], "adagrad": [], "sgd": []}
+    k_ms = {"fwd": [], "bwd": [], "adagrad": [], "sgd": [], "bwd_adagrad": []}
     for ev in events:
         k_ms["fwd"].append(ev[0].elapsed_time(ev[1]))
-        if do_bwd:
+        if fused:
+            k_ms["bwd_adagrad"].append(ev[1].elapsed_time(ev[3]))
+        elif do_bwd:
             k_ms["bwd"].append(ev[1].elapsed_time(ev[2]))
             if do_ada:
                 k_ms["adagrad"].append(ev[2].elapsed_time(ev[3]))
             if do_sgd:
                 k_ms["sgd"].append(ev[2].elapsed_time(ev[3]))
+    if fused:
+        # the two separate entry points, timed beside the fused step (not part of the timed steps)
+        for k in range(3 + 5):
+            idd, offd = dev_batches[k % len(dev_batches)]
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(stream)
+            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
+            e[1].record(stream)
+            robe.robe_adagrad_update(h, Md, st, ga, w.lr, w.eps)
+            e[2].record(stream)
+            torch.cuda.synchronize()
+            if k >= 3:
+                k_ms["bwd"].append(e[0].elapsed_time(e[1]))
+                k_ms["adagrad"].append(e[1].elapsed_time(e[2]))
     avg = {k: (sum(v) / len(v) if v else 0.0) for k, v in k_ms.items()}
     tok = sum(tokens[k % len(tokens)] for k in range(args.steps)) / args.steps
     alg = algorithmic_bytes(w, rows, tok, touched)
@@ -235,27 +260,37 @@ def main():
         return tok / (ms * 1e-3) if ms > 0 else None
 
     kernels = {}
-    for name in ("fwd", "bwd", "adagrad", "sgd"):
+    for name in ("fwd", "bwd", "adagrad", "sgd", "bwd_adagrad"):
         if avg[name] > 0:
             gbs = alg[name] / (avg[name] * 1e-3) / 1e9
             kernels[name] = {"ms": round(avg[name], 4), "algorithmic_GB": round(alg[name] / 1e9, 4),
                              "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
-    dominant = max(kernels, key=lambda n: kernels[n]["ms"])
+    in_step = [n for n in kernels if not (fused and n in ("bwd", "adagrad"))]
+    dominant = max(in_step, key=lambda n: kernels[n]["ms"])
     phases = {"fwd": {"ms": round(avg["fwd"], 4), "lookups_per_s": rate(avg["fwd"])}}
     if do_bwd:
         phases["fwd_bwd"] = {"ms": round(avg["fwd"] + avg["bwd"], 4), "lookups_per_s": rate(avg["fwd"] + avg["bwd"])}
-    if do_ada or do_sgd:
+    if fused:
+        t_all = avg["fwd"] + avg["bwd_adagrad"]
+        phases["fwd_bwd_adagrad"] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all),
+                                      "how": "robe_forward + fused robe_backward_adagrad"}
+        t_sep = avg["fwd"] + avg["bwd"] + avg["adagrad"]
+        phases["fwd_bwd_adagrad_separate_calls"] = {"ms": round(t_sep, 4), "lookups_per_s": rate(t_sep)}
+    elif do_ada or do_sgd:
         opt = "adagrad" if do_ada else "sgd"
         t_all = avg["fwd"] + avg["bwd"] + avg[opt]
         phases["fwd_bwd_" + opt] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all)}
-    total_alg = sum(alg[n] for n in kernels)
+    total_alg = sum(alg[n] for n in in_step)
     # the timed unit of each phase is one entry-point call; backward is several kernels when it sorts
     entry_names = {"fwd": "robe_forward", "adagrad": "robe_adagrad_update", "sgd": "robe_sgd_update",
+                   "bwd_adagrad": "robe_backward_adagrad (token_keys + radix sort + combine_rows + region count/scan/"
+                                  "records + region_reduce kernels)",
                    "bwd": "robe_backward (" + ("token_keys + radix sort + combine_scatter kernels" if ws_bytes
                                                else "direct scatter kernel") + ")"}
     result = {
         "metric": "ROBE lookups/sec, whole step (fwd%s%s), d=%d, Z=%d" % (
-            "+bwd" if do_bwd else "", "+Adagrad" if do_ada else ("+SGD" if do_sgd else ""), w.d, w.Z),
+            "+bwd" if do_bwd else "", "+Adagrad" if do_ada else ("+SGD" if do_sgd else ""), w.d, w.Z)
+                  + (" [backward and Adagrad fused]" if fused else ""),
         "value": tok / (ms_per_step * 1e-3),
         "unit": "lookups/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

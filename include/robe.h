@@ -179,6 +179,28 @@ int robe_adagrad_update(const robe_hash_t *hash, float *array, float *state, flo
  */
 int robe_sgd_update(const robe_hash_t *hash, float *array, float *grad_array, float lr, void *stream);
 
+/*
+ * Fused training step: backward scatter-add (Eq. 3) and the Adagrad update in one pass, for a
+ * gradient array that would otherwise start from zero.  The result is that of
+ *   robe_backward(..., grad_array = zeros, ...) followed by robe_adagrad_update(array, state, grad_array)
+ * to the same rounding caveats, but for large problems the gradient never exists in device memory:
+ * the blocks are sorted by destination, every region of the array is summed in LDS by the one
+ * workgroup that owns it, and that workgroup updates array and state directly.  Slots that receive
+ * no gradient are left bit-for-bit unchanged.
+ *   array, state   device float[m], updated in place
+ *   workspace      device buffer of at least robe_fused_workspace_bytes(...) bytes, 256-byte aligned
+ *                  (it holds the sort buffers, the summed rows of repeated tokens and the block
+ *                  records; for problems too small or shapes too odd for the sorted path it holds
+ *                  a gradient array instead and the two steps run one after the other)
+ * Errors: ROBE_EINVAL (null pointers, eps <= 0, non-finite lr/eps, workspace too small), ROBE_EHIP.
+ * Like robe_backward it should not be captured into a HIP graph.
+ */
+size_t robe_fused_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices);
+int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
+                          const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                          int64_t batch, int32_t n_features, float *array, float *state,
+                          float lr, float eps, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Text of the calling thread's most recent error ("" if none).  Never NULL. */
 const char *robe_last_error(void);
 

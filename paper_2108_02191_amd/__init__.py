@@ -45,7 +45,8 @@ class RobeHash(ctypes.Structure):
 
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
-           "robe_adagrad_update", "robe_sgd_update", "robe_last_error")
+           "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
+           "robe_last_error")
 
 _lib = None
 
@@ -74,6 +75,11 @@ def lib() -> ctypes.CDLL:
         L.robe_adagrad_update.argtypes = [HP, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp]
         L.robe_sgd_update.restype = ctypes.c_int
         L.robe_sgd_update.argtypes = [HP, vp, vp, ctypes.c_float, vp]
+        L.robe_fused_workspace_bytes.restype = ctypes.c_size_t
+        L.robe_fused_workspace_bytes.argtypes = [HP, i64, i32, i64]
+        L.robe_backward_adagrad.restype = ctypes.c_int
+        L.robe_backward_adagrad.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_float, ctypes.c_float,
+                                            vp, ctypes.c_size_t, vp]
         L.robe_last_error.restype = ctypes.c_char_p
         L.robe_last_error.argtypes = []
         _lib = L
@@ -171,3 +177,29 @@ def robe_sgd_update(h: RobeHash, array: torch.Tensor, grad_array: torch.Tensor, 
             raise ValueError(f"{name} length differs from hash.m")
     _check(lib().robe_sgd_update(ctypes.byref(h), _dev(array, torch.float32, "array"),
                                  _dev(grad_array, torch.float32, "grad_array"), lr, _stream()))
+
+
+def robe_fused_workspace_bytes(h: RobeHash, batch: int, n_features: int, n_indices: int) -> int:
+    return int(lib().robe_fused_workspace_bytes(ctypes.byref(h), batch, n_features, n_indices))
+
+
+def robe_backward_adagrad(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                          batch: int, n_features: int, array: torch.Tensor, state: torch.Tensor,
+                          lr: float, eps: float, workspace: Optional[torch.Tensor] = None) -> None:
+    """Backward scatter-add and Adagrad update in one call (array and state updated in place)."""
+    for t, name in ((array, "array"), (state, "state")):
+        if t.numel() != h.m:
+            raise ValueError(f"{name} length differs from hash.m")
+    if grad_out.numel() != batch * n_features * h.d:
+        raise ValueError("grad_out has the wrong size")
+    if offsets is not None and offsets.numel() != batch * n_features + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    need = robe_fused_workspace_bytes(h, batch, n_features, indices.numel())
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=array.device)
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_len = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().robe_backward_adagrad(ctypes.byref(h), _dev(grad_out, torch.float32, "grad_out"),
+                                       _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                                       indices.numel(), batch, n_features, _dev(array, torch.float32, "array"),
+                                       _dev(state, torch.float32, "state"), lr, eps, ws_ptr, ws_len, _stream()))

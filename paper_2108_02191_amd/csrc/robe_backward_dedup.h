@@ -23,16 +23,7 @@
 
 namespace robe {
 
-constexpr uint32_t kNoToken = 0xFFFFFFFFu;
 constexpr int kRowsInFlight = 8;   // gradient rows a lane group loads before it adds them
-
-__global__ __launch_bounds__(256) void fill_pairs_kernel(uint32_t *keys, uint32_t *vals, uint32_t n)
-{
-    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) {
-        keys[i] = 0x7FFFFFFFu;   // sorts last
-        vals[i] = kNoToken;
-    }
-}
 
 // S1.  Bags: a group of G lanes per bag, grid-stride over bags; single-hot: one lane per lookup.
 template <bool BAGS>

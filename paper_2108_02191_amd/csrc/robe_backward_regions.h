@@ -1,0 +1,479 @@
+// Backward scatter-add (Eq. 3 of the paper) with no float atomics at all, and the fused
+// backward + Adagrad step built on it.
+//
+// After the tokens are sorted by key (robe_backward_dedup.h, S1 and S2):
+//
+//   R1 combine   a group of G lanes walks G consecutive sorted tokens.  A run of identical tokens
+//                that is longer than one gets its gradient rows summed into a row of the scratch
+//                matrix P; a run of one just points at its row of grad_out.  Every run leaves a
+//                record at its first sorted position: a head flag, the key, the source row.
+//   R2 count     every run's d/Z blocks are hashed to their array offsets; the array is cut into
+//                regions of 2^r_shift floats; each workgroup histograms its share of the blocks per
+//                region in LDS and adds the counts to a global table.  A block that runs past the
+//                end of its region (or of the array) counts in both regions it touches.
+//   R3 scan      exclusive prefix sum: first record slot of every region.
+//   R4 scatter   same walk as R2; a workgroup reserves its slots of every region with one integer
+//                atomic per region and writes (offset, source block [, sign term]) records.
+//   R5 reduce    one workgroup per region: the region's records are applied to an LDS copy of the
+//                region with plain read-modify-writes - float atomics in LDS are as slow as those
+//                in memory - made race-free by ownership: the region is cut into one slice per lane
+//                group, a batch of records is counting-sorted by slice with integer atomics, every
+//                group applies the records that start in its slice, and the elements that reach past
+//                a slice's end are applied after a barrier.  The finished region is then added to
+//                grad_array with coalesced plain read-modify-writes - or, fused, fed straight into
+//                the Adagrad update of array and state, so that the gradient never exists in HBM.
+//
+// Every array slot is owned by exactly one workgroup, so nothing here is atomic on floats.  The order
+// of the additions inside a region follows the order of its records, which is not fixed.
+#pragma once
+#include "robe_kernels.h"
+
+namespace robe {
+
+constexpr int kRowsAhead = 8;          // gradient rows a lane group requests before adding them (R1)
+constexpr int kBinBlock = 1024;        // R2 / R4
+constexpr int kReduceBlock = 512;      // R5 (the slice arithmetic assumes 2^9)
+constexpr int kRecBatch = 896;         // records sorted and applied per round in R5 (at most 2 per thread);
+                                       // 32 KB region + batch + counters stay under 40 KB: four workgroups per CU
+constexpr int kRecAhead = 8;           // gradient blocks a lane group requests before adding them (R5)
+constexpr int kWb = 1;                 // vectors per thread and pass in the write-back of R5 (more did not pay: registers)
+constexpr uint32_t kMaxRegions = 32768;
+constexpr uint32_t kPartBit = 0x80000000u;   // record flag: the elements past the end of the block's own region
+constexpr uint32_t kDeadRecord = 0xFFFFFFFFu;
+
+struct RegionPlan {
+    uint32_t r_shift;        // log2 of the region size in floats
+    uint32_t NR;             // regions = ceil(m / 2^r_shift)
+    uint32_t n;              // sorted token positions
+    uint32_t rows;           // rows of grad_out
+    uint32_t src_blocks;     // (rows + P rows) * C: exclusive bound of a record's source block
+    uint32_t bin_blocks;     // grid of R2 / R4
+    uint32_t pos_per_block;  // sorted positions per workgroup in R2 / R4
+    uint32_t lg_shift;       // log2 of the lanes per record in R5
+    const uint32_t *keys;    // sorted keys
+    uint8_t *head;           // [n]  1: a run starts here
+    uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
+    uint32_t *run_tg;        // [n]  at run starts: token part of the sign hash (sign on only)
+    float *P;                // [(n + 1) / 2][d] summed rows of the runs longer than one
+    uint32_t *counts, *starts, *cursors;   // [NR], [NR + 1], [NR]
+    uint2 *rec;              // [<= 2 * n * C] (offset, source block | part flag)
+    uint32_t *rec_tg;        // sign on only
+};
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *dst, uint32_t n, uint32_t v)
+{
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) dst[i] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// R1.  Lane layout as in the direct scatter: G lanes per row, lane `grp` owns elements grp + k*G.
+// ---------------------------------------------------------------------------------------------
+template <int V, bool SIGN, bool BAGS>
+__global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, RegionPlan s,
+                                                              const float *__restrict__ grad_out,
+                                                              const int64_t *__restrict__ indices,
+                                                              const uint32_t *__restrict__ vals,     // sorted with the keys
+                                                              const uint32_t *__restrict__ tok_bag)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t grp = lane & (q.G - 1u);
+    const uint32_t base_lane = lane - grp;
+    const uint64_t thread_id = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (thread_id - lane >= s.n) return;                // the whole wavefront is past the end
+    const uint32_t i0 = (uint32_t)(thread_id - grp);    // first sorted position of this group's stretch
+    const uint32_t n = s.n;
+
+    // lane l of the group looks at sorted position i0 + l
+    uint32_t my_th = 0, my_tg = 0, my_row = 0, my_e = 0;
+    int64_t my_x = 0;
+    bool my_ok = false;
+    if (i0 + grp < n) {
+        const uint32_t t = vals[i0 + grp];
+        if (t < n) {
+            const uint32_t row = BAGS ? tok_bag[t] : t;
+            if (row < s.rows) {
+                my_ok = true;
+                my_row = row;
+                my_x = indices[t];
+                my_e = row % q.F;
+                my_th = s.keys[i0 + grp];
+                if constexpr (SIGN) my_tg = staged_g(p, my_x, my_e);
+            }
+        }
+    }
+    // does a run start here (first of the stretch, or a different token than the one before),
+    // and does it end here (last of the stretch, or a different token after)?
+    const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
+    const uint32_t p_th = __shfl(my_th, prev), p_e = __shfl(my_e, prev);
+    const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
+    const bool p_ok = __shfl((int)my_ok, prev) != 0;
+    const bool my_head = my_ok && (grp == 0 || !p_ok || p_th != my_th || p_e != my_e ||
+                                   p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32));
+    const int next = (int)(base_lane + (grp + 1u < q.G ? grp + 1u : grp));
+    const bool n_head = __shfl((int)my_head, next) != 0, n_ok = __shfl((int)my_ok, next) != 0;
+    const bool my_end = my_ok && (grp + 1u >= q.G || !n_ok || n_head);
+    const bool my_single = my_head && my_end;
+
+    if (i0 + grp < n) {
+        s.head[i0 + grp] = my_head ? 1 : 0;
+        if (my_single) s.src_row[i0 + grp] = my_row;             // a run of one: read grad_out in place
+        if constexpr (SIGN) {
+            if (my_head) s.run_tg[i0 + grp] = my_tg;
+        }
+    }
+
+    // runs longer than one: sum their rows into P
+    float acc[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+    uint32_t head_pos = 0;
+    for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsAhead) {     // same trip count for every lane of the wavefront
+        uint32_t row[kRowsAhead];
+        bool use[kRowsAhead], head[kRowsAhead], end[kRowsAhead];
+#pragma unroll
+        for (int u = 0; u < kRowsAhead; ++u) {
+            const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
+            const bool in = k0 + u < q.G;
+            use[u] = in && __shfl((int)(my_ok && !my_single), from) != 0;
+            row[u] = __shfl(my_row, from);
+            head[u] = __shfl((int)my_head, from) != 0;
+            end[u] = __shfl((int)my_end, from) != 0;
+        }
+        float v[kRowsAhead][V];
+#pragma unroll
+        for (int u = 0; u < kRowsAhead; ++u) {
+            if (use[u]) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kRowsAhead; ++u) {
+            if (!use[u]) continue;
+            if (head[u]) {
+                head_pos = i0 + k0 + u;
+#pragma unroll
+                for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < V; ++k) acc[k] += v[u][k];
+            if (end[u]) {
+                // two runs longer than one start at least two positions apart: head_pos / 2 is unique
+                const uint32_t prow = head_pos >> 1;
+                store_row<V, false>(s.P + (uint64_t)prow * p.d, q, grp, acc);
+                if (grp == 0) s.src_row[head_pos] = s.rows + prow;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// R2 / R4.  Walk this workgroup's sorted positions; call f(offset, source block, region, part flag,
+// sign term) for every block of every run, twice when the block leaves its region.
+// ---------------------------------------------------------------------------------------------
+template <bool SIGN, typename F>
+__device__ __forceinline__ void for_each_block(const Params &p, const RegionPlan &s, F f)
+{
+    const uint64_t b = (uint64_t)blockIdx.x * s.pos_per_block;
+    uint64_t e = b + s.pos_per_block;
+    if (e > s.n) e = s.n;
+    for (uint64_t i = b + threadIdx.x; i < e; i += kBinBlock) {
+        if (!s.head[i]) continue;
+        const uint32_t th = s.keys[i];
+        const uint32_t src0 = s.src_row[i] * p.C;
+        const uint32_t tg = SIGN ? s.run_tg[i] : 0u;
+        uint32_t cc = 0;  // (Ch * c) mod P, built up by addition
+        for (uint32_t c = 0; c < p.C; ++c) {
+            const uint32_t o = offset_of(p, th, cc);
+            const uint32_t r = o >> s.r_shift;
+            f(o, src0 + c, r, 0u, tg);
+            const uint64_t r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
+            if ((uint64_t)o + p.Z > r_end) f(o, src0 + c, r_end == p.m ? 0u : r + 1u, kPartBit, tg);
+            cc = add_p(cc, p.Ch);
+        }
+    }
+}
+
+template <bool SIGN, bool SCATTER>
+__global__ __launch_bounds__(kBinBlock) void region_bin_kernel(Params p, RegionPlan s)
+{
+    extern __shared__ uint32_t hist[];  // NR counters
+    for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) hist[r] = 0;
+    __syncthreads();
+    for_each_block<false>(p, s, [&](uint32_t, uint32_t, uint32_t r, uint32_t, uint32_t) { atomicAdd(&hist[r], 1u); });
+    __syncthreads();
+    if constexpr (!SCATTER) {
+        for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) {
+            const uint32_t c = hist[r];
+            if (c) atomicAdd(&s.counts[r], c);
+        }
+    } else {
+        for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) {
+            const uint32_t c = hist[r];
+            hist[r] = c ? atomicAdd(&s.cursors[r], c) : 0u;  // first slot of this workgroup in region r
+        }
+        __syncthreads();
+        const uint32_t cap = s.starts[s.NR];                 // all records counted by R2
+        for_each_block<SIGN>(p, s, [&](uint32_t o, uint32_t src, uint32_t r, uint32_t part, uint32_t tg) {
+            const uint32_t slot = atomicAdd(&hist[r], 1u);
+            if (slot < cap) {  // always true unless the inputs changed between R2 and R4
+                s.rec[slot] = make_uint2(o, src | part);
+                if constexpr (SIGN) s.rec_tg[slot] = tg;
+            }
+        });
+    }
+}
+
+// R3: one workgroup.  starts / cursors: exclusive prefix of counts, grand total in starts[NR].
+constexpr uint32_t kScanPer = kMaxRegions / 1024u;   // regions per thread, all loaded before any is added
+
+__global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
+{
+    __shared__ uint32_t part[1024];
+    const uint32_t b = threadIdx.x * kScanPer;
+    uint32_t c[kScanPer];
+#pragma unroll
+    for (uint32_t k = 0; k < kScanPer; ++k) c[k] = b + k < s.NR ? s.counts[b + k] : 0u;
+    uint32_t sum = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < kScanPer; ++k) sum += c[k];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (uint32_t off = 1; off < 1024u; off <<= 1) {          // inclusive scan of the 1024 partial sums
+        const uint32_t add = threadIdx.x >= off ? part[threadIdx.x - off] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t a = part[threadIdx.x] - sum;                      // exclusive prefix of this thread's share
+#pragma unroll
+    for (uint32_t k = 0; k < kScanPer; ++k) {
+        if (b + k < s.NR) {
+            s.starts[b + k] = a;
+            s.cursors[b + k] = a;
+        }
+        a += c[k];
+    }
+    if (threadIdx.x == 1023) s.starts[s.NR] = part[1023];
+}
+
+// ---------------------------------------------------------------------------------------------
+// R5.  RULE 0: grad_array += region.  RULE 1: Adagrad on array / state with the region as gradient.
+// ---------------------------------------------------------------------------------------------
+template <bool SIGN>
+__device__ __forceinline__ float signed_block_value(const Params &p, float v, uint32_t tg, uint32_t src, uint32_t j)
+{
+    if constexpr (SIGN) {
+        const uint32_t el = (src % p.C) * p.Z + j;
+        return apply_sign(v, sign_mask(add_p(tg, mod_p((uint64_t)p.Cg * el))));
+    } else {
+        return v;
+    }
+}
+
+template <bool SIGN, int RULE>
+__global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void region_reduce_kernel(Params p, RegionPlan s,
+                                                                     const float *__restrict__ grad_out,
+                                                                     float *__restrict__ dst,      // RULE 0: grad_array; RULE 1: array
+                                                                     float *__restrict__ state,    // RULE 1 only
+                                                                     float lr, float eps, int vec_ok)
+{
+    extern __shared__ float acc[];  // 2^r_shift floats, then the batch staging area
+    const uint32_t r = blockIdx.x;
+    const uint32_t rb = s.starts[r], re = s.starts[r + 1];
+    if (rb >= re) return;           // nothing lands in this region: it is not touched at all
+
+    const uint32_t R = 1u << s.r_shift;
+    const uint32_t r0 = r << s.r_shift;
+    const uint32_t region_len = (p.m - r0) < R ? (p.m - r0) : R;
+    const uint32_t src_own = s.rows * p.C;   // source blocks below this live in grad_out, the rest in P
+
+    uint2 *srt = reinterpret_cast<uint2 *>(acc + R);
+    uint32_t *srt_tg = reinterpret_cast<uint32_t *>(srt + kRecBatch);
+    uint32_t *cnt = srt_tg + (SIGN ? kRecBatch : 0);   // 64 slice counters
+    uint32_t *pre = cnt + 64;                          // 65 slice starts
+
+    for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = 0.0f;
+
+    typedef Vec<4>::A V4;
+    const uint32_t nvec = vec_ok ? region_len / 4u : 0u;
+
+    const uint32_t LG = 1u << s.lg_shift;
+    const uint32_t j0 = threadIdx.x & (LG - 1u);
+    const uint32_t grp = threadIdx.x >> s.lg_shift;
+    const uint32_t grp_shift = 9u - s.lg_shift;               // log2(groups) for 512 threads
+    const uint32_t groups = 1u << grp_shift;
+    const uint32_t slice_shift = s.r_shift - grp_shift;       // the host guarantees 2^slice_shift >= Z
+    const uint32_t slice_end = (grp + 1u) << slice_shift;
+
+    // Elements of a record that this region (and this record's part) holds: element j sits at array
+    // position (o + j) mod m; part 0 keeps the elements before the end of o's own region, part 1 the
+    // rest, which continue at the start of the next region (or of the array).
+    auto own_end = [&](uint32_t o) -> uint32_t {              // end of the region that holds offset o
+        const uint64_t e = ((uint64_t)((o >> s.r_shift) + 1u)) << s.r_shift;
+        return e < p.m ? (uint32_t)e : p.m;
+    };
+
+    for (uint32_t bb = rb; bb < re; bb += kRecBatch) {
+        const uint32_t nb = re - bb < (uint32_t)kRecBatch ? re - bb : (uint32_t)kRecBatch;
+        if (threadIdx.x < groups) cnt[threadIdx.x] = 0;
+        __syncthreads();   // also orders the previous round's second pass before this round's writes
+
+        // 1. each thread takes two records, finds their slice and their rank inside it
+        uint2 rc[2];
+        uint32_t tgv[2], sl[2], rk[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint32_t k = threadIdx.x + (uint32_t)t * kReduceBlock;
+            rc[t] = make_uint2(kDeadRecord, 0u);
+            tgv[t] = 0;
+            sl[t] = 0;
+            rk[t] = 0;
+            if (k < nb) {
+                const uint2 x = s.rec[bb + k];
+                const uint32_t o = x.x, src = x.y & ~kPartBit;
+                const bool part1 = (x.y & kPartBit) != 0;
+                // where the record's first element of this part lands; anything else cannot occur
+                // with consistent inputs and is dropped
+                const uint32_t first = part1 ? own_end(o) % p.m : o;
+                if (o < p.m && src < s.src_blocks && (first >> s.r_shift) == r) {
+                    rc[t] = x;
+                    if constexpr (SIGN) tgv[t] = s.rec_tg[bb + k];
+                    sl[t] = (first - r0) >> slice_shift;
+                    rk[t] = atomicAdd(&cnt[sl[t]], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t a = 0;
+            for (uint32_t g = 0; g < groups; ++g) {
+                pre[g] = a;
+                a += cnt[g];
+            }
+            pre[groups] = a;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (rc[t].x != kDeadRecord) {
+                const uint32_t at = pre[sl[t]] + rk[t];
+                srt[at] = rc[t];
+                if constexpr (SIGN) srt_tg[at] = tgv[t];
+            }
+        }
+        __syncthreads();
+
+        // 2. every group applies the records that start in its slice, kRecAhead loads in flight;
+        //    elements at or past the slice end wait for pass 3
+        const uint32_t lb = pre[grp], le = pre[grp + 1];
+        for (uint32_t k0 = lb; k0 < le; k0 += kRecAhead) {
+            uint32_t o[kRecAhead], src[kRecAhead], tg[kRecAhead], oend[kRecAhead];
+            bool live[kRecAhead], part1[kRecAhead];
+#pragma unroll
+            for (int u = 0; u < kRecAhead; ++u) {
+                live[u] = k0 + u < le;
+                const uint32_t k = live[u] ? k0 + u : lb;
+                const uint2 x = srt[k];
+                o[u] = x.x;
+                src[u] = x.y & ~kPartBit;
+                part1[u] = (x.y & kPartBit) != 0;
+                oend[u] = own_end(x.x);
+                tg[u] = SIGN ? srt_tg[k] : 0u;
+            }
+            for (uint32_t j = j0; j < p.Z; j += LG) {
+                float v[kRecAhead];
+#pragma unroll
+                for (int u = 0; u < kRecAhead; ++u) {
+                    const float *base = src[u] < src_own ? grad_out + (uint64_t)src[u] * p.Z
+                                                         : s.P + (uint64_t)(src[u] - src_own) * p.Z;
+                    v[u] = __builtin_nontemporal_load(base + j);
+                }
+#pragma unroll
+                for (int u = 0; u < kRecAhead; ++u) {
+                    const bool in_part = (o[u] + j < oend[u]) != part1[u];
+                    const uint32_t a = wrap(o[u] + j, p.m) - r0;
+                    if (live[u] && in_part && a < slice_end && a < region_len)
+                        acc[a] += signed_block_value<SIGN>(p, v[u], tg[u], src[u], j);
+                }
+            }
+        }
+        __syncthreads();
+
+        // 3. elements past the slice end: the next slice's first Z-1 floats, which nobody else writes now
+        for (uint32_t k = lb; k < le; ++k) {
+            const uint2 x = srt[k];
+            if (x.y & kPartBit) continue;                       // a part-1 record starts its slice: never past its end
+            const uint32_t o = x.x, src = x.y;
+            if (o - r0 + p.Z <= slice_end) continue;
+            const uint32_t oend = own_end(o);
+            const uint32_t tgk = SIGN ? srt_tg[k] : 0u;
+            const float *base = src < src_own ? grad_out + (uint64_t)src * p.Z : s.P + (uint64_t)(src - src_own) * p.Z;
+            for (uint32_t j = j0; j < p.Z; j += LG) {
+                const uint32_t a = o + j - r0;
+                if (o + j < oend && a >= slice_end && a < region_len)
+                    acc[a] += signed_block_value<SIGN>(p, base[j], tgk, src, j);
+            }
+        }
+    }
+    __syncthreads();
+
+    // The region is complete and this workgroup is the only one that holds any of its slots.
+    // kWb vectors per thread and pass: all their loads are requested before the first is used.
+    const uint32_t lane = threadIdx.x & 63u;
+    for (uint32_t it0 = 0; it0 < nvec; it0 += kWb * kReduceBlock) {   // same trip count for the whole workgroup
+        V4 g[kWb], w[kWb], st[kWb];
+        bool touch[kWb];
+#pragma unroll
+        for (int u = 0; u < kWb; ++u) {
+            const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) g[u][k] = 0.0f;
+            if (it < nvec) g[u] = *reinterpret_cast<const V4 *>(&acc[4u * it]);
+            const bool any = g[u][0] != 0.0f || g[u][1] != 0.0f || g[u][2] != 0.0f || g[u][3] != 0.0f;
+            // decide per 64-byte granule (4 lanes): partially written granules cost more than they save
+            const uint64_t gran_any = (__ballot(any) >> (lane & ~3u)) & 0xFull;
+            touch[u] = it < nvec && gran_any != 0;
+        }
+#pragma unroll
+        for (int u = 0; u < kWb; ++u) {
+            if (touch[u]) {
+                const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
+                w[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
+                if constexpr (RULE == 1) st[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(state + r0 + 4u * it));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kWb; ++u) {
+            if (!touch[u]) continue;
+            const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
+            if constexpr (RULE == 0) {
+                w[u] += g[u];
+                __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (g[u][k] != 0.0f) {
+                        float wk = w[u][k], sk = st[u][k];
+                        adagrad_one(wk, sk, g[u][k], lr, eps);
+                        w[u][k] = wk;
+                        st[u][k] = sk;
+                    }
+                }
+                __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+                __builtin_nontemporal_store(st[u], reinterpret_cast<V4 *>(state + r0 + 4u * it));
+            }
+        }
+    }
+    for (uint32_t i = 4u * nvec + threadIdx.x; i < region_len; i += kReduceBlock) {   // tail, or unaligned buffers
+        const float g = acc[i];
+        if (g == 0.0f) continue;
+        if constexpr (RULE == 0) {
+            dst[r0 + i] += g;
+        } else {
+            float wk = dst[r0 + i], sk = state[r0 + i];
+            adagrad_one(wk, sk, g, lr, eps);
+            dst[r0 + i] = wk;
+            state[r0 + i] = sk;
+        }
+    }
+}
+
+}  // namespace robe

@@ -70,6 +70,10 @@ def test_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.robe_adagrad_update(ref, None, fake, fake, 0.01, 1e-8, None) == EINVAL
     assert L.robe_adagrad_update(ref, fake, fake, fake, 0.01, 0.0, None) == EINVAL
     assert L.robe_adagrad_update(ref, fake, fake, fake, float("nan"), 1e-8, None) == EINVAL
+    assert L.robe_backward_adagrad(ref, fake, fake, None, 4, 2, 2, None, fake, 0.01, 1e-8, None, 0, None) == EINVAL
+    assert L.robe_backward_adagrad(ref, fake, fake, None, 4, 2, 2, fake, fake, 0.01, -1.0, None, 0, None) == EINVAL
+    assert L.robe_backward_adagrad(ref, fake, fake, None, 4, 2, 2, fake, fake, 0.01, 1e-8, None, 0, None) == EINVAL  # no workspace
+    assert b"workspace" in L.robe_last_error()
     assert L.robe_sgd_update(ref, None, fake, 1.0, None) == EINVAL
     assert L.robe_sgd_update(ref, fake, fake, float("inf"), None) == EINVAL
     assert L.robe_offsets(ref, None, 3, 2, fake, None, None) == EINVAL

@@ -158,7 +158,7 @@ def check_backward(h, H, G, ids, off, B, F):
     return got, want
 
 
-@pytest.mark.parametrize("mode", ["direct", "dedup"])
+@pytest.mark.parametrize("mode", ["direct", "dedup", "regions"])
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,d,Z", SHAPES[:-1])
 def test_backward_single_hot_and_bags(m, d, Z, sign, mode, monkeypatch):
@@ -178,7 +178,7 @@ def test_backward_single_hot_and_bags(m, d, Z, sign, mode, monkeypatch):
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("mode", ["direct", "dedup"])
+@pytest.mark.parametrize("mode", ["direct", "dedup", "regions"])
 def test_backward_accumulates_onto_existing_values(mode, monkeypatch):
     monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
     h, H = both_hashes(2, 50_021, 16, 4, 0)
@@ -193,12 +193,16 @@ def test_backward_accumulates_onto_existing_values(mode, monkeypatch):
     assert np.array_equal(ga.cpu().numpy().astype(np.float64), 5.0 + 2 * want)
 
 
+@pytest.mark.parametrize("mode,rshift", [("dedup", 0), ("regions", 0), ("regions", 10), ("regions", 15)])
 @pytest.mark.parametrize("key_bits", [31, 16, 8])
 @pytest.mark.parametrize("sign", [0, 1])
-def test_dedup_backward_hot_tokens_and_key_collisions(key_bits, sign, monkeypatch):
+def test_dedup_backward_hot_tokens_and_key_collisions(key_bits, sign, mode, rshift, monkeypatch):
     # one token repeated thousands of times (runs far longer than a lane group's stretch), a coarse
-    # sort key so that distinct tokens share keys and interleave, blocks that wrap, unaligned grad_array
-    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", "dedup")
+    # sort key so that distinct tokens share keys and interleave, blocks that wrap or leave their
+    # region, unaligned grad_array; with float atomics and with the region-sorted scatter
+    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
+    if rshift:
+        monkeypatch.setenv("ROBE_TUNE_RSHIFT", str(rshift))
     monkeypatch.setenv("ROBE_TUNE_KEY_BITS", str(key_bits))
     m, d, Z, B, F = 100_003, 64, 32, 301, 7
     h, H = both_hashes(31 + key_bits, m, d, Z, sign)
@@ -285,6 +289,74 @@ def test_sgd_matches_oracle_and_leaves_untouched_slots_alone(m, shift):
     assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(M0) + np.abs(g0)) + TINY)
     # with lr = 1 the product is exact, so the result is the correctly rounded difference: bit-exact
     assert bits_equal(Mg, Mo)
+
+
+def _check_fused(h, H, Gi, ids, off, B, F, m, shift=0):
+    """Fused backward + Adagrad against oracle.backward -> oracle.adagrad.  Small-integer gradients
+    make every slot's sum exact, so both sides feed the same gradient to the update."""
+    rng = np.random.default_rng(m + B)
+    M0 = rng.standard_normal(m).astype(np.float32)
+    s0 = (rng.random(m) * (rng.random(m) < 0.5)).astype(np.float32)
+    def dev_view(a):
+        buf = torch.zeros(m + shift, dtype=torch.float32, device=DEV)
+        view = buf[shift:]
+        view.copy_(torch.from_numpy(a))
+        return view
+    Md, sd = dev_view(M0), dev_view(s0)
+    robe.robe_backward_adagrad(h, to_dev(Gi), to_dev(ids), to_dev(off), B, F, Md, sd, 0.01, 1e-8)
+    g, _ = oracle.backward(H, Gi, ids, off, B, F)
+    assert np.array_equal(g, np.round(g))
+    Mo, so, go = M0.copy(), s0.copy(), g.astype(np.float32)
+    oracle.adagrad(Mo, so, go, 0.01, 1e-8)
+    Mg, sg = Md.cpu().numpy(), sd.cpu().numpy()
+    untouched = g == 0
+    assert bits_equal(Mg[untouched], M0[untouched]) and bits_equal(sg[untouched], s0[untouched])
+    step = np.abs(Mo.astype(np.float64) - M0)
+    assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(M0) + step) + TINY)
+    assert np.all(np.abs(sg.astype(np.float64) - so) <= 1e-6 * np.abs(so) + TINY)
+    assert untouched.all() or not bits_equal(Mg, M0)
+
+
+@pytest.mark.parametrize("rshift", [0, 10, 15])
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,d,Z", [(1_000_003, 128, 32), (100_003, 64, 8), (1000, 64, 32), (300_007, 128, 128), (70_001, 16, 1)])
+def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift, monkeypatch):
+    # enough tokens (n * d >= 2^22) for the region-sorted path: hot tokens, long bags, blocks that
+    # leave their region or wrap, one region only (m = 1000), unaligned array and state
+    monkeypatch.setenv("ROBE_TUNE_FUSED", "regions")
+    if rshift:
+        monkeypatch.setenv("ROBE_TUNE_RSHIFT", str(rshift))
+    h, H = both_hashes(23 * m + Z + sign, m, d, Z, sign)
+    F = 26
+    B = max(8, (1 << 22) // (d * F) + 3)
+    rng = np.random.default_rng(d + Z)
+    ids = rng.integers(0, 4000, size=(B, F), dtype=np.int64)
+    ids[rng.random((B, F)) < 0.3] = 11
+    Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+    assert robe.robe_fused_workspace_bytes(h, B, F, ids.size) > 8 * ids.size
+    _check_fused(h, H, Gi, ids, None, B, F, m)
+    _check_fused(h, H, Gi, ids, None, B, F, m, shift=1)
+    Bb = max(4, B // 8)
+    idsb, off = random_bags(rng, Bb * F, 3000, 8.0, long_bag=2500)
+    _check_fused(h, H, Gi[:Bb], idsb, off, Bb, F, m)
+
+
+@pytest.mark.parametrize("m,d,Z,B,F", [(50_021, 16, 4, 9, 26), (4099, 12, 3, 5, 7), (1000, 4, 16, 6, 3), (100_003, 128, 32, 40, 26)])
+def test_fused_backward_adagrad_small_problems_take_the_two_step_route(m, d, Z, B, F):
+    h, H = both_hashes(m + B, m, d, Z, 1)
+    rng = np.random.default_rng(B)
+    ids = rng.integers(0, 50, size=(B, F), dtype=np.int64)
+    Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+    assert robe.robe_fused_workspace_bytes(h, B, F, ids.size) >= 4 * m
+    _check_fused(h, H, Gi, ids, None, B, F, m)
+    idsb, off = random_bags(rng, B * F, 50, 3.0, long_bag=40)
+    _check_fused(h, H, Gi, idsb, off, B, F, m, shift=1)
+    # nothing to do: nothing touched
+    Md = torch.ones(m, device=DEV)
+    sd = torch.ones(m, device=DEV)
+    robe.robe_backward_adagrad(h, torch.empty((0, F, d), device=DEV), torch.empty((0, F), dtype=torch.int64, device=DEV),
+                               None, 0, F, Md, sd, 0.01, 1e-8)
+    assert bool((Md == 1).all()) and bool((sd == 1).all())
 
 
 @pytest.mark.parametrize("env,val", [("ROBE_TUNE_FWD", "4,1"), ("ROBE_TUNE_FWD", "2,1"), ("ROBE_TUNE_FWD", "1,1"),

@@ -58,7 +58,7 @@ def test_random_problems_match_the_oracle(chunk, monkeypatch):
     for case in range(12):
         m, d, Z, B, F, sign = draw_case(rng)
         monkeypatch.setenv("ROBE_TUNE_XCD", str(int(rng.choice([0, 2]))))
-        monkeypatch.setenv("ROBE_TUNE_BWD_MODE", str(rng.choice(["direct", "dedup"])))
+        monkeypatch.setenv("ROBE_TUNE_BWD_MODE", str(rng.choice(["direct", "dedup", "regions"])))
         tag = f"chunk {chunk} case {case}: m={m} d={d} Z={Z} B={B} F={F} sign={sign}"
         print(tag, flush=True)
         seed = int(rng.integers(0, 2**63))
