@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="time robe_backward and robe_adagrad_update as separate calls inside the step "
                          "(default: the fused robe_backward_adagrad; the separate calls are then timed beside it)")
+    ap.add_argument("--step-only", action="store_true",
+                    help="with the fused step, do not time the separate calls beside it (keeps a profile of "
+                         "the run down to the step's own kernels)")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
     ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
     ap.add_argument("--copy-calib-mb", type=int, default=0,
@@ -62,16 +65,17 @@ def algorithmic_bytes(w, rows, tokens, touched):
 def measured_traffic(workload, kernel):
     """HBM-side bytes per launch from the committed rocprofv3 counter summary, if there is one.
 
-    profiles/<workload>_step.md carries lines `traffic <kernel> <bytes>` (FETCH_SIZE and WRITE_SIZE
-    of separate --pmc runs of this same script, scaled by the calibration copy)."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_step.md")
-    try:
-        for line in open(path):
-            parts = line.split()
-            if len(parts) == 3 and parts[0] == "traffic" and parts[1] == kernel:
-                return int(parts[2])
-    except OSError:
-        pass
+    profiles/<workload>_step.md (the default step) and profiles/<workload>_step_separate_calls.md
+    (--unfused) carry lines `traffic <kernel> <bytes>` (FETCH_SIZE and WRITE_SIZE of separate --pmc
+    runs of this same script, scaled by the calibration copy)."""
+    for suffix in ("_step.md", "_step_separate_calls.md"):
+        try:
+            for line in open(os.path.join(ROOT, "profiles", workload + suffix)):
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic" and parts[1] == kernel:
+                    return int(parts[2])
+        except OSError:
+            pass
     return None
 
 
@@ -238,7 +242,7 @@ def main():
                 k_ms["adagrad"].append(ev[2].elapsed_time(ev[3]))
             if do_sgd:
                 k_ms["sgd"].append(ev[2].elapsed_time(ev[3]))
-    if fused:
+    if fused and not args.step_only:
         # the two separate entry points, timed beside the fused step (not part of the timed steps)
         for k in range(3 + 5):
             idd, offd = dev_batches[k % len(dev_batches)]
@@ -252,6 +256,19 @@ def main():
             if k >= 3:
                 k_ms["bwd"].append(e[0].elapsed_time(e[1]))
                 k_ms["adagrad"].append(e[1].elapsed_time(e[2]))
+    # what this machine's HBM delivers to the simplest streaming kernel: a 1 GiB device-to-device copy
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    c_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(2):
+        dst.copy_(src)
+    c_ev[0].record(stream)
+    for _ in range(5):
+        dst.copy_(src)
+    c_ev[1].record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (c_ev[0].elapsed_time(c_ev[1]) * 1e-3) / 1e9
+    del src, dst
     avg = {k: (sum(v) / len(v) if v else 0.0) for k, v in k_ms.items()}
     tok = sum(tokens[k % len(tokens)] for k in range(args.steps)) / args.steps
     alg = algorithmic_bytes(w, rows, tok, touched)
@@ -264,18 +281,20 @@ def main():
         if avg[name] > 0:
             gbs = alg[name] / (avg[name] * 1e-3) / 1e9
             kernels[name] = {"ms": round(avg[name], 4), "algorithmic_GB": round(alg[name] / 1e9, 4),
-                             "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+                             "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                             "frac_of_device_copy": round(gbs / copy_gbs, 4)}
     in_step = [n for n in kernels if not (fused and n in ("bwd", "adagrad"))]
     dominant = max(in_step, key=lambda n: kernels[n]["ms"])
     phases = {"fwd": {"ms": round(avg["fwd"], 4), "lookups_per_s": rate(avg["fwd"])}}
-    if do_bwd:
+    if do_bwd and avg["bwd"] > 0:
         phases["fwd_bwd"] = {"ms": round(avg["fwd"] + avg["bwd"], 4), "lookups_per_s": rate(avg["fwd"] + avg["bwd"])}
     if fused:
         t_all = avg["fwd"] + avg["bwd_adagrad"]
         phases["fwd_bwd_adagrad"] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all),
                                       "how": "robe_forward + fused robe_backward_adagrad"}
-        t_sep = avg["fwd"] + avg["bwd"] + avg["adagrad"]
-        phases["fwd_bwd_adagrad_separate_calls"] = {"ms": round(t_sep, 4), "lookups_per_s": rate(t_sep)}
+        if avg["bwd"] > 0:
+            t_sep = avg["fwd"] + avg["bwd"] + avg["adagrad"]
+            phases["fwd_bwd_adagrad_separate_calls"] = {"ms": round(t_sep, 4), "lookups_per_s": rate(t_sep)}
     elif do_ada or do_sgd:
         opt = "adagrad" if do_ada else "sgd"
         t_all = avg["fwd"] + avg["bwd"] + avg[opt]
@@ -283,10 +302,11 @@ def main():
     total_alg = sum(alg[n] for n in in_step)
     # the timed unit of each phase is one entry-point call; backward is several kernels when it sorts
     entry_names = {"fwd": "robe_forward", "adagrad": "robe_adagrad_update", "sgd": "robe_sgd_update",
-                   "bwd_adagrad": "robe_backward_adagrad (token_keys + radix sort + combine_rows + region count/scan/"
-                                  "records + region_reduce kernels)",
-                   "bwd": "robe_backward (" + ("token_keys + radix sort + combine_scatter kernels" if ws_bytes
-                                               else "direct scatter kernel") + ")"}
+                   "bwd_adagrad": "robe_backward_adagrad (every kernel of the call: token keys, radix sort, then "
+                                  "combine_rows + region count/scan/records + region_reduce with the Adagrad "
+                                  "write-back on large arrays, scatter + update_kernel on small ones)",
+                   "bwd": "robe_backward (every kernel of the call: "
+                          + ("token keys, radix sort, then combine + scatter" if ws_bytes else "direct scatter kernel") + ")"}
     result = {
         "metric": "ROBE lookups/sec, whole step (fwd%s%s), d=%d, Z=%d" % (
             "+bwd" if do_bwd else "", "+Adagrad" if do_ada else ("+SGD" if do_sgd else ""), w.d, w.Z)
@@ -304,6 +324,8 @@ def main():
                    "touched_slots": touched},
         "effective_GBps_whole_step": total_alg / (ms_per_step * 1e-3) / 1e9,
         "effective_frac_of_hbm_peak": total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "device_copy_GBps": round(copy_gbs, 1),
+        "effective_frac_of_device_copy": total_alg / (ms_per_step * 1e-3) / 1e9 / copy_gbs,
         "phases": phases,
         "kernels": kernels,
         "roofline": {"kernel": entry_names[dominant], "bound": "hbm", "achieved": kernels[dominant]["achieved_GBps"],

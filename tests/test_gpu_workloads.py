@@ -89,7 +89,7 @@ def run_workload(name, **scale):
     lhs = float((out.astype(np.float64) * G).sum())
     rhs = float(M.astype(np.float64) @ got.astype(np.float64))
     assert abs(lhs - rhs) <= 1e-5 * float(np.abs(M).astype(np.float64) @ S) + 1e-9
-    del err, S
+    del err
 
     if "sgd" in w.phases:
         robe.robe_sgd_update(h, Md, ga, w.lr)
@@ -121,6 +121,20 @@ def run_workload(name, **scale):
     Me, se, ge = M.copy(), np.zeros(w.m, dtype=np.float32), ref.astype(np.float32)
     oracle.adagrad(Me, se, ge, w.lr, w.eps, threads=THREADS)
     bad = np.abs(Mg.astype(np.float64) - Me) > 1e-5 * (np.abs(M) + w.lr)
+    assert np.all(np.abs(ref[bad]) <= 1e-4), float(np.abs(ref[bad]).max())
+    assert int(bad.sum()) <= 2 + w.m // 10**5, int(bad.sum())
+    del Mg, sg, Mo, so, go
+
+    # The single call that scatters and updates at once, from the same start, to the same bar.
+    Mf, sf = dev(M), torch.zeros(w.m, dtype=torch.float32, device=DEV)
+    robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Mf, sf, w.lr, w.eps)
+    Mf, sf = Mf.cpu().numpy(), sf.cpu().numpy()
+    assert bits_equal(Mf[untouched], M[untouched]) and not sf[untouched].any()
+    # accumulator: s = g^2 from zero, g within 1e-5 * S of the oracle's
+    g64 = np.abs(ref)
+    tol_g = 1e-5 * S
+    assert np.all(np.abs(sf.astype(np.float64) - ref * ref) <= 2.0 * g64 * tol_g + tol_g * tol_g + 1e-6 * ref * ref + TINY)
+    bad = np.abs(Mf.astype(np.float64) - Me) > 1e-5 * (np.abs(M) + w.lr)
     assert np.all(np.abs(ref[bad]) <= 1e-4), float(np.abs(ref[bad]).max())
     assert int(bad.sum()) <= 2 + w.m // 10**5, int(bad.sum())
 
