@@ -201,6 +201,23 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
                           int64_t batch, int32_t n_features, float *array, float *state,
                           float lr, float eps, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Run-to-run reproducible scatter (process-wide switch, off at start; returns the previous setting).
+ * Eq. 3 sums float32 terms whose order the paper does not fix; with float atomics that order, and so
+ * the last bits of the result, change from run to run.  While the switch is on, robe_backward and
+ * robe_backward_adagrad always take the route that has no float atomic (blocks sorted by destination
+ * region, one workgroup per region) and put every slice's blocks into a canonical order before adding
+ * them, so the same call on the same inputs on the same device gives the same bits every time.  The
+ * price is a few per cent of time on large problems, more on small ones (where the atomics would have
+ * been faster), and the larger workspace: ask robe_workspace_bytes / robe_fused_workspace_bytes after
+ * setting the switch.  Shapes that route cannot handle (Z > d, d / Z or the lane group not a power of
+ * two, more than 2^30 array slots) make the two calls fail with ROBE_EINVAL instead of silently
+ * giving up reproducibility.  The forward pass and the two update rules are reproducible always.
+ * Set it before the calls it should govern: calls that run concurrently with the change may use
+ * either setting.
+ */
+int robe_set_reproducible(int on);
+
 /* Text of the calling thread's most recent error ("" if none).  Never NULL. */
 const char *robe_last_error(void);
 

@@ -46,7 +46,7 @@ class RobeHash(ctypes.Structure):
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
-           "robe_last_error")
+           "robe_set_reproducible", "robe_last_error")
 
 _lib = None
 
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.robe_backward_adagrad.restype = ctypes.c_int
         L.robe_backward_adagrad.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_float, ctypes.c_float,
                                             vp, ctypes.c_size_t, vp]
+        L.robe_set_reproducible.restype = ctypes.c_int
+        L.robe_set_reproducible.argtypes = [ctypes.c_int]
         L.robe_last_error.restype = ctypes.c_char_p
         L.robe_last_error.argtypes = []
         _lib = L
@@ -203,3 +205,8 @@ def robe_backward_adagrad(h: RobeHash, grad_out: torch.Tensor, indices: torch.Te
                                        _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                        indices.numel(), batch, n_features, _dev(array, torch.float32, "array"),
                                        _dev(state, torch.float32, "state"), lr, eps, ws_ptr, ws_len, _stream()))
+
+
+def robe_set_reproducible(on: bool) -> bool:
+    """Process-wide switch for the run-to-run reproducible scatter; returns the previous setting."""
+    return bool(lib().robe_set_reproducible(1 if on else 0))

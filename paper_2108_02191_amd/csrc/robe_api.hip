@@ -17,6 +17,7 @@
 //   ROBE_TUNE_KEY_BITS = 8..31                   key bits the backward sort looks at
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -33,6 +34,7 @@
 namespace {
 
 thread_local char g_err[512] = "";
+std::atomic<int> g_reproducible{0};   // robe_set_reproducible
 
 int fail(int code, const char *fmt, ...)
 {
@@ -264,13 +266,24 @@ bool regions_by_default(const robe_hash_t *h, int64_t n_indices)
     return h->m >= (1ull << 26) && n_indices >= (1ll << 21);
 }
 
+int fail_not_reproducible()
+{
+    return fail(ROBE_EINVAL, "reproducible mode: this shape or size has no route without float atomics "
+                             "(it needs Z <= d, d / Z and the lane group a power of two, at most 2^30 array slots "
+                             "and 32-bit record counts)");
+}
+
 BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, bool bags, const void *grad_out,
                       bool need_regions = false)
 {
     BwdPlan pl;
     memset(&pl, 0, sizeof(pl));
     const char *mode = getenv("ROBE_TUNE_BWD_MODE");
-    if (mode && strcmp(mode, "direct") == 0) return pl;
+    if (mode && strcmp(mode, "direct") == 0 && !g_reproducible.load(std::memory_order_relaxed)) return pl;
+    if (g_reproducible.load(std::memory_order_relaxed)) {
+        need_regions = true;   // the only route without float atomics
+        mode = nullptr;
+    }
     const bool forced = need_regions || (mode && (strcmp(mode, "dedup") == 0 || strcmp(mode, "regions") == 0));
     // 32-bit positions and row numbers
     if (rows < 1 || n_indices < 1 || rows >= 0x7FFFFFFFll || n_indices >= 0x7FFFFFFFll) return pl;
@@ -452,17 +465,20 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
         if (int rc = check_launch("backward (records)")) return rc;
 
         // R5: one workgroup per region
-        const size_t lds_red = ((size_t)1 << r.r_shift) * 4 + (size_t)robe::kRecBatch * (sign ? 12 : 8) + (64 + 65) * 4;   // region + batch + slice counters
+        const size_t lds_red = ((size_t)1 << r.r_shift) * 4 + (size_t)robe::kRecBatch * (sign ? 12 : 8) + (64 + 65 + 1) * 4;   // region + batch + slice counters
         const int vec_ok = aligned(grad_array, 16) && (rule == 0 || aligned(state, 16)) ? 1 : 0;
         const dim3 rgrid(r.NR), rblock(robe::kReduceBlock);
-#define ROBE_REDUCE(S_, R_)                                                                                           \
+        const bool canon = g_reproducible.load(std::memory_order_relaxed) != 0;
+#define ROBE_REDUCE_C(S_, R_, C_)                                                                                     \
     do {                                                                                                              \
-        if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_>, lds_red, "backward (reduce)")) return rc;          \
-        robe::region_reduce_kernel<S_, R_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, lr, eps, vec_ok); \
+        if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_, C_>, lds_red, "backward (reduce)")) return rc;      \
+        robe::region_reduce_kernel<S_, R_, C_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, lr, eps, vec_ok); \
     } while (0)
+#define ROBE_REDUCE(S_, R_) do { if (canon) ROBE_REDUCE_C(S_, R_, true); else ROBE_REDUCE_C(S_, R_, false); } while (0)
         if (sign) { if (rule) ROBE_REDUCE(true, 1); else ROBE_REDUCE(true, 0); }
         else      { if (rule) ROBE_REDUCE(false, 1); else ROBE_REDUCE(false, 0); }
 #undef ROBE_REDUCE
+#undef ROBE_REDUCE_C
         return check_launch("backward (reduce)");
     }
     if (rule != 0) return fail(ROBE_EINVAL, "internal: fused update needs the region-sorted scatter");
@@ -590,10 +606,16 @@ int robe_backward(const robe_hash_t *hash, const float *grad_out, const int64_t 
     if (grad_out == nullptr) return fail(ROBE_EINVAL, "grad_out is NULL");
     if (grad_array == nullptr) return fail(ROBE_EINVAL, "grad_array is NULL");
     if (!aligned(grad_out, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    if (g_reproducible.load(std::memory_order_relaxed) && !pl.regions) return fail_not_reproducible();
     if (pl.dedup)
         return launch_dedup_backward(hash, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
                                       grad_array, workspace, (hipStream_t)stream);
     return launch_rows<true>(hash, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad_array, grad_out, (hipStream_t)stream);
+}
+
+int robe_set_reproducible(int on)
+{
+    return g_reproducible.exchange(on ? 1 : 0);
 }
 
 static int launch_update(int rule, const robe_hash_t *hash, float *array, float *state, float *grad_array,
@@ -643,8 +665,9 @@ static bool fused_plan(const robe_hash_t *hash, int64_t rows, int64_t n_indices,
     *scratch_bytes = 0;
     // ROBE_TUNE_FUSED = regions | twostep overrides the choice (regions still needs n * d >= 2^22).
     const char *how = getenv("ROBE_TUNE_FUSED");
+    const bool repro = g_reproducible.load(std::memory_order_relaxed) != 0;
     const bool want = how ? strcmp(how, "regions") == 0 : regions_by_default(hash, n_indices);
-    if (want && (uint64_t)n_indices * hash->d >= (1ull << 22)) {
+    if (repro || (want && (uint64_t)n_indices * hash->d >= (1ull << 22))) {
         *pl = plan_backward(hash, rows, n_indices, bags, grad_out, true);
         if (pl->regions) return true;
     }
@@ -679,6 +702,7 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const 
     BwdPlan pl;
     size_t scratch = 0;
     const bool fused = fused_plan(hash, rows, n_indices, offsets != nullptr, grad_out, &pl, &scratch);
+    if (g_reproducible.load(std::memory_order_relaxed) && !fused) return fail_not_reproducible();
     const size_t need = scratch + ((pl.dedup || pl.regions) ? pl.bytes : 0);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need))
         return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);

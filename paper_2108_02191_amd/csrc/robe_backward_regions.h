@@ -36,8 +36,10 @@ constexpr int kReduceBlock = 512;      // R5 (the slice arithmetic assumes 2^9)
 constexpr int kRecBatch = 896;         // records sorted and applied per round in R5 (at most 2 per thread);
                                        // 32 KB region + batch + counters stay under 40 KB: four workgroups per CU
 constexpr int kRecAhead = 8;           // gradient blocks a lane group requests before adding them (R5)
+constexpr int kCanonAhead = 4;         // records of a slice compared per step when R5 puts them in canonical order
 constexpr int kWb = 1;                 // vectors per thread and pass in the write-back of R5 (more did not pay: registers)
 constexpr uint32_t kMaxRegions = 32768;
+constexpr uint32_t kMaxClassShift = 10;  // R5 splits an overfull region into at most 2^10 classes (the table lives in the batch area)
 constexpr uint32_t kPartBit = 0x80000000u;   // record flag: the elements past the end of the block's own region
 constexpr uint32_t kDeadRecord = 0xFFFFFFFFu;
 
@@ -268,7 +270,13 @@ __device__ __forceinline__ float signed_block_value(const Params &p, float v, ui
     }
 }
 
-template <bool SIGN, int RULE>
+// Class of a record among 2^shift classes: a fixed hash of its source word.
+__device__ __forceinline__ uint32_t record_class(uint32_t y, uint32_t shift)
+{
+    return (y * 0x9E3779B1u) >> (32u - shift);
+}
+
+template <bool SIGN, int RULE, bool CANON>
 __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void region_reduce_kernel(Params p, RegionPlan s,
                                                                      const float *__restrict__ grad_out,
                                                                      float *__restrict__ dst,      // RULE 0: grad_array; RULE 1: array
@@ -289,6 +297,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
     uint32_t *srt_tg = reinterpret_cast<uint32_t *>(srt + kRecBatch);
     uint32_t *cnt = srt_tg + (SIGN ? kRecBatch : 0);   // 64 slice counters
     uint32_t *pre = cnt + 64;                          // 65 slice starts
+    uint32_t *sel = pre + 65;                          // records staged for this round
 
     for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = 0.0f;
 
@@ -311,33 +320,100 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
         return e < p.m ? (uint32_t)e : p.m;
     };
 
-    for (uint32_t bb = rb; bb < re; bb += kRecBatch) {
-        const uint32_t nb = re - bb < (uint32_t)kRecBatch ? re - bb : (uint32_t)kRecBatch;
+    // Which records go into which round must not depend on the order in which the records were
+    // written (that order comes from integer atomics and changes from run to run): a region with more
+    // than one round's worth of records is split into classes by a hash of the record's source word,
+    // with as many classes as it takes for every class to fit one round.  If even kMaxClasses classes
+    // do not do it (hundreds of blocks per slot), the rounds follow the storage order instead.
+    const uint32_t count = re - rb;
+    uint32_t cls_shift = 0;
+    bool by_class = false;
+    if (CANON && count > (uint32_t)kRecBatch) {
+        uint32_t *hist = reinterpret_cast<uint32_t *>(srt);
+        cls_shift = 1;
+        while (((count + (1u << cls_shift) - 1u) >> cls_shift) > (uint32_t)kRecBatch / 2u) ++cls_shift;
+        for (; cls_shift <= kMaxClassShift; ++cls_shift) {
+            const uint32_t ncls = 1u << cls_shift;
+            __syncthreads();
+            for (uint32_t i = threadIdx.x; i < ncls; i += kReduceBlock) hist[i] = 0;
+            if (threadIdx.x == 0) *sel = 0;
+            __syncthreads();
+            for (uint32_t k = threadIdx.x; k < count; k += kReduceBlock)
+                atomicAdd(&hist[record_class(s.rec[rb + k].y, cls_shift)], 1u);
+            __syncthreads();
+            for (uint32_t i = threadIdx.x; i < ncls; i += kReduceBlock)
+                if (hist[i] > (uint32_t)kRecBatch) *sel = 1;      // a class that does not fit one round
+            __syncthreads();
+            if (*sel == 0) {
+                by_class = true;
+                break;
+            }
+        }
+    }
+    const uint32_t rounds = by_class ? (1u << cls_shift) : (count + kRecBatch - 1u) / kRecBatch;
+
+    for (uint32_t round = 0; round < rounds; ++round) {
         if (threadIdx.x < groups) cnt[threadIdx.x] = 0;
-        __syncthreads();   // also orders the previous round's second pass before this round's writes
+        if (threadIdx.x == 0) *sel = 0;
+        __syncthreads();   // also orders the previous round's last pass before this round's writes
+        uint32_t bb = rb + round * kRecBatch;
+        uint32_t nb = re - bb < (uint32_t)kRecBatch ? re - bb : (uint32_t)kRecBatch;
+        if (CANON && by_class) {
+            // stage this round's class in the batch area, in any order
+            for (uint32_t k = threadIdx.x; k < count; k += kReduceBlock) {
+                const uint2 x = s.rec[rb + k];
+                if (record_class(x.y, cls_shift) != round) continue;
+                const uint32_t at = atomicAdd(sel, 1u);
+                if (at < (uint32_t)kRecBatch) {
+                    srt[at] = x;
+                    if constexpr (SIGN) srt_tg[at] = s.rec_tg[rb + k];
+                }
+            }
+            __syncthreads();
+            nb = *sel < (uint32_t)kRecBatch ? *sel : (uint32_t)kRecBatch;
+        }
 
         // 1. each thread takes two records, finds their slice and their rank inside it
         uint2 rc[2];
         uint32_t tgv[2], sl[2], rk[2];
+        if (CANON && by_class) {   // two branches: one reads LDS, the other global memory
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint32_t k = threadIdx.x + (uint32_t)t * kReduceBlock;
+                rc[t] = make_uint2(kDeadRecord, 0u);
+                tgv[t] = 0;
+                if (k < nb) {
+                    rc[t] = srt[k];
+                    if constexpr (SIGN) tgv[t] = srt_tg[k];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint32_t k = threadIdx.x + (uint32_t)t * kReduceBlock;
+                rc[t] = make_uint2(kDeadRecord, 0u);
+                tgv[t] = 0;
+                if (k < nb) {
+                    rc[t] = s.rec[bb + k];
+                    if constexpr (SIGN) tgv[t] = s.rec_tg[bb + k];
+                }
+            }
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const uint32_t k = threadIdx.x + (uint32_t)t * kReduceBlock;
-            rc[t] = make_uint2(kDeadRecord, 0u);
-            tgv[t] = 0;
             sl[t] = 0;
             rk[t] = 0;
-            if (k < nb) {
-                const uint2 x = s.rec[bb + k];
-                const uint32_t o = x.x, src = x.y & ~kPartBit;
-                const bool part1 = (x.y & kPartBit) != 0;
+            if (rc[t].x != kDeadRecord) {
+                const uint32_t o = rc[t].x, src = rc[t].y & ~kPartBit;
+                const bool part1 = (rc[t].y & kPartBit) != 0;
                 // where the record's first element of this part lands; anything else cannot occur
                 // with consistent inputs and is dropped
                 const uint32_t first = part1 ? own_end(o) % p.m : o;
                 if (o < p.m && src < s.src_blocks && (first >> s.r_shift) == r) {
-                    rc[t] = x;
-                    if constexpr (SIGN) tgv[t] = s.rec_tg[bb + k];
                     sl[t] = (first - r0) >> slice_shift;
                     rk[t] = atomicAdd(&cnt[sl[t]], 1u);
+                } else {
+                    rc[t].x = kDeadRecord;
                 }
             }
         }
@@ -360,6 +436,52 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             }
         }
         __syncthreads();
+        if constexpr (CANON) {
+            // The rank above came from an atomic and is arbitrary.  The order in which a slice's records
+            // are added decides the rounding, so it is made canonical: by source word, then offset, then
+            // sign term.  Records that agree in all three are interchangeable; their arbitrary places only
+            // keep them apart.  (Tokens of one bag share their source blocks, so the source word alone
+            // does not identify a record.)
+            auto goes_before = [&](const uint2 &x, uint32_t tk, uint32_t k, const uint2 &mine, uint32_t mine_tg,
+                                   uint32_t mine_at) -> bool {
+                if (x.y != mine.y) return x.y < mine.y;
+                if (x.x != mine.x) return x.x < mine.x;
+                return tk < mine_tg || (tk == mine_tg && k < mine_at);
+            };
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                if (rc[t].x != kDeadRecord) {
+                    const uint32_t a = pre[sl[t]], b = pre[sl[t] + 1u], me = a + rk[t];
+                    uint32_t c = 0;
+                    for (uint32_t k0 = a; k0 < b; k0 += kCanonAhead) {     // kCanonAhead independent LDS reads per step
+                        uint2 x[kCanonAhead];
+                        uint32_t tk[kCanonAhead];
+#pragma unroll
+                        for (int u = 0; u < kCanonAhead; ++u) {
+                            const uint32_t k = k0 + u < b ? k0 + u : me;   // past the end: compare with itself, never "before"
+                            x[u] = srt[k];
+                            tk[u] = SIGN ? srt_tg[k] : 0u;
+                        }
+#pragma unroll
+                        for (int u = 0; u < kCanonAhead; ++u) {
+                            const uint32_t k = k0 + u < b ? k0 + u : me;
+                            c += goes_before(x[u], tk[u], k, rc[t], tgv[t], me);
+                        }
+                    }
+                    rk[t] = c;
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                if (rc[t].x != kDeadRecord) {
+                    const uint32_t at = pre[sl[t]] + rk[t];
+                    srt[at] = rc[t];
+                    if constexpr (SIGN) srt_tg[at] = tgv[t];
+                }
+            }
+            __syncthreads();
+        }
 
         // 2. every group applies the records that start in its slice, kRecAhead loads in flight;
         //    elements at or past the slice end wait for pass 3

@@ -83,6 +83,10 @@ def test_entry_points_reject_bad_arguments_without_a_gpu():
         bad = robe.robe_init_hash(1, 1000, 16, 4, 0)
         setattr(bad, field, val)
         assert L.robe_forward(ctypes.byref(bad), fake, fake, None, 4, 2, 2, fake, None) == EINVAL, field
+    # the reproducibility switch is plain host state: returns the previous setting
+    assert L.robe_set_reproducible(1) == 0
+    assert L.robe_set_reproducible(0) == 1
+    assert L.robe_set_reproducible(0) == 0
     # empty problems are no-ops that succeed
     assert L.robe_forward(ref, None, None, None, 0, 0, 2, None, None) == robe.ROBE_OK
     assert L.robe_backward(ref, None, None, None, 0, 0, 2, None, None, 0, None) == robe.ROBE_OK

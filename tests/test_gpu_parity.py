@@ -341,6 +341,97 @@ def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift, monkeypatch):
     _check_fused(h, H, Gi[:Bb], idsb, off, Bb, F, m)
 
 
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,d,Z,card,rshift", [
+    (1_000_003, 128, 32, 40_000, 0),     # a few hundred records per region: one round each
+    (20_011, 32, 8, 1_000_000, 10),      # tens of thousands of records per region: split into classes
+    (1000, 64, 32, 4000, 0),             # one region, every block overlaps hundreds of others
+    (300_007, 128, 128, 3000, 13),       # blocks as long as a slice
+])
+def test_reproducible_mode_gives_the_same_bits_every_run(m, d, Z, card, rshift, sign, monkeypatch):
+    # No float atomics on this route and a canonical order of additions: the same call on the same
+    # inputs gives the same bits, whatever order the integer atomics hand out record slots in.
+    if rshift:
+        monkeypatch.setenv("ROBE_TUNE_RSHIFT", str(rshift))
+    assert robe.robe_set_reproducible(True) is False
+    try:
+        _reproducible_case(m, d, Z, card, sign)
+    finally:
+        assert robe.robe_set_reproducible(False) is True
+
+
+def _reproducible_case(m, d, Z, card, sign):
+    h, H = both_hashes(5 * m + Z + sign, m, d, Z, sign)
+    F = 26
+    B = max(8, (1 << 22) // (d * F) + 3)
+    rng = np.random.default_rng(m + d)
+    ids = rng.integers(0, card, size=(B, F), dtype=np.int64)
+    ids[rng.random((B, F)) < 0.2] = 7
+    G = rng.standard_normal((B, F, d)).astype(np.float32)
+    M0 = rng.standard_normal(m).astype(np.float32)
+    Gd, idd = to_dev(G), to_dev(ids)
+    assert robe.robe_fused_workspace_bytes(h, B, F, ids.size) > 8 * ids.size      # the sorted route is taken
+    assert robe.robe_workspace_bytes(h, B, F, ids.size) > 8 * ids.size
+    runs = []
+    for _ in range(4):
+        Md, sd = to_dev(M0), torch.zeros(m, dtype=torch.float32, device=DEV)
+        robe.robe_backward_adagrad(h, Gd, idd, None, B, F, Md, sd, 0.01, 1e-8)
+        ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+        robe.robe_backward(h, Gd, idd, None, B, F, ga)
+        runs.append((Md.cpu().numpy(), sd.cpu().numpy(), ga.cpu().numpy()))
+    for Mk, sk, gk in runs[1:]:
+        assert bits_equal(Mk, runs[0][0]) and bits_equal(sk, runs[0][1]) and bits_equal(gk, runs[0][2])
+    # and it is the right result
+    ref, S = oracle.backward(H, G, ids, None, B, F)
+    assert np.all(np.abs(runs[0][2].astype(np.float64) - ref) <= 1e-5 * S + TINY)
+    # the accumulator of the fused call is the square of the very gradient the plain call returns
+    g32 = runs[0][2]
+    assert bits_equal(runs[0][1], g32 * g32)
+
+
+def test_reproducible_mode_covers_small_problems_and_refuses_what_it_cannot_do():
+    robe.robe_set_reproducible(True)
+    try:
+        # a handful of tokens: still the sorted route, still the right answer, bags included
+        h, H = both_hashes(3, 5003, 16, 4, 1)
+        rng = np.random.default_rng(0)
+        B, F = 7, 5
+        ids = rng.integers(0, 50, size=(B, F), dtype=np.int64)
+        G = rng.standard_normal((B, F, 16)).astype(np.float32)
+        assert robe.robe_workspace_bytes(h, B, F, ids.size) > 0
+        outs = []
+        for _ in range(3):
+            ga = torch.zeros(5003, dtype=torch.float32, device=DEV)
+            robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga)
+            outs.append(ga.cpu().numpy())
+        assert bits_equal(outs[0], outs[1]) and bits_equal(outs[0], outs[2])
+        ref, S = oracle.backward(H, G, ids, None, B, F)
+        assert np.all(np.abs(outs[0].astype(np.float64) - ref) <= 1e-5 * S + TINY)
+        flat, off = random_bags(rng, B * F, 50, 3.0)
+        ga = torch.zeros(5003, dtype=torch.float32, device=DEV)
+        robe.robe_backward(h, to_dev(G), to_dev(flat), to_dev(off), B, F, ga)
+        ref, S = oracle.backward(H, G, flat, off, B, F)
+        assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * S + TINY)
+        Md, sd = to_dev(rng.standard_normal(5003).astype(np.float32)), torch.zeros(5003, dtype=torch.float32, device=DEV)
+        robe.robe_backward_adagrad(h, to_dev(G), to_dev(flat), to_dev(off), B, F, Md, sd, 0.01, 1e-8)
+        g32 = ga.cpu().numpy()
+        assert bits_equal(sd.cpu().numpy(), g32 * g32)
+        # a block longer than the embedding has no atomic-free route: a loud error, not a silent fallback
+        h2, _ = both_hashes(4, 1000, 4, 16, 0)
+        ids2 = rng.integers(0, 99, size=(6, 3), dtype=np.int64)
+        G2 = rng.standard_normal((6, 3, 4)).astype(np.float32)
+        with pytest.raises(robe.RobeError) as ei:
+            robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV))
+        assert ei.value.code == robe.ROBE_EINVAL and "reproducible" in str(ei.value)
+        with pytest.raises(robe.RobeError):
+            robe.robe_backward_adagrad(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV),
+                                       torch.zeros(1000, dtype=torch.float32, device=DEV), 0.01, 1e-8)
+    finally:
+        robe.robe_set_reproducible(False)
+    # with the switch off the same shape runs (float atomics)
+    robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV))
+
+
 @pytest.mark.parametrize("m,d,Z,B,F", [(50_021, 16, 4, 9, 26), (4099, 12, 3, 5, 7), (1000, 4, 16, 6, 3), (100_003, 128, 32, 40, 26)])
 def test_fused_backward_adagrad_small_problems_take_the_two_step_route(m, d, Z, B, F):
     h, H = both_hashes(m + B, m, d, Z, 1)
