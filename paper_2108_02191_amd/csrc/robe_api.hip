@@ -395,10 +395,11 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     const uint64_t key_threads = (uint64_t)rows << g_shift;
     uint64_t key_blocks = (key_threads + 255) / 256;
     if (key_blocks > 65536) key_blocks = 65536;
-    if (bags)
-        robe::token_keys_kernel<true><<<dim3((uint32_t)key_blocks), dim3(256), 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
-    else
-        robe::token_keys_kernel<false><<<dim3((uint32_t)key_blocks), dim3(256), 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    const dim3 kgrid((uint32_t)key_blocks), kblock(256);
+    // sign off: the sorted value is the token's row of grad_out and positions are never needed again
+    if (bags && sign) robe::token_keys_kernel<true, false><<<kgrid, kblock, 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    else if (bags) robe::token_keys_kernel<true, true><<<kgrid, kblock, 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    else robe::token_keys_kernel<false, true><<<kgrid, kblock, 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
     if (int rc = check_launch("backward (keys)")) return rc;
 
     // S2: sort (key, position) pairs by the top key_bits bits of the 31-bit key

@@ -7,14 +7,23 @@
 // (same table, same id) hit the same d slots with the same signs.  So:
 //
 //   S1 keys     every token gets the key th = (Bh*x + Ah*e + Dh) mod P - the token
-//               part of its offset hash, equal for equal (e, x) - and its position.
-//   S2 sort     radix sort of (key, position) pairs (rocPRIM device primitive).
+//               part of its offset hash, equal for equal (e, x) - and a value: its
+//               row of grad_out when the sign is off, its position when it is on.
+//   S2 sort     radix sort of (key, value) pairs (rocPRIM device primitive).
 //   S3 combine  a group of G lanes walks G consecutive sorted tokens, adds the
 //               gradient rows of runs of identical tokens in registers, and issues
-//               the d atomics once per run.  Identity is checked on (key, id,
-//               table), so distinct tokens that share a key are merely not merged.
-//               A run longer than a group's stretch is flushed once per stretch,
-//               which also spreads very frequent tokens over many groups.
+//               the d atomics once per run.  A run longer than a group's stretch is
+//               flushed once per stretch, which also spreads very frequent tokens
+//               over many groups.
+//
+// When are two tokens "identical"?  Every offset of a token is a function of th
+// alone (h(e,x,c) = ((th + Ch*c) mod P) mod m), so with the sign off two tokens
+// with the same th write the same slots whatever their table and id are: th is
+// the identity, and S3 needs neither the ids nor the positions again (no random
+// reads besides the gradient rows).  With the sign on, g depends on (e, x)
+// through a second hash; identity is then checked on (th, table, id), which
+// takes the position to fetch the id; distinct tokens that share th are merely
+// not merged.
 //
 // The order of the float additions is not fixed, so results agree with an exact
 // sum to rounding only.
@@ -26,7 +35,7 @@ namespace robe {
 constexpr int kRowsInFlight = 8;   // gradient rows a lane group loads before it adds them
 
 // S1.  Bags: a group of G lanes per bag, grid-stride over bags; single-hot: one lane per lookup.
-template <bool BAGS>
+template <bool BAGS, bool ROWVAL>
 __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, uint32_t g_shift,
                                                          const int64_t *__restrict__ indices,
                                                          const int64_t *__restrict__ offsets,
@@ -48,8 +57,8 @@ __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, u
         const uint32_t e = (uint32_t)bag % F;
         for (int64_t t = t0 + lane; t < t1; t += G) {
             keys[t] = staged_h(p, indices[t], e);
-            vals[t] = (uint32_t)t;
-            if constexpr (BAGS) tok_bag[t] = (uint32_t)bag;
+            vals[t] = ROWVAL ? (uint32_t)bag : (uint32_t)t;
+            if constexpr (BAGS && !ROWVAL) tok_bag[t] = (uint32_t)bag;
         }
     }
 }
@@ -77,26 +86,29 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
     int64_t my_x = 0;
     bool my_ok = false;
     if (i0 + grp < n_indices) {
-        const uint32_t t = vals[i0 + grp];
-        if (t < n_indices) {
-            const uint32_t row = BAGS ? tok_bag[t] : t;
-            if (row < rows) {
-                my_ok = true;
-                my_row = row;
+        const uint32_t t = vals[i0 + grp];                 // sign off: the row itself
+        const uint32_t row = !SIGN ? t : (t < n_indices ? (BAGS ? tok_bag[t] : t) : rows);
+        if (row < rows) {
+            my_ok = true;
+            my_row = row;
+            my_th = keys[i0 + grp];
+            if constexpr (SIGN) {
                 my_x = indices[t];
                 my_e = row % q.F;
-                my_th = keys[i0 + grp];
-                if constexpr (SIGN) my_tg = staged_g(p, my_x, my_e);
+                my_tg = staged_g(p, my_x, my_e);
             }
         }
     }
     // does this position start a new run?  (first of the stretch, or a different token than the one before)
     const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
-    const uint32_t p_th = __shfl(my_th, prev), p_e = __shfl(my_e, prev);
-    const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
+    const uint32_t p_th = __shfl(my_th, prev);
     const bool p_ok = __shfl((int)my_ok, prev) != 0;
-    const bool my_head = grp == 0 || !p_ok || p_th != my_th || p_e != my_e ||
-                         p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32);
+    bool my_head = grp == 0 || !p_ok || p_th != my_th;
+    if constexpr (SIGN) {
+        const uint32_t p_e = __shfl(my_e, prev);
+        const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
+        my_head = my_head || p_e != my_e || p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32);
+    }
 
     Lane<V, false, SIGN> L;
     L.init(p, q, grp);

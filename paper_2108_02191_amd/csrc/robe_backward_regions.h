@@ -90,27 +90,31 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
     int64_t my_x = 0;
     bool my_ok = false;
     if (i0 + grp < n) {
-        const uint32_t t = vals[i0 + grp];
-        if (t < n) {
-            const uint32_t row = BAGS ? tok_bag[t] : t;
-            if (row < s.rows) {
-                my_ok = true;
-                my_row = row;
+        const uint32_t t = vals[i0 + grp];                 // sign off: the row itself (see robe_backward_dedup.h)
+        const uint32_t row = !SIGN ? t : (t < n ? (BAGS ? tok_bag[t] : t) : s.rows);
+        if (row < s.rows) {
+            my_ok = true;
+            my_row = row;
+            my_th = s.keys[i0 + grp];
+            if constexpr (SIGN) {
                 my_x = indices[t];
                 my_e = row % q.F;
-                my_th = s.keys[i0 + grp];
-                if constexpr (SIGN) my_tg = staged_g(p, my_x, my_e);
+                my_tg = staged_g(p, my_x, my_e);
             }
         }
     }
     // does a run start here (first of the stretch, or a different token than the one before),
     // and does it end here (last of the stretch, or a different token after)?
     const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
-    const uint32_t p_th = __shfl(my_th, prev), p_e = __shfl(my_e, prev);
-    const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
+    const uint32_t p_th = __shfl(my_th, prev);
     const bool p_ok = __shfl((int)my_ok, prev) != 0;
-    const bool my_head = my_ok && (grp == 0 || !p_ok || p_th != my_th || p_e != my_e ||
-                                   p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32));
+    bool differs = grp == 0 || !p_ok || p_th != my_th;
+    if constexpr (SIGN) {
+        const uint32_t p_e = __shfl(my_e, prev);
+        const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
+        differs = differs || p_e != my_e || p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32);
+    }
+    const bool my_head = my_ok && differs;
     const int next = (int)(base_lane + (grp + 1u < q.G ? grp + 1u : grp));
     const bool n_head = __shfl((int)my_head, next) != 0, n_ok = __shfl((int)my_ok, next) != 0;
     const bool my_end = my_ok && (grp + 1u >= q.G || !n_ok || n_head);
