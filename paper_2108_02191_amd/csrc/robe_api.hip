@@ -246,6 +246,7 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
 struct BwdPlan {
     bool dedup;          // sort the tokens and combine identical ones
     bool regions;        // ... and then sort the blocks by destination region instead of using float atomics
+    bool spill_rows;     // ... with room in LDS for a row of Z floats per lane group of the reduce kernel
     Layout lay;
     uint32_t key_bits;   // most significant key bits the sort looks at
     size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_tok_bag, off_temp, temp_bytes, bytes;
@@ -344,6 +345,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     if (n < (size_t)r.bin_blocks * 1024) r.bin_blocks = (uint32_t)((n + 1023) / 1024);
     r.pos_per_block = (uint32_t)((n + r.bin_blocks - 1) / r.bin_blocks);
     r.lg_shift = log2u(lg);
+    pl.spill_rows = (uint64_t)(512u / lg) * h->Z <= robe::kSpillFloats;
     pl.off_head = off;    off = align_up(off + n, 256);
     pl.off_src_row = off; off = align_up(off + n * 4, 256);
     pl.off_run_tg = off;  if (h->use_sign) off = align_up(off + n * 4, 256);
@@ -466,16 +468,23 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
         if (int rc = check_launch("backward (records)")) return rc;
 
         // R5: one workgroup per region
-        const size_t lds_red = ((size_t)1 << r.r_shift) * 4 + (size_t)robe::kRecBatch * (sign ? 12 : 8) + (64 + 65 + 1) * 4;   // region + batch + slice counters
+        const size_t lds_red = ((size_t)1 << r.r_shift) * 4 + (size_t)robe::kRecBatch * (sign ? 12 : 8) + (64 + 65 + 1) * 4   // region + batch + slice counters
+                               + (pl.spill_rows ? (size_t)robe::kSpillFloats * 4 : 0);
         const int vec_ok = aligned(grad_array, 16) && (rule == 0 || aligned(state, 16)) ? 1 : 0;
         const dim3 rgrid(r.NR), rblock(robe::kReduceBlock);
         const bool canon = g_reproducible.load(std::memory_order_relaxed) != 0;
-#define ROBE_REDUCE_C(S_, R_, C_)                                                                                     \
+#define ROBE_REDUCE_C(S_, R_, C_, P_)                                                                                 \
     do {                                                                                                              \
-        if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_, C_>, lds_red, "backward (reduce)")) return rc;      \
-        robe::region_reduce_kernel<S_, R_, C_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, lr, eps, vec_ok); \
+        if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_, C_, P_>, lds_red, "backward (reduce)")) return rc;  \
+        robe::region_reduce_kernel<S_, R_, C_, P_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, lr, eps, vec_ok); \
     } while (0)
-#define ROBE_REDUCE(S_, R_) do { if (canon) ROBE_REDUCE_C(S_, R_, true); else ROBE_REDUCE_C(S_, R_, false); } while (0)
+#define ROBE_REDUCE(S_, R_)                                                                                           \
+    do {                                                                                                              \
+        if (canon && pl.spill_rows) ROBE_REDUCE_C(S_, R_, true, true);                                                \
+        else if (canon) ROBE_REDUCE_C(S_, R_, true, false);                                                           \
+        else if (pl.spill_rows) ROBE_REDUCE_C(S_, R_, false, true);                                                   \
+        else ROBE_REDUCE_C(S_, R_, false, false);                                                                     \
+    } while (0)
         if (sign) { if (rule) ROBE_REDUCE(true, 1); else ROBE_REDUCE(true, 0); }
         else      { if (rule) ROBE_REDUCE(false, 1); else ROBE_REDUCE(false, 0); }
 #undef ROBE_REDUCE

@@ -33,8 +33,10 @@ namespace robe {
 constexpr int kRowsAhead = 8;          // gradient rows a lane group requests before adding them (R1)
 constexpr int kBinBlock = 1024;        // R2 / R4
 constexpr int kReduceBlock = 512;      // R5 (the slice arithmetic assumes 2^9)
-constexpr int kRecBatch = 896;         // records sorted and applied per round in R5 (at most 2 per thread);
-                                       // 32 KB region + batch + counters stay under 40 KB: four workgroups per CU
+constexpr int kRecBatch = 640;         // records sorted and applied per round in R5 (at most 2 per thread);
+                                       // 32 KB region + batch + counters + spill-over rows stay under 40 KB:
+                                       // four workgroups per CU
+constexpr uint32_t kSpillFloats = 512; // LDS floats for the spill-over rows of R5 (used when groups * Z fits)
 constexpr int kRecAhead = 8;           // gradient blocks a lane group requests before adding them (R5)
 constexpr int kCanonAhead = 4;         // records of a slice compared per step when R5 puts them in canonical order
 constexpr int kWb = 1;                 // vectors per thread and pass in the write-back of R5 (more did not pay: registers)
@@ -232,7 +234,7 @@ constexpr uint32_t kScanPer = kMaxRegions / 1024u;   // regions per thread, all 
 
 __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
 {
-    __shared__ uint32_t part[1024];
+    __shared__ uint32_t wave_total[16];
     const uint32_t b = threadIdx.x * kScanPer;
     uint32_t c[kScanPer];
 #pragma unroll
@@ -240,15 +242,24 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
     uint32_t sum = 0;
 #pragma unroll
     for (uint32_t k = 0; k < kScanPer; ++k) sum += c[k];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    for (uint32_t off = 1; off < 1024u; off <<= 1) {          // inclusive scan of the 1024 partial sums
-        const uint32_t add = threadIdx.x >= off ? part[threadIdx.x - off] : 0u;
-        __syncthreads();
-        part[threadIdx.x] += add;
-        __syncthreads();
+    // inclusive scan of the 1024 partial sums: inside each wavefront by shuffles, then across the 16
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    uint32_t incl = sum;
+#pragma unroll
+    for (uint32_t off = 1; off < 64u; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
     }
-    uint32_t a = part[threadIdx.x] - sum;                      // exclusive prefix of this thread's share
+    if (lane == 63u) wave_total[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < 16u; ++k) {
+        const uint32_t t = wave_total[k];
+        before += k < wave ? t : 0u;
+        total += t;
+    }
+    uint32_t a = before + incl - sum;                          // exclusive prefix of this thread's share
 #pragma unroll
     for (uint32_t k = 0; k < kScanPer; ++k) {
         if (b + k < s.NR) {
@@ -257,7 +268,7 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
         }
         a += c[k];
     }
-    if (threadIdx.x == 1023) s.starts[s.NR] = part[1023];
+    if (threadIdx.x == 1023) s.starts[s.NR] = total;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -280,7 +291,7 @@ __device__ __forceinline__ uint32_t record_class(uint32_t y, uint32_t shift)
     return (y * 0x9E3779B1u) >> (32u - shift);
 }
 
-template <bool SIGN, int RULE, bool CANON>
+template <bool SIGN, int RULE, bool CANON, bool SPILL>
 __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void region_reduce_kernel(Params p, RegionPlan s,
                                                                      const float *__restrict__ grad_out,
                                                                      float *__restrict__ dst,      // RULE 0: grad_array; RULE 1: array
@@ -302,6 +313,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
     uint32_t *cnt = srt_tg + (SIGN ? kRecBatch : 0);   // 64 slice counters
     uint32_t *pre = cnt + 64;                          // 65 slice starts
     uint32_t *sel = pre + 65;                          // records staged for this round
+    // this group's spill-over row, as an index into acc
+    const uint32_t spill_at = (uint32_t)(reinterpret_cast<float *>(sel + 1) - acc) + (threadIdx.x >> s.lg_shift) * p.Z;
 
     for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = 0.0f;
 
@@ -487,22 +500,33 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             __syncthreads();
         }
 
-        // 2. every group applies the records that start in its slice, kRecAhead loads in flight;
-        //    elements at or past the slice end wait for pass 3
+        // 2. every group applies the records that start in its slice, kRecAhead loads in flight.
+        //    Elements at or past the slice end belong to the next group's slice: they are summed in the
+        //    group's own spill-over row (first element past the end first) and added in pass 3, or,
+        //    when there is no room for such rows, read again in pass 3.
         const uint32_t lb = pre[grp], le = pre[grp + 1];
+        if constexpr (SPILL) {
+            for (uint32_t j = j0; j < p.Z; j += LG) acc[spill_at + j] = 0.0f;
+        }
         for (uint32_t k0 = lb; k0 < le; k0 += kRecAhead) {
-            uint32_t o[kRecAhead], src[kRecAhead], tg[kRecAhead], oend[kRecAhead];
-            bool live[kRecAhead], part1[kRecAhead];
+            // per record: element j lands at region slot abase + j, for j in [jlo, jhi) (packed; Z <= 2^15)
+            uint32_t abase[kRecAhead], win[kRecAhead], src[kRecAhead], tg[kRecAhead];
 #pragma unroll
             for (int u = 0; u < kRecAhead; ++u) {
-                live[u] = k0 + u < le;
-                const uint32_t k = live[u] ? k0 + u : lb;
-                const uint2 x = srt[k];
-                o[u] = x.x;
+                const bool live = k0 + u < le;
+                const uint2 x = srt[live ? k0 + u : lb];
                 src[u] = x.y & ~kPartBit;
-                part1[u] = (x.y & kPartBit) != 0;
-                oend[u] = own_end(x.x);
-                tg[u] = SIGN ? srt_tg[k] : 0u;
+                tg[u] = SIGN ? srt_tg[live ? k0 + u : lb] : 0u;
+                const uint32_t keep = own_end(x.x) - x.x;                 // elements before the end of o's own region
+                const uint32_t cut = keep < p.Z ? keep : p.Z;
+                if (x.y & kPartBit) {
+                    abase[u] = 0u - cut;                                  // element `cut` is the first of this region
+                    win[u] = cut | (p.Z << 16);
+                } else {
+                    abase[u] = x.x - r0;
+                    win[u] = cut << 16;
+                }
+                if (!live) win[u] = 0;
             }
             for (uint32_t j = j0; j < p.Z; j += LG) {
                 float v[kRecAhead];
@@ -514,28 +538,42 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                 }
 #pragma unroll
                 for (int u = 0; u < kRecAhead; ++u) {
-                    const bool in_part = (o[u] + j < oend[u]) != part1[u];
-                    const uint32_t a = wrap(o[u] + j, p.m) - r0;
-                    if (live[u] && in_part && a < slice_end && a < region_len)
-                        acc[a] += signed_block_value<SIGN>(p, v[u], tg[u], src[u], j);
+                    const uint32_t a = abase[u] + j;
+                    if (j >= (win[u] & 0xFFFFu) && j < (win[u] >> 16) && a < region_len) {
+                        const float val = signed_block_value<SIGN>(p, v[u], tg[u], src[u], j);
+                        if constexpr (SPILL) {
+                            // one read-modify-write, in the slice or in the group's spill-over row
+                            // (which follows acc at spill_at; a - slice_end < Z - 1)
+                            acc[a < slice_end ? a : spill_at + (a - slice_end)] += val;
+                        } else {
+                            if (a < slice_end) acc[a] += val;
+                        }
+                    }
                 }
             }
         }
         __syncthreads();
 
         // 3. elements past the slice end: the next slice's first Z-1 floats, which nobody else writes now
-        for (uint32_t k = lb; k < le; ++k) {
-            const uint2 x = srt[k];
-            if (x.y & kPartBit) continue;                       // a part-1 record starts its slice: never past its end
-            const uint32_t o = x.x, src = x.y;
-            if (o - r0 + p.Z <= slice_end) continue;
-            const uint32_t oend = own_end(o);
-            const uint32_t tgk = SIGN ? srt_tg[k] : 0u;
-            const float *base = src < src_own ? grad_out + (uint64_t)src * p.Z : s.P + (uint64_t)(src - src_own) * p.Z;
-            for (uint32_t j = j0; j < p.Z; j += LG) {
-                const uint32_t a = o + j - r0;
-                if (o + j < oend && a >= slice_end && a < region_len)
-                    acc[a] += signed_block_value<SIGN>(p, base[j], tgk, src, j);
+        if constexpr (SPILL) {
+            for (uint32_t j = j0; j + 1u < p.Z; j += LG) {
+                const uint32_t a = slice_end + j;
+                if (a < region_len) acc[a] += acc[spill_at + j];
+            }
+        } else {
+            for (uint32_t k = lb; k < le; ++k) {
+                const uint2 x = srt[k];
+                if (x.y & kPartBit) continue;                       // a part-1 record starts its slice: never past its end
+                const uint32_t o = x.x, src = x.y;
+                if (o - r0 + p.Z <= slice_end) continue;
+                const uint32_t oend = own_end(o);
+                const uint32_t tgk = SIGN ? srt_tg[k] : 0u;
+                const float *base = src < src_own ? grad_out + (uint64_t)src * p.Z : s.P + (uint64_t)(src - src_own) * p.Z;
+                for (uint32_t j = j0; j < p.Z; j += LG) {
+                    const uint32_t a = o + j - r0;
+                    if (o + j < oend && a >= slice_end && a < region_len)
+                        acc[a] += signed_block_value<SIGN>(p, base[j], tgk, src, j);
+                }
             }
         }
     }
