@@ -230,45 +230,63 @@ __global__ __launch_bounds__(kBinBlock) void region_bin_kernel(Params p, RegionP
 }
 
 // R3: one workgroup.  starts / cursors: exclusive prefix of counts, grand total in starts[NR].
-constexpr uint32_t kScanPer = kMaxRegions / 1024u;   // regions per thread, all loaded before any is added
+// Thread t holds elements t, t + 1024, ... (coalesced loads, all requested at once); every chunk of
+// 1024 is scanned inside the wavefronts by shuffles, and the 32 x 16 (chunk, wavefront) totals are
+// scanned once more to give every wavefront its base in every chunk.
+constexpr uint32_t kScanPer = kMaxRegions / 1024u;
 
 __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
 {
-    __shared__ uint32_t wave_total[16];
-    const uint32_t b = threadIdx.x * kScanPer;
-    uint32_t c[kScanPer];
+    __shared__ uint32_t base[kScanPer * 16u];
+    __shared__ uint32_t upper[8];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    uint32_t c[kScanPer], incl[kScanPer];
 #pragma unroll
-    for (uint32_t k = 0; k < kScanPer; ++k) c[k] = b + k < s.NR ? s.counts[b + k] : 0u;
-    uint32_t sum = 0;
+    for (uint32_t k = 0; k < kScanPer; ++k) c[k] = k * 1024u + t < s.NR ? s.counts[k * 1024u + t] : 0u;
 #pragma unroll
-    for (uint32_t k = 0; k < kScanPer; ++k) sum += c[k];
-    // inclusive scan of the 1024 partial sums: inside each wavefront by shuffles, then across the 16
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    uint32_t incl = sum;
+    for (uint32_t k = 0; k < kScanPer; ++k) {
+        uint32_t v = c[k];
 #pragma unroll
-    for (uint32_t off = 1; off < 64u; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off);
-        if (lane >= off) incl += up;
+        for (uint32_t off = 1; off < 64u; off <<= 1) {
+            const uint32_t up = __shfl_up(v, off);
+            if (lane >= off) v += up;
+        }
+        incl[k] = v;
+        if (lane == 63u) base[k * 16u + wave] = v;
     }
-    if (lane == 63u) wave_total[wave] = incl;
+    __syncthreads();
+    // exclusive scan of the 512 totals in (chunk, wavefront) order, by the first 512 threads
+    uint32_t x = 0, xi = 0;
+    if (t < kScanPer * 16u) {
+        x = base[t];
+        xi = x;
+#pragma unroll
+        for (uint32_t off = 1; off < 64u; off <<= 1) {
+            const uint32_t up = __shfl_up(xi, off);
+            if (lane >= off) xi += up;
+        }
+        if (lane == 63u) upper[wave] = xi;
+    }
     __syncthreads();
     uint32_t before = 0, total = 0;
 #pragma unroll
-    for (uint32_t k = 0; k < 16u; ++k) {
-        const uint32_t t = wave_total[k];
-        before += k < wave ? t : 0u;
-        total += t;
+    for (uint32_t w = 0; w < 8u; ++w) {
+        const uint32_t u = upper[w];
+        before += w < wave ? u : 0u;
+        total += u;
     }
-    uint32_t a = before + incl - sum;                          // exclusive prefix of this thread's share
+    if (t < kScanPer * 16u) base[t] = before + xi - x;
+    __syncthreads();
 #pragma unroll
     for (uint32_t k = 0; k < kScanPer; ++k) {
-        if (b + k < s.NR) {
-            s.starts[b + k] = a;
-            s.cursors[b + k] = a;
+        const uint32_t i = k * 1024u + t;
+        if (i < s.NR) {
+            const uint32_t a = base[k * 16u + wave] + incl[k] - c[k];
+            s.starts[i] = a;
+            s.cursors[i] = a;
         }
-        a += c[k];
     }
-    if (threadIdx.x == 1023) s.starts[s.NR] = total;
+    if (t == 0) s.starts[s.NR] = total;
 }
 
 // ---------------------------------------------------------------------------------------------
