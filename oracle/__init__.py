@@ -63,6 +63,10 @@ def _load():
         L.oracle_forward.argtypes = [vp, u64, u64, u32, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp, ctypes.c_int]
         L.oracle_backward.restype = None
         L.oracle_backward.argtypes = [vp, u64, u64, u32, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp, vp, ctypes.c_int]
+        L.oracle_forward_mixed.restype = None
+        L.oracle_forward_mixed.argtypes = [vp, u64, u64, vp, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp]
+        L.oracle_backward_mixed.restype = None
+        L.oracle_backward_mixed.argtypes = [vp, u64, u64, vp, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp, vp]
         L.oracle_adagrad.restype = None
         L.oracle_adagrad.argtypes = [vp, vp, vp, u64, ctypes.c_double, ctypes.c_double, ctypes.c_int]
         L.oracle_sgd.restype = None
@@ -174,6 +178,45 @@ def backward(H: Hash, grad_out, indices, bag_offsets, batch: int, F: int, thread
     ab = np.zeros(H.m, dtype=np.float64) if want_abs else None
     _load().oracle_backward(H._c(), H.P, H.m, H.d, H.Z, H.use_sign, _ptr(go), _ptr(ind), _ptr(off),
                             batch, F, _ptr(ga), _ptr(ab), threads)
+    return ga, ab
+
+
+def _check_dims(H: Hash, dims) -> np.ndarray:
+    dm = np.ascontiguousarray(dims, dtype=np.uint32).ravel()
+    for d in dm.tolist():
+        if d < 1 or not (d % H.Z == 0 or H.Z % d == 0):
+            raise ValueError("every table dimension must be a multiple or a divisor of Z")
+    return dm
+
+
+def forward_mixed(H: Hash, dims, array, indices, bag_offsets, batch: int) -> np.ndarray:
+    """Tables of different dimensions (H.d is not used): returns float32[batch, sum(dims)]."""
+    dm = _check_dims(H, dims)
+    F = dm.size
+    arr = _f32(array)
+    assert arr.size == H.m
+    ind = _i64(indices).ravel()
+    off = None if bag_offsets is None else _i64(bag_offsets)
+    _check_bags(ind, off, batch * F)
+    out = np.empty((batch, int(dm.sum())), dtype=np.float32)
+    _load().oracle_forward_mixed(H._c(), H.P, H.m, _ptr(dm), H.Z, H.use_sign, _ptr(arr), _ptr(ind), _ptr(off),
+                                 batch, F, _ptr(out))
+    return out
+
+
+def backward_mixed(H: Hash, dims, grad_out, indices, bag_offsets, batch: int):
+    """Returns (grad_array float64[m], abs_sum float64[m]), both from zero."""
+    dm = _check_dims(H, dims)
+    F = dm.size
+    go = _f32(grad_out)
+    assert go.size == batch * int(dm.sum())
+    ind = _i64(indices).ravel()
+    off = None if bag_offsets is None else _i64(bag_offsets)
+    _check_bags(ind, off, batch * F)
+    ga = np.zeros(H.m, dtype=np.float64)
+    ab = np.zeros(H.m, dtype=np.float64)
+    _load().oracle_backward_mixed(H._c(), H.P, H.m, _ptr(dm), H.Z, H.use_sign, _ptr(go), _ptr(ind), _ptr(off),
+                                  batch, F, _ptr(ga), _ptr(ab))
     return ga, ab
 
 

@@ -201,6 +201,78 @@ void oracle_backward(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t d,
 }
 
 /*
+ * Tables of different embedding dimensions sharing the one array (Section 3.2,
+ * "Multiple embedding tables": all tables, even with varying dimensions, share
+ * the array; the table id is an argument of h and g).  Table f has dimension
+ * dims[f]; its embedding is the same construction with d = dims[f].  A sample's
+ * output is the concatenation of its F embeddings: row b of out holds
+ * D = sum(dims) floats, table f at column col[f] = dims[0] + ... + dims[f-1].
+ * Single-hot (offsets == NULL) copies with an exact sign flip; bags sum in double.
+ */
+void oracle_forward_mixed(const uint64_t coef[8], uint64_t P, uint64_t m, const uint32_t *dims, uint32_t Z,
+                          int use_sign, const float *array, const int64_t *indices, const int64_t *offsets,
+                          int64_t batch, int32_t F, float *out)
+{
+    int64_t D = 0;
+    for (int32_t f = 0; f < F; ++f) D += dims[f];
+    for (int64_t b = 0; b < batch; ++b) {
+        int64_t col = 0;
+        for (int32_t f = 0; f < F; ++f) {
+            int64_t k = b * (int64_t)F + f;
+            uint32_t d = dims[f];
+            int64_t t0 = offsets ? offsets[k] : k;
+            int64_t t1 = offsets ? offsets[k + 1] : k + 1;
+            for (uint32_t i = 0; i < d; ++i) {
+                float *dst = &out[b * D + col + i];
+                if (offsets == NULL) {
+                    uint64_t x = (uint64_t)indices[k];
+                    float v = array[oracle_idx(coef, P, m, d, Z, (uint64_t)f, x, i)];
+                    *dst = oracle_g(coef, P, use_sign, (uint64_t)f, x, i) < 0 ? -v : v;
+                    continue;
+                }
+                double acc = 0.0;
+                for (int64_t t = t0; t < t1; ++t) {
+                    uint64_t x = (uint64_t)indices[t];
+                    acc += (double)oracle_g(coef, P, use_sign, (uint64_t)f, x, i) *
+                           (double)array[oracle_idx(coef, P, m, d, Z, (uint64_t)f, x, i)];
+                }
+                *dst = (float)acc;
+            }
+            col += d;
+        }
+    }
+}
+
+/* Backward of the above (backward-pass equation of Section 3.1 with d = dims[f] per table);
+ * grad_out has the layout of out.  Accumulates into double buffers; abs_sum may be NULL. */
+void oracle_backward_mixed(const uint64_t coef[8], uint64_t P, uint64_t m, const uint32_t *dims, uint32_t Z,
+                           int use_sign, const float *grad_out, const int64_t *indices, const int64_t *offsets,
+                           int64_t batch, int32_t F, double *grad_array, double *abs_sum)
+{
+    int64_t D = 0;
+    for (int32_t f = 0; f < F; ++f) D += dims[f];
+    for (int64_t b = 0; b < batch; ++b) {
+        int64_t col = 0;
+        for (int32_t f = 0; f < F; ++f) {
+            int64_t k = b * (int64_t)F + f;
+            uint32_t d = dims[f];
+            int64_t t0 = offsets ? offsets[k] : k;
+            int64_t t1 = offsets ? offsets[k + 1] : k + 1;
+            for (int64_t t = t0; t < t1; ++t) {
+                uint64_t x = (uint64_t)indices[t];
+                for (uint32_t i = 0; i < d; ++i) {
+                    uint64_t j = oracle_idx(coef, P, m, d, Z, (uint64_t)f, x, i);
+                    double term = (double)oracle_g(coef, P, use_sign, (uint64_t)f, x, i) * (double)grad_out[b * D + col + i];
+                    grad_array[j] += term;
+                    if (abs_sum) abs_sum[j] += fabs(term);
+                }
+            }
+            col += d;
+        }
+    }
+}
+
+/*
  * Adagrad step (Duchi, Hazan, Singer 2011; not part of the paper, named by the
  * workload): for every slot j, in double on float-stored operands,
  *   s'[j] = s[j] + g[j]^2 ;  M'[j] = M[j] - lr * g[j] / (sqrt(s'[j]) + eps) ;  g[j] = 0.

@@ -279,3 +279,72 @@ def test_inner_product_estimator_is_unbiased_over_hash_draws():
         est.append(float(xh @ yh))
     est = np.array(est)
     assert abs(est.mean() - true) < 4 * est.std() / np.sqrt(len(est)) + 1e-9
+
+
+# ---------------------------------------------------------------------------------------------
+# Tables of different dimensions sharing the array (Section 3.2, "Multiple embedding tables")
+# ---------------------------------------------------------------------------------------------
+MIXED = [(11, 101, (8, 4, 16, 4), 4, 1), (12, 37, (16, 8, 8), 8, 0), (13, 64, (3, 6, 9, 3), 3, 1),
+         (14, 50, (5, 1, 2), 1, 1), (15, 16, (16, 16), 16, 0)]
+
+
+@pytest.mark.parametrize("seed,m,dims,Z,sign", MIXED)
+def test_mixed_dimensions_are_per_table_embeddings_side_by_side(seed, m, dims, Z, sign):
+    # every table's slice of a sample's row is that table's embedding, built from the two-piece
+    # circular reads of the forward equation with d = dims[f]
+    F, B = len(dims), 5
+    H = oracle.init_hash(seed, m, max(dims), Z, sign)
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(0, 40, size=(B, F))
+    M = rng.standard_normal(m).astype(np.float32)
+    out = oracle.forward_mixed(H, dims, M, ids, None, B)
+    assert out.shape == (B, sum(dims))
+    col = np.concatenate([[0], np.cumsum(dims)])
+    for b in range(B):
+        for f in range(F):
+            want = brute.embedding(H.coef, P, M, dims[f], Z, sign, f, int(ids[b, f]))
+            assert out[b, col[f]:col[f + 1]].tobytes() == np.array(want, dtype=np.float32).tobytes()
+
+
+@pytest.mark.parametrize("seed,m,dims,Z,sign", MIXED)
+def test_mixed_forward_and_backward_equal_the_sketching_matrix(seed, m, dims, Z, sign):
+    # rows of S: one per (sample, table, element) in output order; forward = S M, backward = S^T G
+    F, B = len(dims), 3
+    H = oracle.init_hash(seed, m, max(dims), Z, sign)
+    rng = np.random.default_rng(seed + 100)
+    flat = rng.integers(0, 30, size=40)
+    sizes = rng.integers(0, 4, size=B * F)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    flat = flat[:off[-1]]
+    M = rng.standard_normal(m).astype(np.float32)
+    D = sum(dims)
+    S = np.zeros((B * D, m))
+    col = np.concatenate([[0], np.cumsum(dims)])
+    for b in range(B):
+        for f in range(F):
+            k = b * F + f
+            toks = [(f, int(x)) for x in flat[off[k]:off[k + 1]]]
+            if toks:
+                St = brute.sketch_matrix(H.coef, P, m, dims[f], Z, sign, toks)      # (len * d_f) x m
+                S[b * D + col[f]: b * D + col[f + 1]] = St.reshape(len(toks), dims[f], m).sum(axis=0)
+    out = oracle.forward_mixed(H, dims, M, flat, off, B)
+    assert np.allclose(out.ravel(), S @ M.astype(np.float64), rtol=0, atol=1e-6)
+    G = rng.standard_normal((B, D)).astype(np.float32)
+    ga, ab = oracle.backward_mixed(H, dims, G, flat, off, B)
+    assert np.allclose(ga, S.T @ G.ravel().astype(np.float64), rtol=0, atol=1e-12)
+    assert np.allclose(ab, np.abs(S).T @ np.abs(G.ravel().astype(np.float64)), rtol=0, atol=1e-12)
+
+
+def test_mixed_with_equal_dimensions_is_the_uniform_path():
+    H = oracle.init_hash(3, 997, 8, 4, 1)
+    rng = np.random.default_rng(3)
+    B, F = 6, 4
+    ids = rng.integers(0, 100, size=(B, F))
+    M = rng.standard_normal(997).astype(np.float32)
+    G = rng.standard_normal((B, F, 8)).astype(np.float32)
+    assert oracle.forward_mixed(H, [8] * F, M, ids, None, B).tobytes() == oracle.forward(H, M, ids, None, B, F).tobytes()
+    ga, ab = oracle.backward_mixed(H, [8] * F, G, ids, None, B)
+    gu, au = oracle.backward(H, G, ids, None, B, F)
+    assert np.array_equal(ga, gu) and np.array_equal(ab, au)
+    with pytest.raises(ValueError):
+        oracle.forward_mixed(H, [8, 6], M, ids[:, :2], None, B)      # 6 is neither a multiple nor a divisor of 4
