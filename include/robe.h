@@ -202,6 +202,26 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
                           float lr, float eps, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Tables of different embedding dimensions sharing the one array (Section 3.2, "Multiple embedding
+ * tables": all tables, even with varying dimensions, share the array; the table id is an argument of
+ * h and g).  Table f has dimension dims[f], a positive multiple of Z; its embedding is Eq. 4 / Eq. 5
+ * with d = dims[f] (hash->d is not used).  A sample's row is the concatenation of its tables'
+ * embeddings: out and grad_out are device float[batch][D], D = dims[0] + ... + dims[n_features-1],
+ * table f at column dims[0] + ... + dims[f-1].  indices / offsets / n_indices / batch are as in
+ * robe_forward; dims is a HOST array of n_features entries, read during the call only.
+ * One launch is made per run of consecutive tables of equal dimension.  robe_backward_mixed
+ * accumulates onto grad_array like robe_backward, always with float atomics (no workspace; it is
+ * refused while the reproducible switch is on); follow it with robe_adagrad_update / robe_sgd_update.
+ * Errors: ROBE_EINVAL (also: a dims entry that is zero or not a multiple of Z), ROBE_EHIP.
+ */
+int robe_forward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *array,
+                       const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                       int64_t batch, int32_t n_features, float *out, void *stream);
+int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out,
+                        const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                        int64_t batch, int32_t n_features, float *grad_array, void *stream);
+
+/*
  * Run-to-run reproducible scatter (process-wide switch, off at start; returns the previous setting).
  * Eq. 3 sums float32 terms whose order the paper does not fix; with float atomics that order, and so
  * the last bits of the result, change from run to run.  While the switch is on, robe_backward and

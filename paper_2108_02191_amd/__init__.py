@@ -46,7 +46,7 @@ class RobeHash(ctypes.Structure):
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
-           "robe_set_reproducible", "robe_last_error")
+           "robe_forward_mixed", "robe_backward_mixed", "robe_set_reproducible", "robe_last_error")
 
 _lib = None
 
@@ -80,6 +80,10 @@ def lib() -> ctypes.CDLL:
         L.robe_backward_adagrad.restype = ctypes.c_int
         L.robe_backward_adagrad.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_float, ctypes.c_float,
                                             vp, ctypes.c_size_t, vp]
+        for fn in (L.robe_forward_mixed, L.robe_backward_mixed):
+            fn.restype = ctypes.c_int
+            fn.argtypes = [HP, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                           ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
         L.robe_set_reproducible.restype = ctypes.c_int
         L.robe_set_reproducible.argtypes = [ctypes.c_int]
         L.robe_last_error.restype = ctypes.c_char_p
@@ -210,3 +214,43 @@ def robe_backward_adagrad(h: RobeHash, grad_out: torch.Tensor, indices: torch.Te
 def robe_set_reproducible(on: bool) -> bool:
     """Process-wide switch for the run-to-run reproducible scatter; returns the previous setting."""
     return bool(lib().robe_set_reproducible(1 if on else 0))
+
+
+def _dims_array(dims):
+    arr = (ctypes.c_uint32 * len(dims))(*[int(d) for d in dims])
+    return arr
+
+
+def robe_forward_mixed(h: RobeHash, dims, array: torch.Tensor, indices: torch.Tensor,
+                       offsets: Optional[torch.Tensor], batch: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Forward for tables of different dimensions: returns float32[batch, sum(dims)]."""
+    F, D = len(dims), int(sum(dims))
+    if array.numel() != h.m:
+        raise ValueError("array length differs from hash.m")
+    if offsets is not None and offsets.numel() != batch * F + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    if out is None:
+        out = torch.empty((batch, D), dtype=torch.float32, device=array.device)
+    elif out.numel() != batch * D:
+        raise ValueError("out has the wrong size")
+    da = _dims_array(dims)
+    _check(lib().robe_forward_mixed(ctypes.byref(h), ctypes.cast(da, ctypes.c_void_p), _dev(array, torch.float32, "array"),
+                                    _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                                    indices.numel(), batch, F, _dev(out, torch.float32, "out"), _stream()))
+    return out
+
+
+def robe_backward_mixed(h: RobeHash, dims, grad_out: torch.Tensor, indices: torch.Tensor,
+                        offsets: Optional[torch.Tensor], batch: int, grad_array: torch.Tensor) -> None:
+    """Backward for tables of different dimensions (accumulates onto grad_array)."""
+    F, D = len(dims), int(sum(dims))
+    if grad_array.numel() != h.m:
+        raise ValueError("grad_array length differs from hash.m")
+    if grad_out.numel() != batch * D:
+        raise ValueError("grad_out has the wrong size")
+    if offsets is not None and offsets.numel() != batch * F + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    da = _dims_array(dims)
+    _check(lib().robe_backward_mixed(ctypes.byref(h), ctypes.cast(da, ctypes.c_void_p), _dev(grad_out, torch.float32, "grad_out"),
+                                     _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                                     indices.numel(), batch, F, _dev(grad_array, torch.float32, "grad_array"), _stream()))

@@ -158,14 +158,30 @@ int env_int(const char *name, int dflt)
     return v ? atoi(v) : dflt;
 }
 
+// Where a launch's tables sit inside a sample's input row and output row (see robe::Geom).
+struct TableView {
+    uint32_t F_in, e0;
+    int64_t row_floats, col0;
+};
+
 template <bool BWD>
 int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, const int64_t *offsets,
-                int64_t n_indices, int64_t rows, uint32_t F, float *dst, const void *rows_ptr, hipStream_t stream)
+                int64_t n_indices, int64_t rows, uint32_t F, float *dst, const void *rows_ptr, hipStream_t stream,
+                const TableView *view = nullptr)
 {
     const robe::Params p = to_params(h);
     const Layout lay = pick_layout(h, BWD, rows_ptr);
     const bool sign = h->use_sign != 0;
     const bool bags = offsets != nullptr;
+
+    robe::Geom q;
+    memset(&q, 0, sizeof(q));
+    q.F = F;
+    q.batch = rows / (int64_t)F;
+    q.F_in = view ? view->F_in : F;
+    q.e0 = view ? view->e0 : 0u;
+    q.row_floats = view ? view->row_floats : (int64_t)F * h->d;
+    q.col0 = view ? view->col0 : 0;
 
     if (lay.V == 0) {
         uint32_t rpb = robe::kBlock / h->d;
@@ -173,14 +189,12 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
         const int64_t blocks = (rows + rpb - 1) / rpb;
         if (blocks > 0x7FFFFFFFll) return fail(ROBE_EINVAL, "too many rows for one launch");
         if (sign)
-            robe::generic_kernel<true, BWD><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, F, rpb, src, indices, offsets, rows, n_indices, dst);
+            robe::generic_kernel<true, BWD><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, q, rpb, src, indices, offsets, rows, n_indices, dst);
         else
-            robe::generic_kernel<false, BWD><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, F, rpb, src, indices, offsets, rows, n_indices, dst);
+            robe::generic_kernel<false, BWD><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, q, rpb, src, indices, offsets, rows, n_indices, dst);
         return check_launch(BWD ? "backward (generic)" : "forward (generic)");
     }
 
-    robe::Geom q;
-    q.F = F;
     q.G = lay.G;
     q.g_shift = log2u(lay.G);
     const uint32_t step = 64u / lay.G;
@@ -195,7 +209,6 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
     int64_t blocks = (waves + robe::kWavesPerBlock - 1) / robe::kWavesPerBlock;
     // Walk the rows table by table, one eighth of that order per XCD (see RowWalk), unless the launch
     // is too small to matter.  ROBE_TUNE_XCD=0 keeps the memory order.
-    q.batch = rows / (int64_t)F;
     q.bpx = 0;
     // It pays where array reads dominate the traffic: bags (many blocks read per row written) and
     // blocks of at most one 64-byte sector (several sectors fetched per sector used).  For single-hot
@@ -411,12 +424,10 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     if (st != hipSuccess) return fail(ROBE_EHIP, "backward (sort): %s", hipGetErrorString(st));
 
     robe::Geom q;
+    memset(&q, 0, sizeof(q));
     q.F = F;
     q.G = pl.lay.G;
     q.g_shift = log2u(pl.lay.G);
-    q.TL = 0;
-    q.bpx = 0;
-    q.batch = 0;
     const uint64_t blocks = ((uint64_t)n + robe::kBlock - 1) / robe::kBlock;   // one lane per sorted position
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
 
@@ -527,6 +538,46 @@ int check_rows(const robe_hash_t *h, const int64_t *indices, const int64_t *offs
     return ROBE_OK;
 }
 
+// Tables of mixed dimensions: one launch per run of consecutive tables of one dimension, each a view
+// into the [batch][n_features] inputs and the [batch][sum(dims)] rows.
+template <bool BWD>
+int launch_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *src, const int64_t *indices,
+                        const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features, float *dst,
+                        const float *rows_ptr, void *stream)
+{
+    int64_t rows = 0;
+    if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
+    if (dims == nullptr) return fail(ROBE_EINVAL, "dims is NULL");
+    int64_t D = 0;
+    for (int32_t f = 0; f < n_features; ++f) {
+        if (dims[f] < 1 || dims[f] % hash->Z != 0)
+            return fail(ROBE_EINVAL, "dims[%d] = %u is not a positive multiple of Z = %u", f, dims[f], hash->Z);
+        D += dims[f];
+        if (D > 0x7FFFFFFFll) return fail(ROBE_EINVAL, "sum of dims exceeds 2^31 - 1");
+    }
+    if (batch > (int64_t)0x7FFFFFFFFFFFFFll / D) return fail(ROBE_EINVAL, "batch * sum(dims) overflows");
+    if (rows == 0) return ROBE_OK;
+    if (src == nullptr || dst == nullptr) return fail(ROBE_EINVAL, BWD ? "grad_out or grad_array is NULL" : "array or out is NULL");
+    if (!aligned(src, 4) || !aligned(dst, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    int64_t col = 0;
+    for (int32_t f0 = 0; f0 < n_features;) {
+        int32_t f1 = f0 + 1;
+        while (f1 < n_features && dims[f1] == dims[f0]) ++f1;
+        robe_hash_t h = *hash;
+        h.d = dims[f0];
+        const TableView view = {(uint32_t)n_features, (uint32_t)f0, D, col};
+        // the vector layouts need every row start of this view on a vector boundary
+        const uintptr_t probe = (uintptr_t)rows_ptr | (uintptr_t)(D * 4) | (uintptr_t)(col * 4);
+        const uint32_t Fv = (uint32_t)(f1 - f0);
+        if (int rc = launch_rows<BWD>(&h, src, indices, offsets, n_indices, batch * (int64_t)Fv, Fv, dst,
+                                      reinterpret_cast<const void *>(probe), (hipStream_t)stream, &view))
+            return rc;
+        col += (int64_t)Fv * dims[f0];
+        f0 = f1;
+    }
+    return ROBE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -621,6 +672,22 @@ int robe_backward(const robe_hash_t *hash, const float *grad_out, const int64_t 
         return launch_dedup_backward(hash, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
                                       grad_array, workspace, (hipStream_t)stream);
     return launch_rows<true>(hash, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad_array, grad_out, (hipStream_t)stream);
+}
+
+int robe_forward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *array, const int64_t *indices,
+                       const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features, float *out,
+                       void *stream)
+{
+    return launch_mixed<false>(hash, dims, array, indices, offsets, n_indices, batch, n_features, out, out, stream);
+}
+
+int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out, const int64_t *indices,
+                        const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features,
+                        float *grad_array, void *stream)
+{
+    if (g_reproducible.load(std::memory_order_relaxed)) return fail_not_reproducible();
+    return launch_mixed<true>(hash, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
+                              grad_out, stream);
 }
 
 int robe_set_reproducible(int on)

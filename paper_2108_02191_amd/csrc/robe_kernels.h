@@ -35,6 +35,20 @@ struct Geom {
     uint32_t TL;       // rows per wavefront tile (single-hot kernels), multiple of 64/G, <= 64 (0: unused)
     uint32_t bpx;      // workgroups per XCD when rows are walked table by table (0: walk rows in memory order)
     int64_t batch;     // rows = batch * F
+    // Where the F tables of this launch sit in the caller's buffers.  A plain call covers all of a
+    // sample's tables (F_in = F, e0 = 0, row_floats = F * d, col0 = 0); a call for tables of mixed
+    // dimensions launches once per run of consecutive tables of one dimension.
+    uint32_t F_in;       // tables per sample in indices / offsets
+    uint32_t e0;         // table id of this launch's first table = its place in a sample's input row
+    int64_t row_floats;  // floats per sample in out / grad_out
+    int64_t col0;        // first float of this launch's first table inside a sample
+};
+
+// One row of a launch: where its id (or bag bounds) and its d floats live, and its table id.
+struct RowRef {
+    int64_t in_row;    // index into indices (single-hot) or offsets (bags)
+    int64_t out_off;   // first float in out / grad_out
+    uint32_t e;
 };
 
 // Which rows a wavefront works on.
@@ -71,21 +85,29 @@ __device__ __forceinline__ bool start_walk(const Geom &q, int64_t rows, int64_t 
     return true;
 }
 
-// Row index k and table f of the position `ahead` steps after the wavefront's first one (ahead < 64).
-__device__ __forceinline__ int64_t walk_row(const Geom &q, const RowWalk &w, uint32_t ahead, uint32_t &f)
+// The row `ahead` steps after the wavefront's first one (ahead < 64).
+__device__ __forceinline__ RowRef walk_row(const Geom &q, const RowWalk &w, uint32_t ahead, uint32_t d)
 {
+    int64_t b;
+    uint32_t f;
     if (q.bpx) {
-        int64_t b = w.b0 + ahead;
+        b = w.b0 + ahead;
         f = w.f0;
         while (b >= q.batch) {   // crosses into the next table(s); at most `ahead` rounds
             b -= q.batch;
             ++f;
         }
-        return b * (int64_t)q.F + f;
+    } else {
+        const uint32_t t = w.f0 + ahead;  // < F + 64
+        const uint32_t over = t / q.F;
+        f = t - over * q.F;
+        b = w.b0 + over;
     }
-    const uint32_t t = w.f0 + ahead;  // < F + 64
-    f = t % q.F;
-    return w.q0 + ahead;
+    RowRef r;
+    r.in_row = b * (int64_t)q.F_in + q.e0 + f;
+    r.out_off = b * q.row_floats + q.col0 + (int64_t)f * d;
+    r.e = q.e0 + f;
+    return r;
 }
 
 template <int V>
@@ -226,11 +248,10 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
     // pass 1: lane l hashes the l-th lookup of the tile
     uint32_t th = 0, tg = 0;
     if (lane < n) {
-        uint32_t e;
-        const int64_t k = walk_row(q, w, lane, e);
-        const int64_t x = indices[k];
-        th = staged_h(p, x, e);
-        if constexpr (SIGN) tg = staged_g(p, x, e);
+        const RowRef k = walk_row(q, w, lane, p.d);
+        const int64_t x = indices[k.in_row];
+        th = staged_h(p, x, k.e);
+        if constexpr (SIGN) tg = staged_g(p, x, k.e);
     }
 
     // pass 2: groups of G lanes walk the tile, 64/G rows per step
@@ -257,17 +278,13 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
             for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u]);  // lookup 0 stands in for dead slots
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
-                if (live[u]) {
-                    uint32_t f_unused;
-                    store_row<V, CONSEC>(dst + walk_row(q, w, rl[u], f_unused) * (int64_t)p.d, q, grp, v[u]);
-                }
+                if (live[u]) store_row<V, CONSEC>(dst + walk_row(q, w, rl[u], p.d).out_off, q, grp, v[u]);
         } else {
             float v[kUnroll][V];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const uint32_t safe = live[u] ? rl[u] : 0u;
-                uint32_t f_unused;
-                load_row<V, CONSEC>(src + walk_row(q, w, safe, f_unused) * (int64_t)p.d, q, grp, v[u]);
+                load_row<V, CONSEC>(src + walk_row(q, w, safe, p.d).out_off, q, grp, v[u]);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
@@ -296,13 +313,13 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
     const uint32_t sub = lane >> q.g_shift;
     const uint32_t base_lane = lane - grp;                  // first lane of this group
     const bool have_bag = w.q0 + sub < rows;
-    uint32_t e = 0;
-    const int64_t bag = have_bag ? walk_row(q, w, sub, e) : 0;
+    const RowRef bag = walk_row(q, w, have_bag ? sub : 0u, p.d);
+    const uint32_t e = bag.e;
 
     int64_t t0 = 0, t1 = 0;
     if (have_bag) {
-        t0 = offsets[bag];
-        t1 = offsets[bag + 1];
+        t0 = offsets[bag.in_row];
+        t1 = offsets[bag.in_row + 1];
         t0 = t0 < 0 ? 0 : (t0 > n_indices ? n_indices : t0);
         t1 = t1 < t0 ? t0 : (t1 > n_indices ? n_indices : t1);
     }
@@ -314,7 +331,7 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
 #pragma unroll
     for (int k = 0; k < V; ++k) acc[k] = 0.0f;
     if constexpr (BWD) {
-        if (have_bag) load_row<V, CONSEC>(src + bag * (int64_t)p.d, q, grp, acc);
+        if (have_bag) load_row<V, CONSEC>(src + bag.out_off, q, grp, acc);
     }
 
     for (int64_t tb = t0; __any(tb < t1); tb += q.G) {
@@ -356,7 +373,7 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
         }
     }
     if constexpr (!BWD) {
-        if (have_bag) store_row<V, CONSEC>(dst + bag * (int64_t)p.d, q, grp, acc);
+        if (have_bag) store_row<V, CONSEC>(dst + bag.out_off, q, grp, acc);
     }
 }
 
@@ -365,7 +382,7 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
 // every hash evaluated in full by the thread that needs it.
 // ---------------------------------------------------------------------------
 template <bool SIGN, bool BWD>
-__global__ __launch_bounds__(kBlock) void generic_kernel(Params p, uint32_t F, uint32_t rows_per_block,
+__global__ __launch_bounds__(kBlock) void generic_kernel(Params p, Geom q, uint32_t rows_per_block,
                                                          const float *__restrict__ src,
                                                          const int64_t *__restrict__ indices,
                                                          const int64_t *__restrict__ offsets,  // NULL: single-hot
@@ -373,25 +390,28 @@ __global__ __launch_bounds__(kBlock) void generic_kernel(Params p, uint32_t F, u
                                                          float *__restrict__ dst)
 {
     const int64_t row_base = (int64_t)blockIdx.x * rows_per_block;
-    const uint32_t e_base = (uint32_t)(row_base % (int64_t)F);
     const uint64_t items = (uint64_t)rows_per_block * p.d;
     for (uint64_t local = threadIdx.x; local < items; local += kBlock) {
         const uint32_t rl = (uint32_t)(local / p.d);
         const uint32_t i = (uint32_t)(local - (uint64_t)rl * p.d);
         const int64_t row = row_base + rl;
         if (row >= rows) break;
-        const uint32_t e = (e_base + rl) % F;
+        const int64_t b = row / (int64_t)q.F;
+        const uint32_t f = (uint32_t)(row - b * (int64_t)q.F);
+        const uint32_t e = q.e0 + f;
+        const int64_t in_row = b * (int64_t)q.F_in + e;
+        const int64_t at = b * q.row_floats + q.col0 + (int64_t)f * p.d + i;   // this element in out / grad_out
         const uint32_t c = i / p.Z, j = i - c * p.Z;
         const uint32_t cc = mod_p((uint64_t)p.Ch * c);
         const uint32_t cg = SIGN ? mod_p((uint64_t)p.Cg * i) : 0u;
-        int64_t t0 = row, t1 = row + 1;
+        int64_t t0 = in_row, t1 = in_row + 1;
         if (offsets != nullptr) {
-            t0 = offsets[row];
-            t1 = offsets[row + 1];
+            t0 = offsets[in_row];
+            t1 = offsets[in_row + 1];
             t0 = t0 < 0 ? 0 : (t0 > n_indices ? n_indices : t0);
             t1 = t1 < t0 ? t0 : (t1 > n_indices ? n_indices : t1);
         }
-        float acc = BWD ? src[row * (int64_t)p.d + i] : 0.0f;
+        float acc = BWD ? src[at] : 0.0f;
         for (int64_t t = t0; t < t1; ++t) {
             const int64_t x = indices[t];
             // Z > d (Section 3.3): r = Z/d embeddings share a chunk; the chunk id x / r takes the
@@ -407,7 +427,7 @@ __global__ __launch_bounds__(kBlock) void generic_kernel(Params p, uint32_t F, u
                 acc = (offsets == nullptr) ? v : acc + v;   // single-hot keeps the sign of zero
             }
         }
-        if constexpr (!BWD) dst[row * (int64_t)p.d + i] = acc;
+        if constexpr (!BWD) dst[at] = acc;
     }
 }
 

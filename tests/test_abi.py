@@ -83,6 +83,15 @@ def test_entry_points_reject_bad_arguments_without_a_gpu():
         bad = robe.robe_init_hash(1, 1000, 16, 4, 0)
         setattr(bad, field, val)
         assert L.robe_forward(ctypes.byref(bad), fake, fake, None, 4, 2, 2, fake, None) == EINVAL, field
+    # tables of mixed dimensions: the dims array is validated on the host
+    dims_ok = (ctypes.c_uint32 * 2)(8, 4)
+    dims_bad = (ctypes.c_uint32 * 2)(8, 6)
+    assert L.robe_forward_mixed(ref, None, fake, fake, None, 4, 2, 2, fake, None) == EINVAL
+    assert L.robe_forward_mixed(ref, dims_bad, fake, fake, None, 4, 2, 2, fake, None) == EINVAL
+    assert b"dims[1]" in L.robe_last_error()
+    assert L.robe_forward_mixed(ref, dims_ok, None, fake, None, 4, 2, 2, fake, None) == EINVAL
+    assert L.robe_backward_mixed(ref, dims_ok, fake, fake, None, 5, 2, 2, fake, None) == EINVAL
+    assert L.robe_forward_mixed(ref, dims_ok, None, None, None, 0, 0, 2, None, None) == robe.ROBE_OK
     # the reproducibility switch is plain host state: returns the previous setting
     assert L.robe_set_reproducible(1) == 0
     assert L.robe_set_reproducible(0) == 1

@@ -1,0 +1,119 @@
+"""GPU parity for tables of different dimensions sharing the array (Section 3.2,
+"Multiple embedding tables"): robe_forward_mixed / robe_backward_mixed against
+the oracle's mixed functions, element by element, on seeded synthetic inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2108_02191_amd as robe
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TINY = 1e-30
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def bits_equal(a, b):
+    return np.array_equal(np.ascontiguousarray(a).ravel().view(np.int32), np.ascontiguousarray(b).ravel().view(np.int32))
+
+
+def hashes(seed, m, Z, sign, dmax):
+    h = robe.robe_init_hash(seed, m, dmax, Z, sign)
+    H = oracle.init_hash(seed, m, dmax, Z, sign)
+    assert tuple(h.coef) == H.coef
+    return h, H
+
+
+# (m, dims, Z): runs of equal dimensions, alternating ones, every lane layout, a dimension only the
+# shape-generic kernel takes (12 with Z = 3 -> 24), rows whose starts are not 16-byte aligned (Z = 1,
+# odd dimensions), an array small enough that blocks wrap
+CASES = [
+    (1_000_003, (128, 128, 64, 64, 64, 32, 128), 32),
+    (100_003, (16, 4, 4, 8, 16, 16, 4), 4),
+    (70_001, (8, 16, 8, 16, 8, 16), 8),
+    (9973, (3, 12, 24, 3, 6), 3),
+    (4099, (1, 5, 2, 7, 64, 1), 1),
+    (61, (16, 8, 8, 32), 8),
+    (500_009, (256, 512, 128), 128),
+]
+
+
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,dims,Z", CASES)
+def test_mixed_single_hot_forward_is_bit_exact_and_backward_within_tolerance(m, dims, Z, sign):
+    h, H = hashes(7 * m + Z + sign, m, Z, sign, max(dims))
+    F, B = len(dims), 257
+    rng = np.random.default_rng(m + sum(dims))
+    ids = rng.integers(0, 5000, size=(B, F), dtype=np.int64)
+    ids[rng.random((B, F)) < 0.2] = 3
+    M = rng.standard_normal(m).astype(np.float32)
+    out = robe.robe_forward_mixed(h, dims, dev(M), dev(ids), None, B).cpu().numpy()
+    assert bits_equal(out, oracle.forward_mixed(H, dims, M, ids, None, B))
+    G = rng.standard_normal((B, sum(dims))).astype(np.float32)
+    ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+    robe.robe_backward_mixed(h, dims, dev(G), dev(ids), None, B, ga)
+    ref, S = oracle.backward_mixed(H, dims, G, ids, None, B)
+    got = ga.cpu().numpy()
+    assert np.all(np.abs(got.astype(np.float64) - ref) <= 1e-5 * S + TINY)
+    assert not got[S == 0].any()
+    # accumulates onto what is there
+    robe.robe_backward_mixed(h, dims, dev(G), dev(ids), None, B, ga)
+    assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - 2 * ref) <= 2e-5 * S + TINY)
+
+
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,dims,Z", CASES)
+def test_mixed_bags_within_tolerance(m, dims, Z, sign):
+    h, H = hashes(11 * m + Z + sign, m, Z, sign, max(dims))
+    F, B = len(dims), 131
+    rng = np.random.default_rng(m + 1)
+    sizes = rng.poisson(4.0, size=B * F).astype(np.int64)
+    sizes[0] = 0
+    sizes[5] = 70
+    off = np.zeros(B * F + 1, dtype=np.int64)
+    np.cumsum(sizes, out=off[1:])
+    flat = rng.integers(0, 3000, size=int(off[-1]), dtype=np.int64)
+    M = rng.standard_normal(m).astype(np.float32)
+    out = robe.robe_forward_mixed(h, dims, dev(M), dev(flat), dev(off), B).cpu().numpy()
+    want = oracle.forward_mixed(H, dims, M, flat, off, B)
+    H_abs = oracle.Hash(H.m, H.d, H.Z, 0, H.P, H.coef)
+    S = oracle.forward_mixed(H_abs, dims, np.abs(M), flat, off, B).astype(np.float64)
+    assert np.all(np.abs(out.astype(np.float64) - want) <= 1e-5 * S + TINY)
+    G = rng.standard_normal((B, sum(dims))).astype(np.float32)
+    ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+    robe.robe_backward_mixed(h, dims, dev(G), dev(flat), dev(off), B, ga)
+    ref, Sb = oracle.backward_mixed(H, dims, G, flat, off, B)
+    assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * Sb + TINY)
+
+
+def test_mixed_with_equal_dimensions_is_the_plain_forward_bitwise():
+    h, H = hashes(5, 250_007, 32, 1, 128)
+    rng = np.random.default_rng(5)
+    B, F = 300, 26
+    ids = rng.integers(0, 10**6, size=(B, F), dtype=np.int64)
+    M = rng.standard_normal(250_007).astype(np.float32)
+    a = robe.robe_forward_mixed(h, [128] * F, dev(M), dev(ids), None, B).cpu().numpy()
+    b = robe.robe_forward(h, dev(M), dev(ids), None, B, F).cpu().numpy()
+    assert bits_equal(a, b)
+
+
+def test_mixed_rejects_bad_dimensions_and_the_reproducible_switch():
+    h, _ = hashes(1, 1000, 4, 0, 16)
+    ids = dev(np.zeros((2, 3), dtype=np.int64))
+    M = torch.zeros(1000, dtype=torch.float32, device=DEV)
+    for dims in ([16, 6, 4], [16, 0, 4], [2, 4, 4]):
+        with pytest.raises(robe.RobeError) as ei:
+            robe.robe_forward_mixed(h, dims, M, ids, None, 2)
+        assert ei.value.code == robe.ROBE_EINVAL
+    robe.robe_set_reproducible(True)
+    try:
+        with pytest.raises(robe.RobeError):
+            robe.robe_backward_mixed(h, [16, 4, 4], torch.zeros((2, 24), dtype=torch.float32, device=DEV), ids, None, 2, M)
+    finally:
+        robe.robe_set_reproducible(False)
+    assert robe.robe_forward_mixed(h, [16, 4, 4], M, dev(np.zeros((0, 3), dtype=np.int64)), None, 0).shape == (0, 24)
