@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="multihot",
-                    help="multihot | training | inference | sweep_z{1,8,32,128} | kaggle_z{1,2,4,8,16} | tiny")
+                    help="multihot | training | inference | sweep_z{1,8,32,128} | kaggle_z{1,2,4,8,16} | mixed_dims | tiny")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0: as defined)")
     ap.add_argument("--m", type=int, default=0, help="override the array length in floats (0: as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -53,6 +53,11 @@ def parse():
 
 def algorithmic_bytes(w, rows, tokens, touched):
     """Bytes the method itself must move per launch (d floats per vector, 8-byte ids)."""
+    if w.dims is not None:    # single-hot, one vector of dims[f] floats per (sample, table)
+        D, F = sum(w.dims), w.n_features
+        fwd = w.batch * (8 * D + 8 * F)
+        bwd = w.batch * (12 * D + 8 * F)
+        return {"fwd": fwd, "bwd": bwd, "adagrad": touched * 24, "sgd": touched * 16, "bwd_adagrad": bwd + touched * 24}
     vec = 4 * w.d
     bags = w.bag_mean is not None
     fwd = tokens * (vec + 8) + rows * vec + (rows + 1) * 8 * bags
@@ -86,6 +91,8 @@ def cpu_baseline(w, M, ids, off, G, target_s):
     H = oracle.init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
     threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
     F = w.n_features
+    if w.dims is not None:
+        threads = 1             # the oracle's mixed-dimension loops are sequential
 
     def sub(bs):
         rows = bs * F
@@ -97,11 +104,17 @@ def cpu_baseline(w, M, ids, off, G, target_s):
     def run(bs):
         i_, o_, g_, ntok = sub(bs)
         t0 = time.perf_counter()
-        oracle.forward(H, M, i_, o_, bs, F, threads=threads)
+        if w.dims is not None:
+            oracle.forward_mixed(H, w.dims, M, i_, o_, bs)
+        else:
+            oracle.forward(H, M, i_, o_, bs, F, threads=threads)
         t1 = time.perf_counter()
         tb = 0.0
         if "bwd" in w.phases:
-            oracle.backward(H, g_, i_, o_, bs, F, threads=threads, want_abs=False)
+            if w.dims is not None:
+                oracle.backward_mixed(H, w.dims, g_, i_, o_, bs)
+            else:
+                oracle.backward(H, g_, i_, o_, bs, F, threads=threads, want_abs=False)
             tb = time.perf_counter() - t1
         return ntok, t1 - t0, tb
 
@@ -167,10 +180,11 @@ def main():
     Md = torch.from_numpy(M).to(dev)
     dev_batches = [(torch.from_numpy(i).to(dev), None if o is None else torch.from_numpy(o).to(dev)) for i, o in batches]
     Gd = torch.from_numpy(G).to(dev)
-    out = torch.empty((B, F, w.d), dtype=torch.float32, device=dev)
+    mixed = w.dims is not None
+    out = torch.empty((B, sum(w.dims)) if mixed else (B, F, w.d), dtype=torch.float32, device=dev)
     ga = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_bwd else None
     st = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_ada else None
-    ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n) for n in tokens) if do_bwd else 0
+    ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n) for n in tokens) if (do_bwd and w.dims is None) else 0
     fused = do_ada and not args.unfused
     fws_bytes = max(robe.robe_fused_workspace_bytes(h, B, F, n) for n in tokens) if fused else 0
     ws = torch.empty(max(ws_bytes, fws_bytes, 1), dtype=torch.uint8, device=dev) if max(ws_bytes, fws_bytes) else None
@@ -181,10 +195,20 @@ def main():
         idd, offd = dev_batches[k % len(dev_batches)]
         if ev:
             ev[0].record(stream)
-        robe.robe_forward(h, Md, idd, offd, B, F, out=out)
+        if mixed:
+            robe.robe_forward_mixed(h, w.dims, Md, idd, offd, B, out=out)
+        else:
+            robe.robe_forward(h, Md, idd, offd, B, F, out=out)
         if ev:
             ev[1].record(stream)
-        if fused:
+        if mixed:
+            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga)
+            if ev:
+                ev[2].record(stream)
+            ga.zero_()
+            if ev:
+                ev[3].record(stream)
+        elif fused:
             robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Md, st, w.lr, w.eps, workspace=ws)
             if ev:
                 ev[3].record(stream)
@@ -205,7 +229,10 @@ def main():
     touched = 0
     if do_bwd:
         idd, offd = dev_batches[0]
-        robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
+        if mixed:
+            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga)
+        else:
+            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
         touched = int((ga != 0).sum().item())
         ga.zero_()
 
@@ -367,6 +394,9 @@ def main():
                                   "write-back on large arrays, scatter + update_kernel on small ones)",
                    "bwd": "robe_backward (every kernel of the call: "
                           + ("token keys, radix sort, then combine + scatter" if ws_bytes else "direct scatter kernel") + ")"}
+    if mixed:
+        entry_names["fwd"] = "robe_forward_mixed (one launch per run of equal dimensions)"
+        entry_names["bwd"] = "robe_backward_mixed (direct scatter, one launch per run of equal dimensions)"
     result = {
         "metric": "ROBE lookups/sec, whole step (fwd%s%s), d=%d, Z=%d" % (
             "+bwd" if do_bwd else "", "+Adagrad" if do_ada else ("+SGD" if do_sgd else ""), w.d, w.Z)
@@ -377,7 +407,7 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "m": w.m, "array_bytes": 4 * w.m, "d": w.d, "Z": w.Z, "batch": B,
+        "config": {"workload": w.name, "m": w.m, "array_bytes": 4 * w.m, "d": list(w.dims) if w.dims else w.d, "Z": w.Z, "batch": B,
                    "n_features": F, "rows": rows, "tokens_per_step": tok, "bag_mean": w.bag_mean,
                    "ids": f"{w.id_dist}({w.zipf_alpha})" if w.id_dist == "zipf" else w.id_dist,
                    "use_sign": w.use_sign, "phases": w.phases, "id_batches": len(batches),

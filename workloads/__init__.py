@@ -39,6 +39,7 @@ class Workload:
     lr: float = 0.01
     eps: float = 1e-8
     hash_seed: int = 2108_02191
+    dims: Optional[Tuple[int, ...]] = None   # per-table dimensions (tables of mixed dimensions); None: all d
 
     @property
     def rows(self) -> int:
@@ -76,6 +77,13 @@ def get(name: str) -> Workload:
         Z = int(name[len("kaggle_z"):])
         return Workload(name, 540_000, 16, Z, 2048, N_FEATURES, KAGGLE_CARDINALITIES, "zipf", 1.05, 0, None,
                         "fwd+bwd+sgd", lr=1.0)
+    if name == "mixed_dims":
+        # Tables of different dimensions in one array (Section 3.2, "Multiple embedding tables").  The
+        # paper runs no such configuration; this one keeps the inference shapes and gives the small
+        # tables small dimensions: 16 / 32 / 64 / 128 for the four quarters of the log-spaced sizes.
+        dims = tuple(16 if f < 6 else 32 if f < 12 else 64 if f < 19 else 128 for f in range(N_FEATURES))
+        return Workload("mixed_dims", 25_000_000, 128, 16, 32768, N_FEATURES, ls, "zipf", 1.05, 0, None, "fwd+bwd",
+                        dims=dims)
     if name == "multihot":
         return Workload("multihot", 250_000_000, 128, 32, 16384, N_FEATURES, (40_000_000,) * N_FEATURES,
                         "zipf", 1.05, 0, 20.0, "fwd+bwd+adagrad")
@@ -83,7 +91,7 @@ def get(name: str) -> Workload:
 
 
 ALL = ("tiny", "inference", "training", "sweep_z1", "sweep_z8", "sweep_z32", "sweep_z128", "multihot",
-       "kaggle_z1", "kaggle_z2", "kaggle_z4", "kaggle_z8", "kaggle_z16")
+       "kaggle_z1", "kaggle_z2", "kaggle_z4", "kaggle_z8", "kaggle_z16", "mixed_dims")
 
 
 def make_array(m: int, seed: int = 0) -> np.ndarray:
@@ -170,6 +178,8 @@ def _ragged_arange(counts: np.ndarray) -> np.ndarray:
 
 
 def make_grad_out(w: Workload, seed: int = 2) -> np.ndarray:
-    """float32[batch, F, d] ~ normal(0, 1)."""
+    """float32[batch, F, d] ~ normal(0, 1) (tables of mixed dimensions: float32[batch, sum(dims)])."""
     rng = np.random.default_rng(seed)
+    if w.dims is not None:
+        return rng.standard_normal((w.batch, sum(w.dims)), dtype=np.float32)
     return rng.standard_normal((w.batch, w.n_features, w.d), dtype=np.float32)
