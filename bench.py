@@ -41,8 +41,8 @@ def parse():
                     help="time robe_backward and robe_adagrad_update as separate calls inside the step "
                          "(default: the fused robe_backward_adagrad; the separate calls are then timed beside it)")
     ap.add_argument("--step-only", action="store_true",
-                    help="with the fused step, do not time the separate calls beside it (keeps a profile of "
-                         "the run down to the step's own kernels)")
+                    help="time the steps only: neither the separate calls beside the fused step nor the "
+                         "PCIe-inclusive legs (keeps a profile of the run down to the step's own kernels)")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
     ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
     ap.add_argument("--copy-calib-mb", type=int, default=0,
@@ -298,15 +298,15 @@ def main():
             do_.copy_(ho, non_blocking=True)
         step(k)
 
-    for k in range(2):
+    n_h2d = 0 if args.step_only else max(2, min(args.steps, 10))
+    for k in range(min(2, n_h2d)):
         h2d_step(k)
     torch.cuda.synchronize()
-    n_h2d = max(2, min(args.steps, 10))
     t1 = time.perf_counter()
     for k in range(n_h2d):
         h2d_step(k)
     torch.cuda.synchronize()
-    h2d_ms = 1e3 * (time.perf_counter() - t1) / n_h2d
+    h2d_ms = 1e3 * (time.perf_counter() - t1) / max(n_h2d, 1)
 
     # The same again with the copy of batch k+1 on a second stream while batch k computes (two device
     # buffers per input, events in both directions).
@@ -327,7 +327,7 @@ def main():
             ready[b].record(copy_stream)
 
     h2d_overlap_ms = None
-    if n_buf >= 2:
+    if n_buf >= 2 and n_h2d:
         for b in range(n_buf):
             drained[b].record(stream)
         torch.cuda.synchronize()
@@ -421,7 +421,8 @@ def main():
         "roofline": {"kernel": entry_names[dominant], "bound": "hbm", "achieved": kernels[dominant]["achieved_GBps"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"],
                      "traffic": measured_traffic(w.name, dominant)},
-        "pcie_inclusive": {"ms_per_step": round(h2d_ms, 4), "lookups_per_s": tok / (h2d_ms * 1e-3),
+        "pcie_inclusive": None if not n_h2d else {
+                           "ms_per_step": round(h2d_ms, 4), "lookups_per_s": tok / (h2d_ms * 1e-3),
                            "host_to_device_bytes_per_step": int(id_bytes), "steps": n_h2d,
                            "what": "ids and CSR offsets copied from pinned host memory inside every step",
                            "ms_per_step_copy_overlapped": None if h2d_overlap_ms is None else round(h2d_overlap_ms, 4),
