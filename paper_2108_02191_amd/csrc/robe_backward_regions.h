@@ -54,12 +54,13 @@ struct RegionPlan {
     uint32_t bin_blocks;     // grid of R2 / R4
     uint32_t pos_per_block;  // sorted positions per workgroup in R2 / R4
     uint32_t lg_shift;       // log2 of the lanes per record in R5
+    uint32_t fullest_first;  // 1: R5 takes the regions by descending size class instead of by address
     const uint32_t *keys;    // sorted keys
     uint8_t *head;           // [n]  1: a run starts here
     uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
     uint32_t *run_tg;        // [n]  at run starts: token part of the sign hash (sign on only)
     float *P;                // [(n + 1) / 2][d] summed rows of the runs longer than one
-    uint32_t *counts, *starts, *cursors;   // [NR], [NR + 1], [NR]
+    uint32_t *counts, *starts, *cursors;   // [NR], [NR + 1], [NR]; after R3 counts holds the order of the regions for R5
     uint2 *rec;              // [<= 2 * n * C] (offset, source block | part flag)
     uint32_t *rec_tg;        // sign on only
 };
@@ -229,20 +230,18 @@ __global__ __launch_bounds__(kBinBlock) void region_bin_kernel(Params p, RegionP
     }
 }
 
-// R3: one workgroup.  starts / cursors: exclusive prefix of counts, grand total in starts[NR].
-// Thread t holds elements t, t + 1024, ... (coalesced loads, all requested at once); every chunk of
-// 1024 is scanned inside the wavefronts by shuffles, and the 32 x 16 (chunk, wavefront) totals are
-// scanned once more to give every wavefront its base in every chunk.
+// R3: one workgroup.  starts / cursors: exclusive prefix of counts, grand total in starts[NR];
+// then the order in which R5 takes the regions.
 constexpr uint32_t kScanPer = kMaxRegions / 1024u;
 
-__global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
+// Exclusive prefix sums over kMaxRegions values in index order, by one workgroup of 1024 threads.
+// Thread t holds elements t, t + 1024, ... (coalesced loads, all requested at once); every chunk of
+// 1024 is scanned inside the wavefronts by shuffles, and the 32 x 16 (chunk, wavefront) totals are
+// scanned once more to give every wavefront its base in every chunk.  Returns the grand total.
+__device__ __forceinline__ uint32_t block_scan(const uint32_t (&c)[kScanPer], uint32_t (&excl)[kScanPer],
+                                               uint32_t *base /* [kScanPer * 16] */, uint32_t *upper /* [8] */)
 {
-    __shared__ uint32_t base[kScanPer * 16u];
-    __shared__ uint32_t upper[8];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    uint32_t c[kScanPer], incl[kScanPer];
-#pragma unroll
-    for (uint32_t k = 0; k < kScanPer; ++k) c[k] = k * 1024u + t < s.NR ? s.counts[k * 1024u + t] : 0u;
 #pragma unroll
     for (uint32_t k = 0; k < kScanPer; ++k) {
         uint32_t v = c[k];
@@ -251,7 +250,7 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
             const uint32_t up = __shfl_up(v, off);
             if (lane >= off) v += up;
         }
-        incl[k] = v;
+        excl[k] = v - c[k];
         if (lane == 63u) base[k * 16u + wave] = v;
     }
     __syncthreads();
@@ -278,15 +277,63 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
     if (t < kScanPer * 16u) base[t] = before + xi - x;
     __syncthreads();
 #pragma unroll
+    for (uint32_t k = 0; k < kScanPer; ++k) excl[k] += base[k * 16u + wave];
+    __syncthreads();    // base and upper may be reused
+    return total;
+}
+
+__global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
+{
+    __shared__ uint32_t base[kScanPer * 16u];
+    __shared__ uint32_t upper[8];
+    const uint32_t t = threadIdx.x;
+    uint32_t c[kScanPer], at[kScanPer];
+#pragma unroll
+    for (uint32_t k = 0; k < kScanPer; ++k) c[k] = k * 1024u + t < s.NR ? s.counts[k * 1024u + t] : 0u;
+    const uint32_t total = block_scan(c, at, base, upper);
+#pragma unroll
     for (uint32_t k = 0; k < kScanPer; ++k) {
         const uint32_t i = k * 1024u + t;
         if (i < s.NR) {
-            const uint32_t a = base[k * 16u + wave] + incl[k] - c[k];
-            s.starts[i] = a;
-            s.cursors[i] = a;
+            s.starts[i] = at[k];
+            s.cursors[i] = at[k];
         }
     }
     if (t == 0) s.starts[s.NR] = total;
+
+    // Order in which R5 takes the regions (it overwrites counts, which nothing reads after this
+    // kernel; every thread has its counts in registers by now).  With few regions per workgroup
+    // slot the ones the frequent tokens hit, which take several times the average, must not end up
+    // as the tail of the launch: fullest first, by power-of-two size class.  With many regions per
+    // slot the tails even out and the address order is as good or better.
+    if (!s.fullest_first) {
+#pragma unroll
+        for (uint32_t k = 0; k < kScanPer; ++k) {
+            if (k * 1024u + t < s.NR) s.counts[k * 1024u + t] = k * 1024u + t;
+        }
+        return;
+    }
+    __shared__ uint32_t cls_n[32], cls_at[32];
+    if (t < 32u) cls_n[t] = 0;
+    __syncthreads();
+#pragma unroll
+    for (uint32_t k = 0; k < kScanPer; ++k) {
+        if (k * 1024u + t < s.NR) atomicAdd(&cls_n[31 - __clz((int)(c[k] | 1u))], 1u);
+    }
+    __syncthreads();
+    if (t == 0) {
+        uint32_t a = 0;
+        for (int cls = 31; cls >= 0; --cls) {
+            cls_at[cls] = a;
+            a += cls_n[cls];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t k = 0; k < kScanPer; ++k) {
+        const uint32_t i = k * 1024u + t;
+        if (i < s.NR) s.counts[atomicAdd(&cls_at[31 - __clz((int)(c[k] | 1u))], 1u)] = i;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -317,7 +364,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                                                                      float lr, float eps, int vec_ok)
 {
     extern __shared__ float acc[];  // 2^r_shift floats, then the batch staging area
-    const uint32_t r = blockIdx.x;
+    const uint32_t r = s.counts[blockIdx.x];     // after R3: the regions, fullest first
+    if (r >= s.NR) return;
     const uint32_t rb = s.starts[r], re = s.starts[r + 1];
     if (rb >= re) return;           // nothing lands in this region: it is not touched at all
 
