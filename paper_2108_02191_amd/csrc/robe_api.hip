@@ -447,13 +447,14 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
         r.rec = reinterpret_cast<uint2 *>(ws + pl.off_rec);
         r.rec_tg = reinterpret_cast<uint32_t *>(ws + pl.off_rec_tg);
 
-        // R1: combine runs into P, leave one record per run
+        // R1: combine runs into P, leave one record per run (a lane group walks kStretch * G positions)
+        const dim3 rgrid1((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * robe::kStretch - 1) / ((uint64_t)robe::kBlock * robe::kStretch)));
 #define ROBE_COMBINE_ROWS(V_)                                                                                         \
     do {                                                                                                              \
-        if (sign && bags) robe::combine_rows_kernel<V_, true, true><<<grid, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);   \
-        else if (sign) robe::combine_rows_kernel<V_, true, false><<<grid, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
-        else if (bags) robe::combine_rows_kernel<V_, false, true><<<grid, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
-        else robe::combine_rows_kernel<V_, false, false><<<grid, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);             \
+        if (sign && bags) robe::combine_rows_kernel<V_, true, true><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);   \
+        else if (sign) robe::combine_rows_kernel<V_, true, false><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
+        else if (bags) robe::combine_rows_kernel<V_, false, true><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
+        else robe::combine_rows_kernel<V_, false, false><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);             \
     } while (0)
         switch (pl.lay.V) {
             case 1: ROBE_COMBINE_ROWS(1); break;
@@ -507,7 +508,8 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     }
     if (rule != 0) return fail(ROBE_EINVAL, "internal: fused update needs the region-sorted scatter");
 
-    // S3: combine runs and scatter with float atomics
+    // S3: combine runs and scatter with float atomics (a lane group walks kWalk * G positions)
+    const dim3 sgrid((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * robe::kWalk - 1) / ((uint64_t)robe::kBlock * robe::kWalk)));
 #define ROBE_COMBINE(V_)                                                                                              \
     do {                                                                                                              \
         if (sign && bags) robe::combine_scatter_kernel<V_, true, true><<<grid, block, 0, stream>>>(p, q, grad_out, indices, keys_out, vals_out, tok_bag, urows, n, grad_array);   \

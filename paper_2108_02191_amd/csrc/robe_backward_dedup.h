@@ -12,9 +12,9 @@
 //   S2 sort     radix sort of (key, value) pairs (rocPRIM device primitive).
 //   S3 combine  a group of G lanes walks G consecutive sorted tokens, adds the
 //               gradient rows of runs of identical tokens in registers, and issues
-//               the d atomics once per run.  A run longer than a group's stretch is
-//               flushed once per stretch, which also spreads very frequent tokens
-//               over many groups.
+//               the d atomics once per run.  A run longer than a group's walk (kWalk
+//               stretches of G positions) is flushed once per walk, which also spreads
+//               very frequent tokens over many groups.
 //
 // When are two tokens "identical"?  Every offset of a token is a function of th
 // alone (h(e,x,c) = ((th + Ch*c) mod P) mod m), so with the sign off two tokens
@@ -33,6 +33,8 @@
 namespace robe {
 
 constexpr int kRowsInFlight = 8;   // gradient rows a lane group loads before it adds them
+constexpr int kWalk = 1;           // stretches of G sorted positions a lane group walks before it flushes its open run
+                                   // (longer walks measured slower here: fewer, longer-lived groups)
 
 // S1.  Bags: a group of G lanes per bag, grid-stride over bags; single-hot: one lane per lookup.
 template <bool BAGS, bool ROWVAL>
@@ -78,37 +80,8 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
     const uint32_t grp = lane & (q.G - 1u);
     const uint32_t base_lane = lane - grp;
     const uint64_t thread_id = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (thread_id - lane >= n_indices) return;          // the whole wavefront is past the end
-    const uint64_t i0 = thread_id - grp;                // first sorted position of this group's stretch
-
-    // lane l of the group looks at sorted position i0 + l
-    uint32_t my_th = 0, my_tg = 0, my_row = 0, my_e = 0;
-    int64_t my_x = 0;
-    bool my_ok = false;
-    if (i0 + grp < n_indices) {
-        const uint32_t t = vals[i0 + grp];                 // sign off: the row itself
-        const uint32_t row = !SIGN ? t : (t < n_indices ? (BAGS ? tok_bag[t] : t) : rows);
-        if (row < rows) {
-            my_ok = true;
-            my_row = row;
-            my_th = keys[i0 + grp];
-            if constexpr (SIGN) {
-                my_x = indices[t];
-                my_e = row % q.F;
-                my_tg = staged_g(p, my_x, my_e);
-            }
-        }
-    }
-    // does this position start a new run?  (first of the stretch, or a different token than the one before)
-    const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
-    const uint32_t p_th = __shfl(my_th, prev);
-    const bool p_ok = __shfl((int)my_ok, prev) != 0;
-    bool my_head = grp == 0 || !p_ok || p_th != my_th;
-    if constexpr (SIGN) {
-        const uint32_t p_e = __shfl(my_e, prev);
-        const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
-        my_head = my_head || p_e != my_e || p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32);
-    }
+    if ((thread_id - lane) * kWalk >= n_indices) return;     // the whole wavefront is past the end
+    const uint64_t i_first = (thread_id - grp) * kWalk;       // first sorted position of this group's walk
 
     Lane<V, false, SIGN> L;
     L.init(p, q, grp);
@@ -118,36 +91,90 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
     for (int k = 0; k < V; ++k) acc[k] = 0.0f;
     uint32_t run_th = 0, run_tg = 0;
     bool open = false;
+    // the last token of the stretch before (none before the first stretch)
+    uint32_t c_th = 0, c_e = 0, c_xlo = 0, c_xhi = 0;
+    bool c_ok = false;
 
-    for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsInFlight) {     // same trip count for every lane of the wavefront
-        uint32_t row[kRowsInFlight], th[kRowsInFlight], tg[kRowsInFlight];
-        bool ok[kRowsInFlight], head[kRowsInFlight];
-#pragma unroll
-        for (int u = 0; u < kRowsInFlight; ++u) {
-            const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
-            ok[u] = (k0 + u < q.G) && __shfl((int)my_ok, from) != 0;
-            row[u] = __shfl(my_row, from);
-            th[u] = __shfl(my_th, from);
-            tg[u] = SIGN ? __shfl(my_tg, from) : 0u;
-            head[u] = __shfl((int)my_head, from) != 0;
-            if (!ok[u]) row[u] = 0;                        // any valid row: its values are discarded
-        }
-        float v[kRowsInFlight][V];
-#pragma unroll
-        for (int u = 0; u < kRowsInFlight; ++u) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
-#pragma unroll
-        for (int u = 0; u < kRowsInFlight; ++u) {
-            if (!ok[u]) continue;
-            if (head[u] && open) {
-                L.scatter(p, grad_array, run_th, run_tg, acc);
-#pragma unroll
-                for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+    for (uint32_t st = 0; st < (uint32_t)kWalk; ++st) {
+        const uint64_t i0 = i_first + (uint64_t)st * q.G;
+        if (__all(i0 >= n_indices)) break;                   // every group of the wavefront is past the end
+
+        // lane l of the group looks at sorted position i0 + l
+        uint32_t my_th = 0, my_tg = 0, my_row = 0, my_e = 0;
+        int64_t my_x = 0;
+        bool my_ok = false;
+        if (i0 + grp < n_indices) {
+            const uint32_t t = vals[i0 + grp];                 // sign off: the row itself
+            const uint32_t row = !SIGN ? t : (t < n_indices ? (BAGS ? tok_bag[t] : t) : rows);
+            if (row < rows) {
+                my_ok = true;
+                my_row = row;
+                my_th = keys[i0 + grp];
+                if constexpr (SIGN) {
+                    my_x = indices[t];
+                    my_e = row % q.F;
+                    my_tg = staged_g(p, my_x, my_e);
+                }
             }
+        }
+        // does this position start a new run?  (a different token than the one before, or the walk begins)
+        const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
+        uint32_t p_th = __shfl(my_th, prev);
+        bool p_ok = __shfl((int)my_ok, prev) != 0;
+        if (grp == 0) {
+            p_th = c_th;
+            p_ok = c_ok;
+        }
+        bool my_head = !p_ok || p_th != my_th;
+        if constexpr (SIGN) {
+            uint32_t p_e = __shfl(my_e, prev);
+            uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
+            if (grp == 0) {
+                p_e = c_e;
+                p_xlo = c_xlo;
+                p_xhi = c_xhi;
+            }
+            my_head = my_head || p_e != my_e || p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32);
+        }
+
+        for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsInFlight) {     // same trip count for every lane of the wavefront
+            uint32_t row[kRowsInFlight], th[kRowsInFlight], tg[kRowsInFlight];
+            bool ok[kRowsInFlight], head[kRowsInFlight];
 #pragma unroll
-            for (int k = 0; k < V; ++k) acc[k] += v[u][k];
-            run_th = th[u];
-            run_tg = tg[u];
-            open = true;
+            for (int u = 0; u < kRowsInFlight; ++u) {
+                const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
+                ok[u] = (k0 + u < q.G) && __shfl((int)my_ok, from) != 0;
+                row[u] = __shfl(my_row, from);
+                th[u] = __shfl(my_th, from);
+                tg[u] = SIGN ? __shfl(my_tg, from) : 0u;
+                head[u] = __shfl((int)my_head, from) != 0;
+                if (!ok[u]) row[u] = 0;                        // any valid row: its values are discarded
+            }
+            float v[kRowsInFlight][V];
+#pragma unroll
+            for (int u = 0; u < kRowsInFlight; ++u) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+#pragma unroll
+            for (int u = 0; u < kRowsInFlight; ++u) {
+                if (!ok[u]) continue;
+                if (head[u] && open) {
+                    L.scatter(p, grad_array, run_th, run_tg, acc);
+#pragma unroll
+                    for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+                }
+#pragma unroll
+                for (int k = 0; k < V; ++k) acc[k] += v[u][k];
+                run_th = th[u];
+                run_tg = tg[u];
+                open = true;
+            }
+        }
+        const int last = (int)(base_lane + q.G - 1u);
+        c_th = __shfl(my_th, last);
+        c_ok = __shfl((int)my_ok, last) != 0;
+        if constexpr (SIGN) {
+            c_e = __shfl(my_e, last);
+            c_xlo = __shfl((uint32_t)my_x, last);
+            c_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), last);
         }
     }
     if (open) L.scatter(p, grad_array, run_th, run_tg, acc);

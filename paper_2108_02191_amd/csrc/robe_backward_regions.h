@@ -31,6 +31,7 @@
 namespace robe {
 
 constexpr int kRowsAhead = 8;          // gradient rows a lane group requests before adding them (R1)
+constexpr int kStretch = 8;            // stretches of G sorted positions a lane group walks in R1
 constexpr int kBinBlock = 1024;        // R2 / R4
 constexpr int kReduceBlock = 512;      // R5 (the slice arithmetic assumes 2^9)
 constexpr int kRecBatch = 640;         // records sorted and applied per round in R5 (at most 2 per thread);
@@ -72,7 +73,37 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *dst, uint32_t n
 
 // ---------------------------------------------------------------------------------------------
 // R1.  Lane layout as in the direct scatter: G lanes per row, lane `grp` owns elements grp + k*G.
+// A group walks kStretch * G consecutive sorted positions, G at a time; a run is cut only where the
+// group's walk begins and ends, so a token that fills whole stretches leaves one record per
+// kStretch * G copies.
 // ---------------------------------------------------------------------------------------------
+struct SortedToken {
+    uint32_t th, row, e, xlo, xhi, tg;
+    bool ok;
+};
+
+template <bool SIGN>
+__device__ __forceinline__ bool same_token(const SortedToken &a, const SortedToken &b)
+{
+    bool same = a.th == b.th;
+    if constexpr (SIGN) same = same && a.e == b.e && a.xlo == b.xlo && a.xhi == b.xhi;
+    return same;
+}
+
+template <bool SIGN>
+__device__ __forceinline__ SortedToken shfl_token(const SortedToken &t, int from)
+{
+    SortedToken r;
+    r.th = __shfl(t.th, from);
+    r.ok = __shfl((int)t.ok, from) != 0;
+    r.row = 0;
+    r.tg = 0;
+    r.e = SIGN ? __shfl(t.e, from) : 0u;
+    r.xlo = SIGN ? __shfl(t.xlo, from) : 0u;
+    r.xhi = SIGN ? __shfl(t.xhi, from) : 0u;
+    return r;
+}
+
 template <int V, bool SIGN, bool BAGS>
 __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, RegionPlan s,
                                                               const float *__restrict__ grad_out,
@@ -83,93 +114,111 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t grp = lane & (q.G - 1u);
     const uint32_t base_lane = lane - grp;
-    const uint64_t thread_id = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (thread_id - lane >= s.n) return;                // the whole wavefront is past the end
-    const uint32_t i0 = (uint32_t)(thread_id - grp);    // first sorted position of this group's stretch
     const uint32_t n = s.n;
+    const uint64_t thread_id = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if ((thread_id - lane) * kStretch >= n) return;     // the whole wavefront is past the end
+    const uint64_t i_first = (thread_id - grp) * kStretch;   // first sorted position of this group's walk
 
-    // lane l of the group looks at sorted position i0 + l
-    uint32_t my_th = 0, my_tg = 0, my_row = 0, my_e = 0;
-    int64_t my_x = 0;
-    bool my_ok = false;
-    if (i0 + grp < n) {
-        const uint32_t t = vals[i0 + grp];                 // sign off: the row itself (see robe_backward_dedup.h)
-        const uint32_t row = !SIGN ? t : (t < n ? (BAGS ? tok_bag[t] : t) : s.rows);
-        if (row < s.rows) {
-            my_ok = true;
-            my_row = row;
-            my_th = s.keys[i0 + grp];
-            if constexpr (SIGN) {
-                my_x = indices[t];
-                my_e = row % q.F;
-                my_tg = staged_g(p, my_x, my_e);
+    // the token at a sorted position (lane l of the group looks at position i0 + l)
+    auto fetch = [&](uint64_t pos) -> SortedToken {
+        SortedToken t;
+        t.th = t.row = t.e = t.xlo = t.xhi = t.tg = 0;
+        t.ok = false;
+        if (pos < n) {
+            const uint32_t v = vals[pos];                  // sign off: the row itself (see robe_backward_dedup.h)
+            const uint32_t row = !SIGN ? v : (v < n ? (BAGS ? tok_bag[v] : v) : s.rows);
+            if (row < s.rows) {
+                t.ok = true;
+                t.row = row;
+                t.th = s.keys[pos];
+                if constexpr (SIGN) {
+                    const int64_t x = indices[v];
+                    t.e = row % q.F;
+                    t.xlo = (uint32_t)x;
+                    t.xhi = (uint32_t)((uint64_t)x >> 32);
+                    t.tg = staged_g(p, x, t.e);
+                }
             }
         }
-    }
-    // does a run start here (first of the stretch, or a different token than the one before),
-    // and does it end here (last of the stretch, or a different token after)?
-    const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
-    const uint32_t p_th = __shfl(my_th, prev);
-    const bool p_ok = __shfl((int)my_ok, prev) != 0;
-    bool differs = grp == 0 || !p_ok || p_th != my_th;
-    if constexpr (SIGN) {
-        const uint32_t p_e = __shfl(my_e, prev);
-        const uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
-        differs = differs || p_e != my_e || p_xlo != (uint32_t)my_x || p_xhi != (uint32_t)((uint64_t)my_x >> 32);
-    }
-    const bool my_head = my_ok && differs;
-    const int next = (int)(base_lane + (grp + 1u < q.G ? grp + 1u : grp));
-    const bool n_head = __shfl((int)my_head, next) != 0, n_ok = __shfl((int)my_ok, next) != 0;
-    const bool my_end = my_ok && (grp + 1u >= q.G || !n_ok || n_head);
-    const bool my_single = my_head && my_end;
+        return t;
+    };
 
-    if (i0 + grp < n) {
-        s.head[i0 + grp] = my_head ? 1 : 0;
-        if (my_single) s.src_row[i0 + grp] = my_row;             // a run of one: read grad_out in place
-        if constexpr (SIGN) {
-            if (my_head) s.run_tg[i0 + grp] = my_tg;
-        }
-    }
-
-    // runs longer than one: sum their rows into P
     float acc[V];
 #pragma unroll
     for (int k = 0; k < V; ++k) acc[k] = 0.0f;
     uint32_t head_pos = 0;
-    for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsAhead) {     // same trip count for every lane of the wavefront
-        uint32_t row[kRowsAhead];
-        bool use[kRowsAhead], head[kRowsAhead], end[kRowsAhead];
-#pragma unroll
-        for (int u = 0; u < kRowsAhead; ++u) {
-            const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
-            const bool in = k0 + u < q.G;
-            use[u] = in && __shfl((int)(my_ok && !my_single), from) != 0;
-            row[u] = __shfl(my_row, from);
-            head[u] = __shfl((int)my_head, from) != 0;
-            end[u] = __shfl((int)my_end, from) != 0;
+
+    SortedToken cur = fetch(i_first + grp);
+    SortedToken carry;          // the last token of the stretch before; none before the first
+    carry.th = carry.row = carry.e = carry.xlo = carry.xhi = carry.tg = 0;
+    carry.ok = false;
+    for (uint32_t st = 0; st < (uint32_t)kStretch; ++st) {
+        const uint64_t i0 = i_first + (uint64_t)st * q.G;
+        if (__all(i0 >= n)) break;                          // every group of the wavefront is past the end
+        SortedToken nxt;
+        if (st + 1u < (uint32_t)kStretch) {
+            nxt = fetch(i0 + q.G + grp);
+        } else {
+            nxt = carry;
+            nxt.ok = false;
         }
-        float v[kRowsAhead][V];
-#pragma unroll
-        for (int u = 0; u < kRowsAhead; ++u) {
-            if (use[u]) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+        // does a run start here (a different token than the one before, or the walk begins), and
+        // does it end here (a different token after, or the walk ends)?
+        SortedToken before = shfl_token<SIGN>(cur, (int)(base_lane + (grp ? grp - 1u : 0u)));
+        if (grp == 0) before = carry;
+        const bool my_head = cur.ok && (!before.ok || !same_token<SIGN>(before, cur));
+        SortedToken after = shfl_token<SIGN>(cur, (int)(base_lane + (grp + 1u < q.G ? grp + 1u : grp)));
+        const SortedToken first_of_next = shfl_token<SIGN>(nxt, (int)base_lane);
+        if (grp + 1u >= q.G) after = first_of_next;
+        const bool my_end = cur.ok && (!after.ok || !same_token<SIGN>(after, cur));
+        const bool my_single = my_head && my_end;
+
+        if (i0 + grp < n) {
+            s.head[i0 + grp] = my_head ? 1 : 0;
+            if (my_single) s.src_row[i0 + grp] = cur.row;            // a run of one: read grad_out in place
+            if constexpr (SIGN) {
+                if (my_head) s.run_tg[i0 + grp] = cur.tg;
+            }
         }
+
+        // runs longer than one: sum their rows into P (a run may have begun in an earlier stretch)
+        for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsAhead) {     // same trip count for every lane of the wavefront
+            uint32_t row[kRowsAhead];
+            bool use[kRowsAhead], head[kRowsAhead], end[kRowsAhead];
 #pragma unroll
-        for (int u = 0; u < kRowsAhead; ++u) {
-            if (!use[u]) continue;
-            if (head[u]) {
-                head_pos = i0 + k0 + u;
+            for (int u = 0; u < kRowsAhead; ++u) {
+                const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
+                const bool in = k0 + u < q.G;
+                use[u] = in && __shfl((int)(cur.ok && !my_single), from) != 0;
+                row[u] = __shfl(cur.row, from);
+                head[u] = __shfl((int)my_head, from) != 0;
+                end[u] = __shfl((int)my_end, from) != 0;
+            }
+            float v[kRowsAhead][V];
 #pragma unroll
-                for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+            for (int u = 0; u < kRowsAhead; ++u) {
+                if (use[u]) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
             }
 #pragma unroll
-            for (int k = 0; k < V; ++k) acc[k] += v[u][k];
-            if (end[u]) {
-                // two runs longer than one start at least two positions apart: head_pos / 2 is unique
-                const uint32_t prow = head_pos >> 1;
-                store_row<V, false>(s.P + (uint64_t)prow * p.d, q, grp, acc);
-                if (grp == 0) s.src_row[head_pos] = s.rows + prow;
+            for (int u = 0; u < kRowsAhead; ++u) {
+                if (!use[u]) continue;
+                if (head[u]) {
+                    head_pos = (uint32_t)i0 + k0 + u;
+#pragma unroll
+                    for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+                }
+#pragma unroll
+                for (int k = 0; k < V; ++k) acc[k] += v[u][k];
+                if (end[u]) {
+                    // two runs longer than one start at least two positions apart: head_pos / 2 is unique
+                    const uint32_t prow = head_pos >> 1;
+                    store_row<V, false>(s.P + (uint64_t)prow * p.d, q, grp, acc);
+                    if (grp == 0) s.src_row[head_pos] = s.rows + prow;
+                }
             }
         }
+        carry = shfl_token<SIGN>(cur, (int)(base_lane + q.G - 1u));
+        cur = nxt;
     }
 }
 
