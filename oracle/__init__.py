@@ -67,6 +67,10 @@ def _load():
         L.oracle_forward_mixed.argtypes = [vp, u64, u64, vp, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp]
         L.oracle_backward_mixed.restype = None
         L.oracle_backward_mixed.argtypes = [vp, u64, u64, vp, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp, vp]
+        L.oracle_array_to_bf16.restype = None
+        L.oracle_array_to_bf16.argtypes = [vp, vp, u64]
+        L.oracle_forward_bf16.restype = None
+        L.oracle_forward_bf16.argtypes = [vp, u64, u64, u32, u32, ctypes.c_int, vp, vp, vp, i64, i32, vp]
         L.oracle_adagrad.restype = None
         L.oracle_adagrad.argtypes = [vp, vp, vp, u64, ctypes.c_double, ctypes.c_double, ctypes.c_int]
         L.oracle_sgd.restype = None
@@ -218,6 +222,27 @@ def backward_mixed(H: Hash, dims, grad_out, indices, bag_offsets, batch: int):
     _load().oracle_backward_mixed(H._c(), H.P, H.m, _ptr(dm), H.Z, H.use_sign, _ptr(go), _ptr(ind), _ptr(off),
                                   batch, F, _ptr(ga), _ptr(ab))
     return ga, ab
+
+
+def to_bf16(array) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns (uint16), round to nearest, ties to even."""
+    arr = _f32(array).ravel()
+    out = np.empty(arr.size, dtype=np.uint16)
+    _load().oracle_array_to_bf16(_ptr(arr), _ptr(out), arr.size)
+    return out
+
+
+def forward_bf16(H: Hash, array_bf16, indices, bag_offsets, batch: int, F: int) -> np.ndarray:
+    """Forward on an array of bfloat16 bit patterns (uint16[m]); output float32[batch, F, d]."""
+    arr = np.ascontiguousarray(array_bf16, dtype=np.uint16).ravel()
+    assert arr.size == H.m
+    ind = _i64(indices).ravel()
+    off = None if bag_offsets is None else _i64(bag_offsets)
+    _check_bags(ind, off, batch * F)
+    out = np.empty((batch, F, H.d), dtype=np.float32)
+    _load().oracle_forward_bf16(H._c(), H.P, H.m, H.d, H.Z, H.use_sign, _ptr(arr), _ptr(ind), _ptr(off),
+                                batch, F, _ptr(out))
+    return out
 
 
 def adagrad(array: np.ndarray, state: np.ndarray, grad: np.ndarray, lr: float, eps: float,

@@ -201,6 +201,66 @@ void oracle_backward(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t d,
 }
 
 /*
+ * Low-precision array (Section 2 notes that quantisation composes with the method; no format is
+ * fixed there).  The array is stored as bfloat16: the upper 16 bits of the float32 pattern.
+ * float32 -> bfloat16 rounds to nearest, ties to even, on the 16 dropped bits; NaN stays NaN (quiet
+ * bit set, payload truncated); bfloat16 -> float32 appends 16 zero bits and is exact.
+ */
+uint16_t oracle_bf16_from_f32(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu) != 0u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t keep = u >> 16, drop = u & 0xFFFFu;
+    if (drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) keep += 1u;   /* may carry into the exponent: correct */
+    return (uint16_t)keep;
+}
+
+float oracle_f32_from_bf16(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float v;
+    memcpy(&v, &u, 4);
+    return v;
+}
+
+void oracle_array_to_bf16(const float *src, uint16_t *dst, uint64_t n)
+{
+    for (uint64_t j = 0; j < n; ++j) dst[j] = oracle_bf16_from_f32(src[j]);
+}
+
+/* Forward (ROBE-Z forward equation) on a bfloat16 array: every element read is widened exactly,
+ * then the definition is that of oracle_forward (single-hot: a copy with an exact sign flip; bags:
+ * sums in double, rounded once to float32). */
+void oracle_forward_bf16(const uint64_t coef[8], uint64_t P, uint64_t m, uint32_t d, uint32_t Z, int use_sign,
+                         const uint16_t *array, const int64_t *indices, const int64_t *offsets,
+                         int64_t batch, int32_t F, float *out)
+{
+    int64_t rows = batch * (int64_t)F;
+    for (int64_t k = 0; k < rows; ++k) {
+        uint64_t e = (uint64_t)(k % F);
+        int64_t t0 = offsets ? offsets[k] : k;
+        int64_t t1 = offsets ? offsets[k + 1] : k + 1;
+        for (uint32_t i = 0; i < d; ++i) {
+            if (offsets == NULL) {
+                uint64_t x = (uint64_t)indices[k];
+                float v = oracle_f32_from_bf16(array[oracle_idx(coef, P, m, d, Z, e, x, i)]);
+                out[k * (int64_t)d + i] = oracle_g(coef, P, use_sign, e, x, i) < 0 ? -v : v;
+                continue;
+            }
+            double acc = 0.0;
+            for (int64_t t = t0; t < t1; ++t) {
+                uint64_t x = (uint64_t)indices[t];
+                acc += (double)oracle_g(coef, P, use_sign, e, x, i) *
+                       (double)oracle_f32_from_bf16(array[oracle_idx(coef, P, m, d, Z, e, x, i)]);
+            }
+            out[k * (int64_t)d + i] = (float)acc;
+        }
+    }
+}
+
+/*
  * Tables of different embedding dimensions sharing the one array (Section 3.2,
  * "Multiple embedding tables": all tables, even with varying dimensions, share
  * the array; the table id is an argument of h and g).  Table f has dimension

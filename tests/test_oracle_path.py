@@ -348,3 +348,51 @@ def test_mixed_with_equal_dimensions_is_the_uniform_path():
     assert np.array_equal(ga, gu) and np.array_equal(ab, au)
     with pytest.raises(ValueError):
         oracle.forward_mixed(H, [8, 6], M, ids[:, :2], None, B)      # 6 is neither a multiple nor a divisor of 4
+
+
+# ---------------------------------------------------------------------------------------------
+# bfloat16 array
+# ---------------------------------------------------------------------------------------------
+def _torch_bf16_bits(a: np.ndarray) -> np.ndarray:
+    return torch.from_numpy(a).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def test_bf16_rounding_matches_the_library_conversion_and_the_format_rules():
+    rng = np.random.default_rng(0)
+    vals = [0.0, -0.0, 1.0, -1.0, 1.00390625, 1.01171875, 3.4028235e38, 1e-40, -1e-45, np.inf, -np.inf,
+            0.01, -0.01, 65280.0, 65408.0, 2.0 ** -126, 2.0 ** -133]
+    a = np.array(vals, dtype=np.float32)
+    # exact ties: patterns whose dropped half is 0x8000, on even and odd kept halves; and neighbours
+    ties = np.array([0x3F808000, 0x3F818000, 0x3F807FFF, 0x3F808001, 0x7F7F8000, 0x00008000, 0x00018000,
+                     0x80008000, 0xBF808000, 0x7F7FFFFF], dtype=np.uint32).view(np.float32)
+    big = rng.standard_normal(200_000).astype(np.float32) * np.float32(0.01)
+    bits = rng.integers(0, 2**32, size=200_000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    bits = bits[~np.isnan(bits)]
+    for arr in (a, ties, big, bits):
+        got = oracle.to_bf16(arr)
+        assert np.array_equal(got, _torch_bf16_bits(np.ascontiguousarray(arr)))
+    # hand-checked rules: tie to even, carry into the exponent, NaN stays NaN
+    assert oracle.to_bf16(np.array([0x3F808000], dtype=np.uint32).view(np.float32))[0] == 0x3F80    # tie, even kept
+    assert oracle.to_bf16(np.array([0x3F818000], dtype=np.uint32).view(np.float32))[0] == 0x3F82    # tie, odd kept -> up
+    assert oracle.to_bf16(np.array([0x3FFFFFFF], dtype=np.uint32).view(np.float32))[0] == 0x4000    # carries into the exponent
+    assert oracle.to_bf16(np.array([0x7F7FFFFF], dtype=np.uint32).view(np.float32))[0] == 0x7F80    # overflows to infinity
+    nan = oracle.to_bf16(np.array([0x7F800001, 0xFFC12345], dtype=np.uint32).view(np.float32))
+    assert all((int(h) & 0x7F80) == 0x7F80 and (int(h) & 0x007F) != 0 for h in nan)
+
+
+@pytest.mark.parametrize("seed,m,d,Z,sign", CASES)
+def test_forward_on_a_bf16_array_is_the_forward_of_the_widened_array(seed, m, d, Z, sign):
+    # widening is exact, so the bf16 forward must equal the (pinned) float32 forward of the array
+    # that a library conversion produces from the same bit patterns
+    B, F = 4, 3
+    H, ids, M = _tiny_case(seed, m, d, Z, sign, B, F)
+    Mb = oracle.to_bf16(M)
+    widened = torch.from_numpy(Mb.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    assert oracle.forward_bf16(H, Mb, ids, None, B, F).tobytes() == oracle.forward(H, widened, ids, None, B, F).tobytes()
+    rng = np.random.default_rng(seed)
+    sizes = rng.integers(0, 5, size=B * F)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    flat = rng.integers(0, 50, size=int(off[-1]))
+    assert oracle.forward_bf16(H, Mb, flat, off, B, F).tobytes() == oracle.forward(H, widened, flat, off, B, F).tobytes()
+    # and quantisation moves every element by at most half a bf16 ulp: 2^-9 relative
+    assert np.all(np.abs(widened - M) <= np.abs(M) * 2.0 ** -8)
