@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="multihot",
-                    help="multihot | training | inference | sweep_z{1,8,32,128} | kaggle_z{1,2,4,8,16} | mixed_dims | tiny")
+                    help="multihot | training | inference | sweep_z{1,8,32,128} | kaggle_z{1,2,4,8,16} | mixed_dims | inference_bf16 | multihot_fwd_bf16 | tiny")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0: as defined)")
     ap.add_argument("--m", type=int, default=0, help="override the array length in floats (0: as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -53,6 +53,10 @@ def parse():
 
 def algorithmic_bytes(w, rows, tokens, touched):
     """Bytes the method itself must move per launch (d floats per vector, 8-byte ids)."""
+    if w.array_dtype == "bf16":    # forward only: 2-byte array elements, float32 output
+        bags = w.bag_mean is not None
+        fwd = tokens * (2 * w.d + 8) + rows * 4 * w.d + (rows + 1) * 8 * bags
+        return {"fwd": fwd, "bwd": 0, "adagrad": 0, "sgd": 0, "bwd_adagrad": 0}
     if w.dims is not None:    # single-hot, one vector of dims[f] floats per (sample, table)
         D, F = sum(w.dims), w.n_features
         fwd = w.batch * (8 * D + 8 * F)
@@ -91,8 +95,9 @@ def cpu_baseline(w, M, ids, off, G, target_s):
     H = oracle.init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
     threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
     F = w.n_features
-    if w.dims is not None:
-        threads = 1             # the oracle's mixed-dimension loops are sequential
+    if w.dims is not None or w.array_dtype == "bf16":
+        threads = 1             # the oracle's mixed-dimension and bf16 loops are sequential
+    Mq = oracle.to_bf16(M) if w.array_dtype == "bf16" else None
 
     def sub(bs):
         rows = bs * F
@@ -104,7 +109,9 @@ def cpu_baseline(w, M, ids, off, G, target_s):
     def run(bs):
         i_, o_, g_, ntok = sub(bs)
         t0 = time.perf_counter()
-        if w.dims is not None:
+        if w.array_dtype == "bf16":
+            oracle.forward_bf16(H, Mq, i_, o_, bs, F)
+        elif w.dims is not None:
             oracle.forward_mixed(H, w.dims, M, i_, o_, bs)
         else:
             oracle.forward(H, M, i_, o_, bs, F, threads=threads)
@@ -178,6 +185,14 @@ def main():
 
     h = robe.robe_init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
     Md = torch.from_numpy(M).to(dev)
+    bf16 = w.array_dtype == "bf16"
+    if bf16:
+        if do_bwd:
+            print("a bf16 array is forward-only", file=sys.stderr)
+            sys.exit(2)
+        Mb = robe.robe_array_to_bf16(Md)
+        del Md
+        Md = None
     dev_batches = [(torch.from_numpy(i).to(dev), None if o is None else torch.from_numpy(o).to(dev)) for i, o in batches]
     Gd = torch.from_numpy(G).to(dev)
     mixed = w.dims is not None
@@ -197,6 +212,8 @@ def main():
             ev[0].record(stream)
         if mixed:
             robe.robe_forward_mixed(h, w.dims, Md, idd, offd, B, out=out)
+        elif bf16:
+            robe.robe_forward_bf16(h, Mb, idd, offd, B, F, out=out)
         else:
             robe.robe_forward(h, Md, idd, offd, B, F, out=out)
         if ev:
@@ -394,6 +411,8 @@ def main():
                                   "write-back on large arrays, scatter + update_kernel on small ones)",
                    "bwd": "robe_backward (every kernel of the call: "
                           + ("token keys, radix sort, then combine + scatter" if ws_bytes else "direct scatter kernel") + ")"}
+    if bf16:
+        entry_names["fwd"] = "robe_forward_bf16"
     if mixed:
         entry_names["fwd"] = "robe_forward_mixed (one launch per run of equal dimensions)"
         entry_names["bwd"] = "robe_backward_mixed (direct scatter, one launch per run of equal dimensions)"
@@ -406,7 +425,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32 (array stored as bf16)" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "m": w.m, "array_bytes": 4 * w.m, "d": list(w.dims) if w.dims else w.d, "Z": w.Z, "batch": B,
                    "n_features": F, "rows": rows, "tokens_per_step": tok, "bag_mean": w.bag_mean,
                    "ids": f"{w.id_dist}({w.zipf_alpha})" if w.id_dist == "zipf" else w.id_dist,

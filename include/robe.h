@@ -222,6 +222,21 @@ int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const flo
                         int64_t batch, int32_t n_features, float *grad_array, void *stream);
 
 /*
+ * Low-precision array (Section 2 notes that quantisation can be applied together with the method;
+ * it fixes no format).  The array is stored as bfloat16 bit patterns, uint16_t[m]: the upper half of
+ * the float32 pattern.  robe_array_to_bf16 converts a float32 device array (round to nearest, ties
+ * to even; NaN stays NaN) - post-hoc quantisation of a trained array; dst may not overlap src.
+ * robe_forward_bf16 is robe_forward on such an array: every element read is widened exactly (16 zero
+ * bits appended), sign, bag-sum and output are float32 as before, so a single-hot lookup returns
+ * exactly the stored values.  Half the array bytes per lookup; training keeps the float32 array.
+ * Errors: ROBE_EINVAL, ROBE_EHIP.
+ */
+int robe_array_to_bf16(const float *src, uint16_t *dst, uint64_t n, void *stream);
+int robe_forward_bf16(const robe_hash_t *hash, const uint16_t *array,
+                      const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                      int64_t batch, int32_t n_features, float *out, void *stream);
+
+/*
  * Run-to-run reproducible scatter (process-wide switch, off at start; returns the previous setting).
  * Eq. 3 sums float32 terms whose order the paper does not fix; with float atomics that order, and so
  * the last bits of the result, change from run to run.  While the switch is on, robe_backward and

@@ -46,7 +46,8 @@ class RobeHash(ctypes.Structure):
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
-           "robe_forward_mixed", "robe_backward_mixed", "robe_set_reproducible", "robe_last_error")
+           "robe_forward_mixed", "robe_backward_mixed", "robe_array_to_bf16", "robe_forward_bf16",
+           "robe_set_reproducible", "robe_last_error")
 
 _lib = None
 
@@ -84,6 +85,11 @@ def lib() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
             fn.argtypes = [HP, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                            ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        L.robe_array_to_bf16.restype = ctypes.c_int
+        L.robe_array_to_bf16.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+        L.robe_forward_bf16.restype = ctypes.c_int
+        L.robe_forward_bf16.argtypes = [HP, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                        ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
         L.robe_set_reproducible.restype = ctypes.c_int
         L.robe_set_reproducible.argtypes = [ctypes.c_int]
         L.robe_last_error.restype = ctypes.c_char_p
@@ -254,3 +260,31 @@ def robe_backward_mixed(h: RobeHash, dims, grad_out: torch.Tensor, indices: torc
     _check(lib().robe_backward_mixed(ctypes.byref(h), ctypes.cast(da, ctypes.c_void_p), _dev(grad_out, torch.float32, "grad_out"),
                                      _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                      indices.numel(), batch, F, _dev(grad_array, torch.float32, "grad_array"), _stream()))
+
+
+def robe_array_to_bf16(array: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """float32 device array -> bfloat16 bit patterns (int16 tensor of the same length)."""
+    if out is None:
+        out = torch.empty(array.numel(), dtype=torch.int16, device=array.device)
+    elif out.numel() != array.numel():
+        raise ValueError("out has the wrong size")
+    _check(lib().robe_array_to_bf16(_dev(array, torch.float32, "array"), _dev(out, torch.int16, "out"),
+                                    array.numel(), _stream()))
+    return out
+
+
+def robe_forward_bf16(h: RobeHash, array_bf16: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                      batch: int, n_features: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """robe_forward on an array of bfloat16 bit patterns (int16 tensor of length m)."""
+    if array_bf16.numel() != h.m:
+        raise ValueError("array length differs from hash.m")
+    if offsets is not None and offsets.numel() != batch * n_features + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    if out is None:
+        out = torch.empty((batch, n_features, h.d), dtype=torch.float32, device=array_bf16.device)
+    elif out.numel() != batch * n_features * h.d:
+        raise ValueError("out has the wrong size")
+    _check(lib().robe_forward_bf16(ctypes.byref(h), _dev(array_bf16, torch.int16, "array"),
+                                   _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                                   indices.numel(), batch, n_features, _dev(out, torch.float32, "out"), _stream()))
+    return out

@@ -164,8 +164,8 @@ struct TableView {
     int64_t row_floats, col0;
 };
 
-template <bool BWD>
-int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, const int64_t *offsets,
+template <bool BWD, typename AT = float>
+int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, const int64_t *offsets,
                 int64_t n_indices, int64_t rows, uint32_t F, float *dst, const void *rows_ptr, hipStream_t stream,
                 const TableView *view = nullptr)
 {
@@ -189,9 +189,9 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
         const int64_t blocks = (rows + rpb - 1) / rpb;
         if (blocks > 0x7FFFFFFFll) return fail(ROBE_EINVAL, "too many rows for one launch");
         if (sign)
-            robe::generic_kernel<true, BWD><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, q, rpb, src, indices, offsets, rows, n_indices, dst);
+            robe::generic_kernel<true, BWD, AT><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, q, rpb, src, indices, offsets, rows, n_indices, dst);
         else
-            robe::generic_kernel<false, BWD><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, q, rpb, src, indices, offsets, rows, n_indices, dst);
+            robe::generic_kernel<false, BWD, AT><<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, stream>>>(p, q, rpb, src, indices, offsets, rows, n_indices, dst);
         return check_launch(BWD ? "backward (generic)" : "forward (generic)");
     }
 
@@ -226,9 +226,9 @@ int launch_rows(const robe_hash_t *h, const float *src, const int64_t *indices, 
 #define ROBE_LAUNCH(V_, C_, S_)                                                                                       \
     do {                                                                                                              \
         if (bags)                                                                                                     \
-            robe::bag_kernel<V_, C_, S_, BWD><<<grid, block, 0, stream>>>(p, q, src, indices, offsets, rows, n_indices, dst); \
+            robe::bag_kernel<V_, C_, S_, BWD, AT><<<grid, block, 0, stream>>>(p, q, src, indices, offsets, rows, n_indices, dst); \
         else                                                                                                          \
-            robe::single_hot_kernel<V_, C_, S_, BWD><<<grid, block, 0, stream>>>(p, q, src, indices, rows, dst);     \
+            robe::single_hot_kernel<V_, C_, S_, BWD, AT><<<grid, block, 0, stream>>>(p, q, src, indices, rows, dst); \
     } while (0)
 #define ROBE_LAUNCH_CS(V_)                                           \
     do {                                                             \
@@ -645,6 +645,31 @@ int robe_forward(const robe_hash_t *hash, const float *array, const int64_t *ind
     if (out == nullptr) return fail(ROBE_EINVAL, "out is NULL");
     if (!aligned(array, 4) || !aligned(out, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
     return launch_rows<false>(hash, array, indices, offsets, n_indices, rows, (uint32_t)n_features, out, out, (hipStream_t)stream);
+}
+
+int robe_forward_bf16(const robe_hash_t *hash, const uint16_t *array, const int64_t *indices, const int64_t *offsets,
+                      int64_t n_indices, int64_t batch, int32_t n_features, float *out, void *stream)
+{
+    int64_t rows = 0;
+    if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
+    if (rows == 0) return ROBE_OK;
+    if (array == nullptr) return fail(ROBE_EINVAL, "array is NULL");
+    if (out == nullptr) return fail(ROBE_EINVAL, "out is NULL");
+    if (!aligned(array, 2) || !aligned(out, 4)) return fail(ROBE_EINVAL, "array must be 2-byte and out 4-byte aligned");
+    return launch_rows<false, uint16_t>(hash, array, indices, offsets, n_indices, rows, (uint32_t)n_features, out, out,
+                                        (hipStream_t)stream);
+}
+
+int robe_array_to_bf16(const float *src, uint16_t *dst, uint64_t n, void *stream)
+{
+    if (n == 0) return ROBE_OK;
+    if (src == nullptr || dst == nullptr) return fail(ROBE_EINVAL, "src or dst is NULL");
+    if (!aligned(src, 4) || !aligned(dst, 2)) return fail(ROBE_EINVAL, "src must be 4-byte and dst 2-byte aligned");
+    const int vec_ok = aligned(src, 16) && aligned(dst, 8) ? 1 : 0;
+    uint64_t blocks = (n / 4 + robe::kBlock - 1) / robe::kBlock;
+    blocks = blocks < 1 ? 1 : (blocks > 65536 ? 65536 : blocks);
+    robe::to_bf16_kernel<<<dim3((uint32_t)blocks), dim3(robe::kBlock), 0, (hipStream_t)stream>>>(src, dst, n, vec_ok);
+    return check_launch("array to bfloat16");
 }
 
 size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices)

@@ -114,7 +114,23 @@ template <int V>
 struct Vec {
     typedef float A __attribute__((ext_vector_type(V)));  // V floats at natural vector alignment
     typedef A U __attribute__((aligned(4)));              // the same at 4-byte alignment
+    typedef uint16_t HA __attribute__((ext_vector_type(V)));  // V bfloat16 bit patterns
+    typedef HA HU __attribute__((aligned(2)));                 // ... at 2-byte alignment
 };
+
+// An array element as float32.  The array is float32, or bfloat16 bit patterns (uint16_t): the upper
+// half of the float32 pattern, widened exactly by appending 16 zero bits.
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// float32 -> bfloat16 bit pattern: round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ uint16_t narrow_bf16(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu) != 0u) return (uint16_t)((u >> 16) | 0x0040u);
+    const uint32_t keep = u >> 16, drop = u & 0xFFFFu;
+    return (uint16_t)(keep + ((drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) ? 1u : 0u));
+}
 
 // Per-lane constants: which elements this lane owns and their chunk terms.
 template <int V, bool CONSEC, bool SIGN>
@@ -154,22 +170,29 @@ struct Lane {
     }
 
     // v[k] = g * M[idx] for the V owned elements of one token.
-    __device__ __forceinline__ void gather(const Params &p, const float *__restrict__ array,
+    template <typename AT>
+    __device__ __forceinline__ void gather(const Params &p, const AT *__restrict__ array,
                                            uint32_t th, uint32_t tg, float (&v)[V]) const
     {
         if constexpr (CONSEC) {
             const uint32_t pos = position(p, th, 0);
             if (V == 1 || pos + V <= p.m) {
-                const typename Vec<V>::A u = *reinterpret_cast<const typename Vec<V>::U *>(array + pos);
+                if constexpr (sizeof(AT) == 4) {
+                    const typename Vec<V>::A u = *reinterpret_cast<const typename Vec<V>::U *>(array + pos);
 #pragma unroll
-                for (int k = 0; k < V; ++k) v[k] = u[k];
+                    for (int k = 0; k < V; ++k) v[k] = u[k];
+                } else {
+                    const typename Vec<V>::HA u = *reinterpret_cast<const typename Vec<V>::HU *>(array + pos);
+#pragma unroll
+                    for (int k = 0; k < V; ++k) v[k] = widen((uint16_t)u[k]);
+                }
             } else {  // the lane's own span crosses the end of the circular array
 #pragma unroll
-                for (int k = 0; k < V; ++k) v[k] = array[wrap(pos + k, p.m)];
+                for (int k = 0; k < V; ++k) v[k] = widen(array[wrap(pos + k, p.m)]);
             }
         } else {
 #pragma unroll
-            for (int k = 0; k < V; ++k) v[k] = array[position(p, th, k)];
+            for (int k = 0; k < V; ++k) v[k] = widen(array[position(p, th, k)]);
         }
         if constexpr (SIGN) {
 #pragma unroll
@@ -233,9 +256,9 @@ __device__ __forceinline__ uint32_t staged_g(const Params &p, int64_t x, uint32_
 // ---------------------------------------------------------------------------
 // Single-hot forward / backward: one wavefront per tile of TL lookups.
 // ---------------------------------------------------------------------------
-template <int V, bool CONSEC, bool SIGN, bool BWD>
+template <int V, bool CONSEC, bool SIGN, bool BWD, typename AT = float>
 __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
-                                                            const float *__restrict__ src,   // fwd: array; bwd: grad_out
+                                                            const AT *__restrict__ src,      // fwd: array; bwd: grad_out
                                                             const int64_t *__restrict__ indices,
                                                             int64_t rows,
                                                             float *__restrict__ dst)         // fwd: out; bwd: grad_array
@@ -297,9 +320,9 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
 // Bag-sum forward / bag backward: one group of G lanes per bag, 64/G bags per
 // wavefront.  A group stages up to G of its bag's tokens at a time.
 // ---------------------------------------------------------------------------
-template <int V, bool CONSEC, bool SIGN, bool BWD>
+template <int V, bool CONSEC, bool SIGN, bool BWD, typename AT = float>
 __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
-                                                     const float *__restrict__ src,      // fwd: array; bwd: grad_out
+                                                     const AT *__restrict__ src,         // fwd: array; bwd: grad_out
                                                      const int64_t *__restrict__ indices,
                                                      const int64_t *__restrict__ offsets,
                                                      int64_t rows, int64_t n_indices,
@@ -381,9 +404,9 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
 // Shape-generic fallback (any d, Z with Z | d): one thread per (row, element),
 // every hash evaluated in full by the thread that needs it.
 // ---------------------------------------------------------------------------
-template <bool SIGN, bool BWD>
+template <bool SIGN, bool BWD, typename AT = float>
 __global__ __launch_bounds__(kBlock) void generic_kernel(Params p, Geom q, uint32_t rows_per_block,
-                                                         const float *__restrict__ src,
+                                                         const AT *__restrict__ src,
                                                          const int64_t *__restrict__ indices,
                                                          const int64_t *__restrict__ offsets,  // NULL: single-hot
                                                          int64_t rows, int64_t n_indices,
@@ -411,7 +434,8 @@ __global__ __launch_bounds__(kBlock) void generic_kernel(Params p, Geom q, uint3
             t0 = t0 < 0 ? 0 : (t0 > n_indices ? n_indices : t0);
             t1 = t1 < t0 ? t0 : (t1 > n_indices ? n_indices : t1);
         }
-        float acc = BWD ? src[at] : 0.0f;
+        float acc = 0.0f;
+        if constexpr (BWD) acc = src[at];
         for (int64_t t = t0; t < t1; ++t) {
             const int64_t x = indices[t];
             // Z > d (Section 3.3): r = Z/d embeddings share a chunk; the chunk id x / r takes the
@@ -423,12 +447,30 @@ __global__ __launch_bounds__(kBlock) void generic_kernel(Params p, Geom q, uint3
             if constexpr (BWD) {
                 __hip_atomic_fetch_add(dst + pos, apply_sign(acc, msk), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
-                const float v = apply_sign(src[pos], msk);
+                const float v = apply_sign(widen(src[pos]), msk);
                 acc = (offsets == nullptr) ? v : acc + v;   // single-hot keeps the sign of zero
             }
         }
         if constexpr (!BWD) dst[at] = acc;
     }
+}
+
+// ---------------------------------------------------------------------------
+// float32 array -> bfloat16 array (post-hoc quantisation of a trained array).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void to_bf16_kernel(const float *__restrict__ src, uint16_t *__restrict__ dst,
+                                                         uint64_t n, int vec_ok)
+{
+    const uint64_t tid = (uint64_t)blockIdx.x * kBlock + threadIdx.x, stride = (uint64_t)gridDim.x * kBlock;
+    const uint64_t nvec = vec_ok ? n / 4u : 0u;
+    for (uint64_t i = tid; i < nvec; i += stride) {
+        const Vec<4>::A a = __builtin_nontemporal_load(reinterpret_cast<const Vec<4>::A *>(src) + i);
+        Vec<4>::HA h;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) h[k] = narrow_bf16(a[k]);
+        __builtin_nontemporal_store(h, reinterpret_cast<Vec<4>::HA *>(dst) + i);
+    }
+    for (uint64_t i = 4u * nvec + tid; i < n; i += stride) dst[i] = narrow_bf16(src[i]);
 }
 
 // ---------------------------------------------------------------------------

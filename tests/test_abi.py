@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "robe.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(robe_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(robe_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -92,6 +92,12 @@ def test_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.robe_forward_mixed(ref, dims_ok, None, fake, None, 4, 2, 2, fake, None) == EINVAL
     assert L.robe_backward_mixed(ref, dims_ok, fake, fake, None, 5, 2, 2, fake, None) == EINVAL
     assert L.robe_forward_mixed(ref, dims_ok, None, None, None, 0, 0, 2, None, None) == robe.ROBE_OK
+    # bfloat16 array
+    assert L.robe_forward_bf16(ref, None, fake, None, 4, 2, 2, fake, None) == EINVAL
+    assert L.robe_forward_bf16(ref, fake, fake, None, 5, 2, 2, fake, None) == EINVAL
+    assert L.robe_forward_bf16(ref, None, None, None, 0, 0, 2, None, None) == robe.ROBE_OK
+    assert L.robe_array_to_bf16(None, fake, 8, None) == EINVAL
+    assert L.robe_array_to_bf16(None, None, 0, None) == robe.ROBE_OK
     # the reproducibility switch is plain host state: returns the previous setting
     assert L.robe_set_reproducible(1) == 0
     assert L.robe_set_reproducible(0) == 1

@@ -198,3 +198,29 @@ def test_mixed_dimensions_workload_full_size():
     rhs = float(M.astype(np.float64) @ got)
     assert abs(lhs - rhs) <= 1e-5 * float(np.abs(M).astype(np.float64) @ S) + 1e-9
     assert abs(got.sum() - float(G.astype(np.float64).sum())) <= 1e-6 * float(S.sum())
+
+
+@pytest.mark.parametrize("name", ["inference_bf16", "multihot_fwd_bf16"])
+def test_bf16_array_workloads_full_size(name):
+    # the array quantised on the GPU equals the oracle's quantisation bit for bit; the forward on it is
+    # bit-exact for single-hot lookups and within the pooled tolerance for bags, at the benchmark's size
+    w = workloads.get(name)
+    B, F = w.batch, w.n_features
+    if name == "multihot_fwd_bf16":
+        w = w.scaled(batch=B // 4)          # the oracle's bf16 loops are sequential: a quarter of the batch
+        B = w.batch
+    h = robe.robe_init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
+    H = oracle.init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
+    M = workloads.make_array(w.m, 0)
+    Mb_dev = robe.robe_array_to_bf16(dev(M))
+    Mb = oracle.to_bf16(M)
+    assert np.array_equal(Mb_dev.cpu().numpy().view(np.uint16), Mb)
+    ids, off = workloads.make_indices(w, 1)
+    out = robe.robe_forward_bf16(h, Mb_dev, dev(ids), dev(off), B, F).cpu().numpy()
+    want = oracle.forward_bf16(H, Mb, ids, off, B, F)
+    if off is None:
+        assert bits_equal(out, want)
+    else:
+        H_abs = oracle.Hash(H.m, H.d, H.Z, 0, H.P, H.coef)
+        S = oracle.forward_bf16(H_abs, Mb & np.uint16(0x7FFF), ids, off, B, F).astype(np.float64)
+        assert np.all(np.abs(out.astype(np.float64) - want) <= 1e-5 * S + TINY)

@@ -40,6 +40,7 @@ class Workload:
     eps: float = 1e-8
     hash_seed: int = 2108_02191
     dims: Optional[Tuple[int, ...]] = None   # per-table dimensions (tables of mixed dimensions); None: all d
+    array_dtype: str = "f32"                 # "bf16": the array is quantised to bfloat16 for the forward pass
 
     @property
     def rows(self) -> int:
@@ -77,6 +78,12 @@ def get(name: str) -> Workload:
         Z = int(name[len("kaggle_z"):])
         return Workload(name, 540_000, 16, Z, 2048, N_FEATURES, KAGGLE_CARDINALITIES, "zipf", 1.05, 0, None,
                         "fwd+bwd+sgd", lr=1.0)
+    if name == "inference_bf16":
+        # the inference configuration on a bfloat16 copy of the array (Section 2: quantisation composes
+        # with the method; the paper measures no such configuration)
+        return get("inference").scaled(name="inference_bf16", array_dtype="bf16")
+    if name == "multihot_fwd_bf16":
+        return get("multihot").scaled(name="multihot_fwd_bf16", phases="fwd", array_dtype="bf16")
     if name == "mixed_dims":
         # Tables of different dimensions in one array (Section 3.2, "Multiple embedding tables").  The
         # paper runs no such configuration; this one keeps the inference shapes and gives the small
@@ -91,7 +98,8 @@ def get(name: str) -> Workload:
 
 
 ALL = ("tiny", "inference", "training", "sweep_z1", "sweep_z8", "sweep_z32", "sweep_z128", "multihot",
-       "kaggle_z1", "kaggle_z2", "kaggle_z4", "kaggle_z8", "kaggle_z16", "mixed_dims")
+       "kaggle_z1", "kaggle_z2", "kaggle_z4", "kaggle_z8", "kaggle_z16", "mixed_dims",
+       "inference_bf16", "multihot_fwd_bf16")
 
 
 def make_array(m: int, seed: int = 0) -> np.ndarray:
