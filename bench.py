@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--step-only", action="store_true",
                     help="time the steps only: neither the separate calls beside the fused step nor the "
                          "PCIe-inclusive legs (keeps a profile of the run down to the step's own kernels)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step (one per id batch) into a HIP graph and time replays; only for "
+                         "workloads whose backward needs no workspace (small problems: one kernel per call)")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
     ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
     ap.add_argument("--copy-calib-mb", type=int, default=0,
@@ -266,6 +269,30 @@ def main():
         step(k)
     torch.cuda.synchronize()
 
+    graph_ms = None
+    if args.graph:
+        if ws is not None or mixed:
+            print("--graph: this workload sorts its tokens (the sort records memset nodes) or launches per "
+                  "dimension; only the small direct-path workloads are captured", file=sys.stderr)
+            sys.exit(2)
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for k in range(len(dev_batches)):
+                step(k)
+        torch.cuda.synchronize()
+        per_replay = len(dev_batches)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        n_rep = max(1, args.steps // per_replay)
+        t1 = time.perf_counter()
+        for _ in range(n_rep):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = 1e3 * (time.perf_counter() - t1) / (n_rep * per_replay)
+
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -446,6 +473,9 @@ def main():
                            "what": "ids and CSR offsets copied from pinned host memory inside every step",
                            "ms_per_step_copy_overlapped": None if h2d_overlap_ms is None else round(h2d_overlap_ms, 4),
                            "lookups_per_s_copy_overlapped": None if h2d_overlap_ms is None else tok / (h2d_overlap_ms * 1e-3)},
+        "graph_replay": None if graph_ms is None else {
+            "ms_per_step": round(graph_ms, 5), "lookups_per_s": tok / (graph_ms * 1e-3),
+            "what": "the same step captured once per id batch into one HIP graph; value stays the eager figure"},
         "input_generation_s": round(t_gen, 1),
     }
 
