@@ -256,6 +256,12 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
 // Backward with duplicate tokens combined: plan (shared by robe_workspace_bytes
 // and robe_backward) and launch.
 // ---------------------------------------------------------------------------
+// The library's default switches to a merge sort below 2^20 items, which for these (key, value)
+// pairs takes about twenty small kernels; the one-sweep radix sort it uses above that is faster
+// here from a few ten thousand items on (measured: 852 K pairs, 146 us against about 40 us).
+using TokenSortConfig = rocprim::radix_sort_config<rocprim::default_config, rocprim::default_config,
+                                                   rocprim::default_config, 32768>;
+
 struct BwdPlan {
     bool dedup;          // sort the tokens and combine identical ones
     bool regions;        // ... and then sort the blocks by destination region instead of using float atomics
@@ -313,7 +319,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     const size_t n = (size_t)n_indices;
     size_t temp = 0;
     uint32_t *nul = nullptr;
-    if (rocprim::radix_sort_pairs(nullptr, temp, nul, nul, nul, nul, n, 31 - pl.key_bits, 31) != hipSuccess) {
+    if (rocprim::radix_sort_pairs<TokenSortConfig>(nullptr, temp, nul, nul, nul, nul, n, 31 - pl.key_bits, 31) != hipSuccess) {
         (void)hipGetLastError();
         return pl;                                    // no device to ask: the caller cannot run the scatter either
     }
@@ -422,7 +428,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
 
     // S2: sort (key, position) pairs by the top key_bits bits of the 31-bit key
     size_t temp = pl.temp_bytes;
-    hipError_t st = rocprim::radix_sort_pairs(ws + pl.off_temp, temp, keys_in, keys_out, vals_in, vals_out,
+    hipError_t st = rocprim::radix_sort_pairs<TokenSortConfig>(ws + pl.off_temp, temp, keys_in, keys_out, vals_in, vals_out,
                                               (size_t)n, 31 - pl.key_bits, 31, stream);
     if (st != hipSuccess) return fail(ROBE_EHIP, "backward (sort): %s", hipGetErrorString(st));
 
