@@ -124,7 +124,8 @@ int robe_forward(const robe_hash_t *hash, const float *array,
 /*
  * Bytes of device workspace robe_backward needs for this problem size, for
  * either kind of input (single-hot or bags); 0 when none is needed (small
- * problems scatter directly).  Needs the current device (it asks the sort
+ * problems scatter directly).  The size depends on the problem size and on the
+ * reproducible switch (robe_set_reproducible): ask after setting it.  Needs the current device (it asks the sort
  * primitive for its temporary-storage size); returns 0 on invalid arguments
  * or when no device is present.
  */
@@ -136,9 +137,12 @@ size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_fe
  * where every token t of bag k receives row k of grad_out (single-hot: one
  * token per row).  Accumulates onto the caller's grad_array (device float[m]);
  * the order of the float32 additions is not fixed, so results agree with an
- * exact sum only to rounding.  Large scatters first combine the gradient rows
- * of repeated tokens (sort by the token part of the hash, run-wise sums) and
- * issue the atomics once per run; that path needs the workspace and rows,
+ * exact sum only to rounding.  Small scatters issue one float atomic per
+ * element.  Larger ones first combine the gradient rows of repeated tokens
+ * (sort by the token part of the hash, run-wise sums) and issue the atomics
+ * once per run; the largest (arrays of 2^26 slots or more with 2^21 tokens or
+ * more) then sort the blocks by destination region and sum each region in LDS,
+ * with no float atomic at all.  The sorted paths need the workspace and rows,
  * n_indices below 2^31 - 1.  With a CSR that is not non-decreasing, bag bounds
  * are clamped to [0, n_indices] so nothing outside the buffers is touched, but
  * which tokens such bags hold is unspecified here.  The sort step records
