@@ -12,6 +12,7 @@
 //   ROBE_TUNE_XCD = 0 | 1 | 2                    row order: memory order / table by table per XCD /
 //                                               the latter even for tiny launches
 //   ROBE_TUNE_BWD_MODE = direct | dedup | regions   backward scatter strategy
+//   ROBE_TUNE_BWD_TILE = 0 | 2                   direct single-hot backward never / always with the per-tile combining
 //   ROBE_TUNE_FUSED = regions | twostep          how robe_backward_adagrad runs
 //   ROBE_TUNE_RSHIFT = 10..15                    log2 of the region size of the region-sorted scatter
 //   ROBE_TUNE_KEY_BITS = 8..31                   key bits the backward sort looks at
@@ -204,7 +205,13 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
         const int tl = atoi(s);
         if (tl >= (int)step && tl <= 64 && tl % (int)step == 0) q.TL = (uint32_t)tl;
     }
-    const int64_t rows_per_wave = bags ? (int64_t)step : (int64_t)q.TL;
+    // single-hot backward: tiles of 64 lookups whose duplicates are combined before the atomics
+    // (ROBE_TUNE_BWD_TILE=0: the plain scatter)
+    // from 16384 lookups on: below that the 64-lookup tiles leave too few wavefronts (measured: 6656
+    // lookups 9 us plain, 21 us tiled; 53248 lookups 34 us plain, 22 us tiled).  ROBE_TUNE_BWD_TILE=2 forces it.
+    const int tile_mode = env_int("ROBE_TUNE_BWD_TILE", 1);
+    const bool tile = BWD && !bags && !lay.consec && (tile_mode == 2 || (tile_mode == 1 && rows >= 16384));
+    const int64_t rows_per_wave = tile ? 64 : (bags ? (int64_t)step : (int64_t)q.TL);
     const int64_t waves = (rows + rows_per_wave - 1) / rows_per_wave;
     int64_t blocks = (waves + robe::kWavesPerBlock - 1) / robe::kWavesPerBlock;
     // Walk the rows table by table, one eighth of that order per XCD (see RowWalk), unless the launch
@@ -215,7 +222,9 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
     // lookups with larger blocks the row writes dominate and the memory order is slightly faster.
     // The direct backward scatter keeps the memory order too: table by table, the copies of a frequent
     // token arrive close together in time and their same-address atomics serialise (measured 30 % slower).
-    const int xcd_mode = env_int("ROBE_TUNE_XCD", (!BWD && (bags || h->Z * 4 <= 64)) ? 1 : 0);   // 2: even for tiny launches
+    // With tiles that combine their duplicates it is the other way round: a tile of one table holds
+    // many copies of that table's frequent tokens.
+    const int xcd_mode = env_int("ROBE_TUNE_XCD", ((!BWD && (bags || h->Z * 4 <= 64)) || tile) ? 1 : 0);   // 2: even for tiny launches
     if (F >= 2 && ((xcd_mode == 1 && blocks >= 64) || xcd_mode == 2)) {
         q.bpx = (uint32_t)((blocks + robe::kXcds - 1) / robe::kXcds);
         blocks = (int64_t)q.bpx * robe::kXcds;
@@ -241,6 +250,22 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
         }                                                            \
     } while (0)
 
+#define ROBE_LAUNCH_TILE(V_)                                                                                          \
+    do {                                                                                                              \
+        if (sign) robe::single_hot_backward_tile_kernel<V_, true><<<grid, block, 0, stream>>>(p, q, src, indices, rows, dst);  \
+        else robe::single_hot_backward_tile_kernel<V_, false><<<grid, block, 0, stream>>>(p, q, src, indices, rows, dst);      \
+    } while (0)
+    if constexpr (BWD && sizeof(AT) == 4) {
+        if (tile) {
+            switch (lay.V) {
+                case 1: ROBE_LAUNCH_TILE(1); break;
+                case 2: ROBE_LAUNCH_TILE(2); break;
+                default: ROBE_LAUNCH_TILE(4); break;
+            }
+            return check_launch("backward (tiles)");
+        }
+    }
+#undef ROBE_LAUNCH_TILE
     switch (lay.V) {
         case 1: ROBE_LAUNCH_CS(1); break;
         case 2: ROBE_LAUNCH_CS(2); break;

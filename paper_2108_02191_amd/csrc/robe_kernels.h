@@ -317,6 +317,86 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
 }
 
 // ---------------------------------------------------------------------------
+// Single-hot backward for the direct scatter, with the duplicates of a tile combined first.
+//
+// Float atomics on one address serialise (tens of nanoseconds each), and a table with a handful of
+// distinct tokens sends thousands of lookups of a batch to the same d addresses.  A wavefront takes
+// a tile of 64 lookups - with the table-by-table row walk, 64 consecutive samples of one table -
+// finds the distinct tokens among them (ballots over the staged hash terms), and every lane group
+// sums the gradient rows of one distinct token at a time and scatters the sum once.  Strided lane
+// layout (lanes of a group on consecutive addresses), as in the plain scatter.
+// ---------------------------------------------------------------------------
+template <int V, bool SIGN>
+__global__ __launch_bounds__(kBlock) void single_hot_backward_tile_kernel(Params p, Geom q,
+                                                                          const float *__restrict__ grad_out,
+                                                                          const int64_t *__restrict__ indices,
+                                                                          int64_t rows,
+                                                                          float *__restrict__ grad_array)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    RowWalk w;
+    if (!start_walk(q, rows, 64, w)) return;             // uniform over the wavefront
+    const uint32_t n = (uint32_t)((rows - w.q0) < 64 ? (rows - w.q0) : 64);
+
+    // lane l hashes the l-th lookup of the tile
+    uint32_t th = 0, tg = 0;
+    const bool have = lane < n;
+    if (have) {
+        const RowRef k = walk_row(q, w, lane, p.d);
+        const int64_t x = indices[k.in_row];
+        th = staged_h(p, x, k.e);
+        if constexpr (SIGN) tg = staged_g(p, x, k.e);
+    }
+    // Distinct tokens: the lowest lane of every set of equal (th, tg) leads it and keeps the set.
+    // (Equal th means equal offsets; with the sign on, equal tg as well means equal signs.)
+    uint64_t remaining = __ballot(have), members = 0;
+    while (remaining) {                                   // one round per distinct token; uniform
+        const int lead = __ffsll((unsigned long long)remaining) - 1;
+        const uint32_t lth = __shfl(th, lead), ltg = SIGN ? __shfl(tg, lead) : 0u;
+        const uint64_t same = __ballot(have && th == lth && (!SIGN || tg == ltg));
+        if ((int)lane == lead) members = same;
+        remaining &= ~same;
+    }
+    const uint32_t mem_lo = (uint32_t)members, mem_hi = (uint32_t)(members >> 32);
+
+    const uint32_t grp = lane & (q.G - 1u);
+    const uint32_t sub = lane >> q.g_shift;
+    const uint32_t step = 64u >> q.g_shift;               // lane groups per wavefront
+    Lane<V, false, SIGN> L;
+    L.init(p, q, grp);
+
+    // group `sub` takes the leaders among lanes sub, sub + step, ...
+    for (uint32_t l0 = 0; l0 < 64u; l0 += step) {         // same trip count for every lane
+        const uint32_t lead = l0 + sub;
+        uint64_t todo = ((uint64_t)__shfl(mem_hi, (int)lead) << 32) | __shfl(mem_lo, (int)lead);
+        const uint32_t lth = __shfl(th, (int)lead), ltg = SIGN ? __shfl(tg, (int)lead) : 0u;
+        const bool any_rows = todo != 0;
+        float acc[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) acc[k] = 0.0f;
+        while (__any(todo != 0)) {                        // kUnroll rows of the set in flight
+            float v[kUnroll][V];
+            bool live[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                live[u] = todo != 0;
+                const uint32_t j = live[u] ? (uint32_t)(__ffsll((unsigned long long)todo) - 1) : 0u;
+                todo &= todo - 1u;                        // (0 stays 0)
+                load_row<V, false>(grad_out + walk_row(q, w, j, p.d).out_off, q, grp, v[u]);   // lookup 0 stands in
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (live[u]) {
+#pragma unroll
+                    for (int k = 0; k < V; ++k) acc[k] += v[u][k];
+                }
+            }
+        }
+        if (any_rows) L.scatter(p, grad_array, lth, ltg, acc);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Bag-sum forward / bag backward: one group of G lanes per bag, 64/G bags per
 // wavefront.  A group stages up to G of its bag's tokens at a time.
 // ---------------------------------------------------------------------------

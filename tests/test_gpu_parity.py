@@ -178,6 +178,28 @@ def test_backward_single_hot_and_bags(m, d, Z, sign, mode, monkeypatch):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("tile,xcd", [("2", "0"), ("2", "2"), ("0", "0"), ("0", "2")])
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,d,Z,B,F", [(1_000_003, 128, 32, 700, 26), (100_003, 16, 4, 2048, 26), (37, 16, 8, 300, 5),
+                                       (70_001, 64, 64, 129, 3), (4099, 8, 1, 1000, 7), (9973, 256, 32, 65, 2),
+                                       (999_983, 2, 2, 5000, 26), (500, 1, 1, 200, 1)])
+def test_direct_single_hot_backward_with_and_without_tile_combining(m, d, Z, B, F, sign, tile, xcd, monkeypatch):
+    # the direct scatter: tiles of 64 lookups with their duplicates combined (in memory order and
+    # walked table by table), and the plain one-atomic-per-element kernel; tables of 3 to 10^6 tokens
+    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", "direct")
+    monkeypatch.setenv("ROBE_TUNE_BWD_TILE", tile)
+    monkeypatch.setenv("ROBE_TUNE_XCD", xcd)
+    h, H = both_hashes(29 * m + Z + sign, m, d, Z, sign)
+    rng = np.random.default_rng(m + B)
+    card = np.array([3, 10, 1000, 10**6] * 7)[:F]
+    ids = (rng.integers(0, 2**40, size=(B, F)) % card).astype(np.int64)
+    G = rng.standard_normal((B, F, d)).astype(np.float32)
+    check_backward(h, H, G, ids, None, B, F)
+    Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+    got, want = check_backward(h, H, Gi, ids, None, B, F)
+    assert np.array_equal(got, want)
+
+
 @pytest.mark.parametrize("mode", ["direct", "dedup", "regions"])
 def test_backward_accumulates_onto_existing_values(mode, monkeypatch):
     monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
