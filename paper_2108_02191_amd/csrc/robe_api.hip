@@ -1,6 +1,8 @@
 // C ABI of the ROBE-Z library (see include/robe.h): argument validation,
 // launch geometry and kernel selection.  All device work is in robe_kernels.h
-// and robe_backward_dedup.h.
+// (forward, direct backward, update rules), robe_backward_dedup.h (sorted
+// backward with float atomics) and robe_backward_regions.h (sorted backward
+// without them, fused Adagrad).
 //
 // Tuning knobs, read from the environment at call time (for experiments and for
 // tests that must reach every kernel variant; the defaults are the measured
