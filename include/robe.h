@@ -52,7 +52,7 @@ extern "C" {
 #define ROBE_EINVAL  (-1)  /* bad argument: null pointer, bad shape, value out of range */
 #define ROBE_EHIP    (-2)  /* a HIP runtime call or kernel launch failed                 */
 
-#define ROBE_PRIME 2147483647u /* P = 2^31 - 1, the "large prime" of Eq. 2 / Eq. 5 */
+#define ROBE_PRIME 2147483647u /* P = 2^31 - 1, the prime modulus of Eq. 2 / Eq. 5 */
 
 /*
  * One ROBE-Z instance (Eq. 5 and the text under it; g from Eq. 2).
