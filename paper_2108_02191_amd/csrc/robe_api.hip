@@ -120,12 +120,12 @@ bool tuned_layout(const char *var, const robe_hash_t *h, Layout *out)
     if (!s) return false;
     int V = 0, consec = 0;
     if (sscanf(s, "%d,%d", &V, &consec) != 2) return false;
-    if (V == 0 || h->Z > h->d) { *out = {0, false, 0}; return true; }
+    if (V == 0) { *out = {0, false, 0}; return true; }
     if (V != 1 && V != 2 && V != 4) return false;
     if (h->d % V) return false;
     const uint32_t G = h->d / V;
     if (!is_pow2(G) || G > 64) return false;
-    if (consec && h->Z % V) return false;
+    if (consec && h->Z <= h->d && h->Z % V) return false;
     *out = {V, consec != 0, G};
     return true;
 }
@@ -136,12 +136,13 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
     if (tuned_layout(bwd ? "ROBE_TUNE_BWD" : "ROBE_TUNE_FWD", h, &t)) {
         if (!t.consec || aligned(rows_ptr, 4 * (size_t)t.V)) return t;
     }
-    if (h->Z > h->d) return {0, false, 0};   // embeddings sharing a chunk: shape-generic kernel
+    // (blocks larger than embeddings, Z > d: an embedding is one contiguous piece of its chunk, so
+    // any V that divides d stays inside it)
     const int vs[3] = {4, 2, 1};
     if (!bwd) {
         // forward: widest per-lane load that stays inside one chunk
         for (int V : vs) {
-            if (h->Z % V || h->d % V) continue;
+            if ((h->Z <= h->d && h->Z % V) || h->d % V) continue;
             const uint32_t G = h->d / V;
             if (is_pow2(G) && G <= 64 && aligned(rows_ptr, 4 * (size_t)V)) return {V, true, G};
         }
@@ -335,7 +336,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     // 32-bit positions and row numbers
     if (rows < 1 || n_indices < 1 || rows >= 0x7FFFFFFFll || n_indices >= 0x7FFFFFFFll) return pl;
     pl.lay = pick_layout(h, true, grad_out);
-    if (pl.lay.V == 0 || pl.lay.consec) return pl;   // shapes only the generic kernel handles
+    if (pl.lay.V == 0 || pl.lay.consec || h->Z > h->d) return pl;   // shapes the sorted routes do not handle
     // sorting costs about 0.1 ms plus 45 ns per thousand tokens: not worth it for small scatters
     if (!forced && (uint64_t)n_indices * h->d < (1ull << 25)) return pl;
     // Sorting on the top 24 key bits is one radix pass cheaper; tokens that share those bits merely

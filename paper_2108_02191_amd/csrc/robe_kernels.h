@@ -158,10 +158,12 @@ struct Lane {
         }
     }
 
-    // Array position of pair k for a token whose staged term is th.
-    __device__ __forceinline__ uint32_t position(const Params &p, uint32_t th, int k) const
+    // Array position of pair k for a token whose staged term is th.  `place` is 0 unless blocks are
+    // larger than embeddings (Z > d): then it is where the token's embedding starts inside its chunk,
+    // place + jj < Z <= m, so one wrap still does.
+    __device__ __forceinline__ uint32_t position(const Params &p, uint32_t th, int k, uint32_t place = 0) const
     {
-        return wrap(offset_of(p, th, cc[k]) + jj[k], p.m);
+        return wrap(offset_of(p, th, cc[k]) + jj[k] + place, p.m);
     }
 
     __device__ __forceinline__ uint32_t mask(uint32_t tg, int k) const
@@ -172,10 +174,10 @@ struct Lane {
     // v[k] = g * M[idx] for the V owned elements of one token.
     template <typename AT>
     __device__ __forceinline__ void gather(const Params &p, const AT *__restrict__ array,
-                                           uint32_t th, uint32_t tg, float (&v)[V]) const
+                                           uint32_t th, uint32_t tg, float (&v)[V], uint32_t place = 0) const
     {
         if constexpr (CONSEC) {
-            const uint32_t pos = position(p, th, 0);
+            const uint32_t pos = position(p, th, 0, place);
             if (V == 1 || pos + V <= p.m) {
                 if constexpr (sizeof(AT) == 4) {
                     const typename Vec<V>::A u = *reinterpret_cast<const typename Vec<V>::U *>(array + pos);
@@ -192,7 +194,7 @@ struct Lane {
             }
         } else {
 #pragma unroll
-            for (int k = 0; k < V; ++k) v[k] = widen(array[position(p, th, k)]);
+            for (int k = 0; k < V; ++k) v[k] = widen(array[position(p, th, k, place)]);
         }
         if constexpr (SIGN) {
 #pragma unroll
@@ -202,13 +204,13 @@ struct Lane {
 
     // grad_array[idx] += g * v[k] for the V owned elements of one token.
     __device__ __forceinline__ void scatter(const Params &p, float *__restrict__ grad_array,
-                                            uint32_t th, uint32_t tg, const float (&v)[V]) const
+                                            uint32_t th, uint32_t tg, const float (&v)[V], uint32_t place = 0) const
     {
-        const uint32_t pos0 = CONSEC ? position(p, th, 0) : 0u;
+        const uint32_t pos0 = CONSEC ? position(p, th, 0, place) : 0u;
 #pragma unroll
         for (int k = 0; k < V; ++k) {
             // CONSEC: every element wraps on its own
-            const uint32_t pos = CONSEC ? wrap(pos0 + (uint32_t)k, p.m) : position(p, th, k);
+            const uint32_t pos = CONSEC ? wrap(pos0 + (uint32_t)k, p.m) : position(p, th, k, place);
             const float val = SIGN ? apply_sign(v[k], mask(tg, k)) : v[k];
             __hip_atomic_fetch_add(grad_array + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -243,6 +245,17 @@ __device__ __forceinline__ void load_row(const float *__restrict__ row, const Ge
     }
 }
 
+// Blocks larger than embeddings (Z > d, Section 3.3): r = Z / d consecutive tokens of a table share
+// a chunk.  The chunk id x div r takes the token's seat in h, and the embedding starts
+// (x mod r) * d places into the chunk.  Otherwise the key is the token and the place is 0.
+__device__ __forceinline__ int64_t block_key(const Params &p, int64_t x, uint32_t &place)
+{
+    place = 0;
+    if (p.r == 0) return x;
+    place = (uint32_t)((uint64_t)x % p.r) * p.d;
+    return (int64_t)((uint64_t)x / p.r);
+}
+
 // Token-and-table part of h (and of g) for one token.
 __device__ __forceinline__ uint32_t staged_h(const Params &p, int64_t x, uint32_t e)
 {
@@ -269,11 +282,11 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
     const uint32_t n = (uint32_t)((rows - w.q0) < (int64_t)q.TL ? (rows - w.q0) : (int64_t)q.TL);
 
     // pass 1: lane l hashes the l-th lookup of the tile
-    uint32_t th = 0, tg = 0;
+    uint32_t th = 0, tg = 0, pl = 0;
     if (lane < n) {
         const RowRef k = walk_row(q, w, lane, p.d);
         const int64_t x = indices[k.in_row];
-        th = staged_h(p, x, k.e);
+        th = staged_h(p, block_key(p, x, pl), k.e);
         if constexpr (SIGN) tg = staged_g(p, x, k.e);
     }
 
@@ -285,7 +298,7 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
     L.init(p, q, grp);
 
     for (uint32_t r = 0; r < n; r += step * kUnroll) {  // trip count uniform over the wavefront
-        uint32_t rl[kUnroll], thr[kUnroll], tgr[kUnroll];
+        uint32_t rl[kUnroll], thr[kUnroll], tgr[kUnroll], plr[kUnroll];
         bool live[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -294,11 +307,12 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
             const uint32_t srcl = live[u] ? rl[u] : 0u;
             thr[u] = __shfl(th, (int)srcl);
             tgr[u] = SIGN ? __shfl(tg, (int)srcl) : 0u;
+            plr[u] = p.r ? __shfl(pl, (int)srcl) : 0u;
         }
         if constexpr (!BWD) {
             float v[kUnroll][V];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u]);  // lookup 0 stands in for dead slots
+            for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u], plr[u]);  // lookup 0 stands in for dead slots
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
                 if (live[u]) store_row<V, CONSEC>(dst + walk_row(q, w, rl[u], p.d).out_off, q, grp, v[u]);
@@ -311,7 +325,7 @@ __global__ __launch_bounds__(kBlock) void single_hot_kernel(Params p, Geom q,
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
-                if (live[u]) L.scatter(p, dst, thr[u], tgr[u], v[u]);
+                if (live[u]) L.scatter(p, dst, thr[u], tgr[u], v[u], plr[u]);
         }
     }
 }
@@ -339,21 +353,21 @@ __global__ __launch_bounds__(kBlock) void single_hot_backward_tile_kernel(Params
     const uint32_t n = (uint32_t)((rows - w.q0) < 64 ? (rows - w.q0) : 64);
 
     // lane l hashes the l-th lookup of the tile
-    uint32_t th = 0, tg = 0;
+    uint32_t th = 0, tg = 0, pl = 0;
     const bool have = lane < n;
     if (have) {
         const RowRef k = walk_row(q, w, lane, p.d);
         const int64_t x = indices[k.in_row];
-        th = staged_h(p, x, k.e);
+        th = staged_h(p, block_key(p, x, pl), k.e);
         if constexpr (SIGN) tg = staged_g(p, x, k.e);
     }
-    // Distinct tokens: the lowest lane of every set of equal (th, tg) leads it and keeps the set.
-    // (Equal th means equal offsets; with the sign on, equal tg as well means equal signs.)
+    // Distinct tokens: the lowest lane of every set of equal (th, place, tg) leads it and keeps the
+    // set.  (Equal th and place mean equal offsets; with the sign on, equal tg as well means equal signs.)
     uint64_t remaining = __ballot(have), members = 0;
     while (remaining) {                                   // one round per distinct token; uniform
         const int lead = __ffsll((unsigned long long)remaining) - 1;
-        const uint32_t lth = __shfl(th, lead), ltg = SIGN ? __shfl(tg, lead) : 0u;
-        const uint64_t same = __ballot(have && th == lth && (!SIGN || tg == ltg));
+        const uint32_t lth = __shfl(th, lead), ltg = SIGN ? __shfl(tg, lead) : 0u, lpl = __shfl(pl, lead);
+        const uint64_t same = __ballot(have && th == lth && pl == lpl && (!SIGN || tg == ltg));
         if ((int)lane == lead) members = same;
         remaining &= ~same;
     }
@@ -370,6 +384,7 @@ __global__ __launch_bounds__(kBlock) void single_hot_backward_tile_kernel(Params
         const uint32_t lead = l0 + sub;
         uint64_t todo = ((uint64_t)__shfl(mem_hi, (int)lead) << 32) | __shfl(mem_lo, (int)lead);
         const uint32_t lth = __shfl(th, (int)lead), ltg = SIGN ? __shfl(tg, (int)lead) : 0u;
+        const uint32_t lpl = p.r ? __shfl(pl, (int)lead) : 0u;
         const bool any_rows = todo != 0;
         float acc[V];
 #pragma unroll
@@ -392,7 +407,7 @@ __global__ __launch_bounds__(kBlock) void single_hot_backward_tile_kernel(Params
                 }
             }
         }
-        if (any_rows) L.scatter(p, grad_array, lth, ltg, acc);
+        if (any_rows) L.scatter(p, grad_array, lth, ltg, acc, lpl);
     }
 }
 
@@ -441,14 +456,14 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
         // stage: lane `grp` of the group hashes token tb + grp
         const int64_t left = t1 - tb;                       // <= 0 once this group is done
         const uint32_t cnt = left <= 0 ? 0u : (left < (int64_t)q.G ? (uint32_t)left : q.G);
-        uint32_t th = 0, tg = 0;
+        uint32_t th = 0, tg = 0, pl = 0;
         if (grp < cnt) {
             const int64_t x = indices[tb + grp];
-            th = staged_h(p, x, e);
+            th = staged_h(p, block_key(p, x, pl), e);
             if constexpr (SIGN) tg = staged_g(p, x, e);
         }
         for (uint32_t u0 = 0; __any(u0 < cnt); u0 += kUnroll) {
-            uint32_t thr[kUnroll], tgr[kUnroll];
+            uint32_t thr[kUnroll], tgr[kUnroll], plr[kUnroll];
             bool live[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -456,11 +471,12 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
                 const uint32_t srcl = base_lane + (live[u] ? u0 + u : 0u);
                 thr[u] = __shfl(th, (int)srcl);
                 tgr[u] = SIGN ? __shfl(tg, (int)srcl) : 0u;
+                plr[u] = p.r ? __shfl(pl, (int)srcl) : 0u;
             }
             if constexpr (!BWD) {
                 float v[kUnroll][V];
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u]);
+                for (int u = 0; u < kUnroll; ++u) L.gather(p, src, thr[u], tgr[u], v[u], plr[u]);
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     if (live[u]) {
@@ -471,7 +487,7 @@ __global__ __launch_bounds__(kBlock) void bag_kernel(Params p, Geom q,
             } else {
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u)
-                    if (live[u]) L.scatter(p, dst, thr[u], tgr[u], acc);
+                    if (live[u]) L.scatter(p, dst, thr[u], tgr[u], acc, plr[u]);
             }
         }
     }
