@@ -3,7 +3,8 @@ structure and id ranges drawn from a fixed seed, each checked against the
 oracle to the bars of the parity suite.  The draws cover what the fixed cases
 may miss: odd batch and table counts, arrays barely larger than a block,
 embeddings sharing a block (Z > d), bags from empty to hundreds of tokens,
-negative and huge ids, both row orders and both scatter strategies."""
+negative and huge ids, both row orders and every scatter strategy; the
+bfloat16 array and tables of mixed dimensions ride along on the same draws."""
 import os
 
 import numpy as np
@@ -59,6 +60,7 @@ def test_random_problems_match_the_oracle(chunk, monkeypatch):
         m, d, Z, B, F, sign = draw_case(rng)
         monkeypatch.setenv("ROBE_TUNE_XCD", str(int(rng.choice([0, 2]))))
         monkeypatch.setenv("ROBE_TUNE_BWD_MODE", str(rng.choice(["direct", "dedup", "regions"])))
+        monkeypatch.setenv("ROBE_TUNE_BWD_TILE", str(rng.choice(["0", "2"])))
         tag = f"chunk {chunk} case {case}: m={m} d={d} Z={Z} B={B} F={F} sign={sign}"
         print(tag, flush=True)
         seed = int(rng.integers(0, 2**63))
@@ -91,3 +93,34 @@ def test_random_problems_match_the_oracle(chunk, monkeypatch):
             robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, ga)
             ref, _ = oracle.backward(H, Gi, i_, o_, B, F, threads=1)
             assert np.array_equal(ga.cpu().numpy().astype(np.float64), ref), tag
+            # the same call in reproducible mode gives the same sums (exact here) when it has a route
+            if Z <= d:
+                robe.robe_set_reproducible(True)
+                try:
+                    gr = torch.zeros(m, dtype=torch.float32, device=DEV)
+                    try:
+                        robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, gr)
+                    except robe.RobeError as e:
+                        assert "reproducible" in str(e), tag      # shapes without an atomic-free route
+                    else:
+                        assert np.array_equal(gr.cpu().numpy().astype(np.float64), ref), tag
+                finally:
+                    robe.robe_set_reproducible(False)
+        # bfloat16 array: single-hot bit-exact
+        Mb = oracle.to_bf16(M)
+        outq = robe.robe_forward_bf16(h, dev(Mb.view(np.int16)), dev(ids), None, B, F).cpu().numpy()
+        wantq = oracle.forward_bf16(H, Mb, ids, None, B, F)
+        assert np.array_equal(outq.view(np.int32), wantq.view(np.int32)), tag
+        # tables of mixed dimensions (multiples of Z), single-hot forward bit-exact, backward exact
+        if Z <= 64:
+            dims = [int(Z * rng.integers(1, 5)) for _ in range(F)]
+            if F > 2:
+                dims[1] = dims[0]                                     # a run of equal dimensions
+            outm = robe.robe_forward_mixed(h, dims, dev(M), dev(ids), None, B).cpu().numpy()
+            wantm = oracle.forward_mixed(H, dims, M, ids, None, B)
+            assert np.array_equal(outm.view(np.int32), wantm.view(np.int32)), tag
+            Gm = rng.integers(-3, 4, size=(B, sum(dims))).astype(np.float32)
+            gm = torch.zeros(m, dtype=torch.float32, device=DEV)
+            robe.robe_backward_mixed(h, dims, dev(Gm), dev(idsb), dev(off), B, gm)
+            refm, _ = oracle.backward_mixed(H, dims, Gm, idsb, off, B)
+            assert np.array_equal(gm.cpu().numpy().astype(np.float64), refm), tag
