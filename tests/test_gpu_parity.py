@@ -576,3 +576,38 @@ def test_runs_on_a_side_stream_and_reports_bad_sizes():
     rc = robe.lib().robe_forward(ctypes.byref(h), Md.data_ptr(), idd.data_ptr(), None,
                                  B * F + 1, B, F, out.data_ptr(), None)
     assert rc == robe.ROBE_EINVAL and b"n_indices" in robe.lib().robe_last_error()
+
+
+@pytest.mark.parametrize("m,modes", [(2**30, ("direct", "dedup", "regions")), (2**31 - 1, ("direct", "dedup"))])
+def test_backward_on_the_largest_arrays(m, modes, monkeypatch):
+    # 2^30 slots is the largest array the region-sorted route takes (32768 regions of 2^15 floats),
+    # 2^31 - 1 the largest array at all; small-integer gradients make every route exact
+    d, Z, B, F = 128, 32, 2048, 26
+    rng = np.random.default_rng(m % 1000)
+    h, H = both_hashes(99, m, d, Z, 1)
+    sizes = rng.poisson(4.0, size=B * F).astype(np.int64)
+    off = np.zeros(B * F + 1, dtype=np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ids = rng.integers(0, 10**5, size=int(off[-1]), dtype=np.int64)
+    ids[rng.random(ids.size) < 0.2] = 5
+    G = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+    ref, _ = oracle.backward(H, G, ids, off, B, F, threads=THREADS, want_abs=False)
+    nz = np.flatnonzero(ref)
+    Gd, idd, offd = to_dev(G), to_dev(ids), to_dev(off)
+    for mode in modes:
+        monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
+        ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+        robe.robe_backward(h, Gd, idd, offd, B, F, ga)
+        assert int(torch.count_nonzero(ga).item()) == nz.size, mode
+        assert np.array_equal(ga[torch.from_numpy(nz).to(DEV)].cpu().numpy().astype(np.float64), ref[nz]), mode
+        del ga
+        if mode == "regions":
+            monkeypatch.setenv("ROBE_TUNE_FUSED", "regions")
+            Md = torch.zeros(m, dtype=torch.float32, device=DEV)
+            sd = torch.zeros(m, dtype=torch.float32, device=DEV)
+            robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Md, sd, 0.01, 1e-8)
+            assert int(torch.count_nonzero(sd).item()) == nz.size
+            got_s = sd[torch.from_numpy(nz).to(DEV)].cpu().numpy()
+            assert np.array_equal(got_s, ref[nz].astype(np.float32) ** 2)
+            del Md, sd
+    torch.cuda.empty_cache()
