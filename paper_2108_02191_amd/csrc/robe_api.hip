@@ -517,7 +517,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
         if (int rc = check_launch("backward (records)")) return rc;
 
         // R5: one workgroup per region
-        const size_t lds_red = ((size_t)1 << r.r_shift) * 4 + (size_t)robe::kRecBatch * (sign ? 12 : 8) + (64 + 65 + 1) * 4   // region + batch + slice counters
+        const size_t lds_red = ((size_t)1 << r.r_shift) * 4 + (sign ? (size_t)robe::rec_batch<true>() * 12 : (size_t)robe::rec_batch<false>() * 8) + (64 + 65 + 1) * 4   // region + batch + slice counters
                                + (pl.spill_rows ? (size_t)robe::kSpillFloats * 4 : 0);
         const int vec_ok = aligned(grad_array, 16) && (rule == 0 || aligned(state, 16)) ? 1 : 0;
         const dim3 rgrid(r.NR), rblock(robe::kReduceBlock);

@@ -34,9 +34,10 @@ constexpr int kRowsAhead = 8;          // gradient rows a lane group requests be
 constexpr int kStretch = 8;            // stretches of G sorted positions a lane group walks in R1
 constexpr int kBinBlock = 1024;        // R2 / R4
 constexpr int kReduceBlock = 512;      // R5 (the slice arithmetic assumes 2^9)
-constexpr int kRecBatch = 640;         // records sorted and applied per round in R5 (at most 2 per thread);
-                                       // 32 KB region + batch + counters + spill-over rows stay under 40 KB:
-                                       // four workgroups per CU
+// Records sorted and applied per round in R5 (at most 2 per thread).  32 KB region + batch (8 bytes
+// a record, 12 with the sign term) + counters + spill-over rows stay under 40 KB: four workgroups per CU.
+template <bool SIGN>
+constexpr int rec_batch() { return SIGN ? 448 : 640; }
 constexpr uint32_t kSpillFloats = 512; // LDS floats for the spill-over rows of R5 (used when groups * Z fits)
 constexpr int kRecAhead = 8;           // gradient blocks a lane group requests before adding them (R5)
 constexpr int kCanonAhead = 4;         // records of a slice compared per step when R5 puts them in canonical order
@@ -412,6 +413,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                                                                      float *__restrict__ state,    // RULE 1 only
                                                                      float lr, float eps, int vec_ok)
 {
+    constexpr int kRecBatch = rec_batch<SIGN>();
     extern __shared__ float acc[];  // 2^r_shift floats, then the batch staging area
     const uint32_t r = s.counts[blockIdx.x];     // after R3: the regions, fullest first
     if (r >= s.NR) return;
