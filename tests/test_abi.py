@@ -27,6 +27,14 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, n) is not None
 
 
+def test_header_is_plain_c():
+    # the boundary is a C ABI: the header must compile as C99 on its own
+    import subprocess
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "robe.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_struct_layout_matches_header():
     # uint64 m; uint32 d, Z, use_sign, P; 8 x uint32 coefficients
     assert ctypes.sizeof(robe.RobeHash) == 8 + 4 * 4 + 8 * 4
