@@ -210,10 +210,11 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
     }
     // single-hot backward: tiles of 64 lookups whose duplicates are combined before the atomics
     // (ROBE_TUNE_BWD_TILE=0: the plain scatter)
-    // from 16384 lookups on: below that the 64-lookup tiles leave too few wavefronts (measured: 6656
-    // lookups 9 us plain, 21 us tiled; 53248 lookups 34 us plain, 22 us tiled).  ROBE_TUNE_BWD_TILE=2 forces it.
+    // from 32768 lookups on: below that the 64-lookup tiles leave too few wavefronts (measured at
+    // d = 128: 26624 lookups 27 us plain, 32 us tiled; 53248 lookups 56 us plain, 38 us tiled).
+    // ROBE_TUNE_BWD_TILE=2 forces it.
     const int tile_mode = env_int("ROBE_TUNE_BWD_TILE", 1);
-    const bool tile = BWD && !bags && !lay.consec && (tile_mode == 2 || (tile_mode == 1 && rows >= 16384));
+    const bool tile = BWD && !bags && !lay.consec && (tile_mode == 2 || (tile_mode == 1 && rows >= 32768));
     const int64_t rows_per_wave = tile ? 64 : (bags ? (int64_t)step : (int64_t)q.TL);
     const int64_t waves = (rows + rows_per_wave - 1) / rows_per_wave;
     int64_t blocks = (waves + robe::kWavesPerBlock - 1) / robe::kWavesPerBlock;

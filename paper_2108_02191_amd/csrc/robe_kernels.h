@@ -379,35 +379,56 @@ __global__ __launch_bounds__(kBlock) void single_hot_backward_tile_kernel(Params
     Lane<V, false, SIGN> L;
     L.init(p, q, grp);
 
-    // group `sub` takes the leaders among lanes sub, sub + step, ...
-    for (uint32_t l0 = 0; l0 < 64u; l0 += step) {         // same trip count for every lane
-        const uint32_t lead = l0 + sub;
-        uint64_t todo = ((uint64_t)__shfl(mem_hi, (int)lead) << 32) | __shfl(mem_lo, (int)lead);
-        const uint32_t lth = __shfl(th, (int)lead), ltg = SIGN ? __shfl(tg, (int)lead) : 0u;
-        const uint32_t lpl = p.r ? __shfl(pl, (int)lead) : 0u;
-        const bool any_rows = todo != 0;
-        float acc[V];
+    // Group `sub` takes the leaders among lanes sub, sub + step, ..., kUnroll of them at a time: the
+    // first row of each is requested at once (distinct tokens keep kUnroll rows in flight, as in the
+    // plain scatter), the further rows of a set follow, and every set is scattered once.
+    for (uint32_t l0 = 0; l0 < 64u; l0 += step * kUnroll) {        // same trip count for every lane
+        uint64_t todo[kUnroll];
+        uint32_t lth[kUnroll], ltg[kUnroll], lpl[kUnroll];
+        bool any_rows[kUnroll];
+        float acc[kUnroll][V];
 #pragma unroll
-        for (int k = 0; k < V; ++k) acc[k] = 0.0f;
-        while (__any(todo != 0)) {                        // kUnroll rows of the set in flight
-            float v[kUnroll][V];
-            bool live[kUnroll];
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t lead = l0 + (uint32_t)u * step + sub;
+            const bool in = lead < 64u;
+            const int from = (int)(in ? lead : 0u);
+            todo[u] = ((uint64_t)__shfl(mem_hi, from) << 32) | __shfl(mem_lo, from);
+            if (!in) todo[u] = 0;
+            lth[u] = __shfl(th, from);
+            ltg[u] = SIGN ? __shfl(tg, from) : 0u;
+            lpl[u] = p.r ? __shfl(pl, from) : 0u;
+            any_rows[u] = todo[u] != 0;
+        }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                live[u] = todo != 0;
-                const uint32_t j = live[u] ? (uint32_t)(__ffsll((unsigned long long)todo) - 1) : 0u;
-                todo &= todo - 1u;                        // (0 stays 0)
-                load_row<V, false>(grad_out + walk_row(q, w, j, p.d).out_off, q, grp, v[u]);   // lookup 0 stands in
-            }
+        for (int u = 0; u < kUnroll; ++u) {                         // first row of every set
+            const uint32_t j = any_rows[u] ? (uint32_t)(__ffsll((unsigned long long)todo[u]) - 1) : 0u;
+            todo[u] &= todo[u] - 1u;                               // (0 stays 0)
+            load_row<V, false>(grad_out + walk_row(q, w, j, p.d).out_off, q, grp, acc[u]);   // lookup 0 stands in
+        }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (live[u]) {
+        for (int u = 0; u < kUnroll; ++u) {                         // the other rows of the set
+            while (__any(todo[u] != 0)) {
+                float v[kUnroll][V];
+                bool live[kUnroll];
 #pragma unroll
-                    for (int k = 0; k < V; ++k) acc[k] += v[u][k];
+                for (int t = 0; t < kUnroll; ++t) {
+                    live[t] = todo[u] != 0;
+                    const uint32_t j = live[t] ? (uint32_t)(__ffsll((unsigned long long)todo[u]) - 1) : 0u;
+                    todo[u] &= todo[u] - 1u;
+                    load_row<V, false>(grad_out + walk_row(q, w, j, p.d).out_off, q, grp, v[t]);
+                }
+#pragma unroll
+                for (int t = 0; t < kUnroll; ++t) {
+                    if (live[t]) {
+#pragma unroll
+                        for (int k = 0; k < V; ++k) acc[u][k] += v[t][k];
+                    }
                 }
             }
         }
-        if (any_rows) L.scatter(p, grad_array, lth, ltg, acc, lpl);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            if (any_rows[u]) L.scatter(p, grad_array, lth[u], ltg[u], acc[u], lpl[u]);
     }
 }
 
