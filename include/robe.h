@@ -241,6 +241,20 @@ int robe_forward_bf16(const robe_hash_t *hash, const uint16_t *array,
                       int64_t batch, int32_t n_features, float *out, void *stream);
 
 /*
+ * The stable radix sort the backward pass sorts its tokens with, on its own (a testing aid, like
+ * robe_offsets, and usable as a primitive): n pairs of 32-bit keys and values are sorted by key bits
+ * [lo_bit, hi_bit) in ascending order, pairs with equal bits keeping their input order.  Eight bits
+ * per pass, ping-pong between the two pairs of device buffers; both are overwritten, and
+ * *result_in_b (host) says whether the sorted pairs ended in (keys_b, vals_b) or (keys_a, vals_a).
+ *   workspace  device buffer of robe_sort_workspace_bytes(n) bytes, 256-byte aligned
+ * Errors: ROBE_EINVAL, ROBE_EHIP.  Records kernels only: it may be captured into a HIP graph.
+ */
+size_t robe_sort_workspace_bytes(uint64_t n);
+int robe_sort_pairs(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint32_t *vals_b, uint64_t n,
+                    uint32_t lo_bit, uint32_t hi_bit, void *workspace, size_t workspace_bytes, int *result_in_b,
+                    void *stream);
+
+/*
  * Run-to-run reproducible scatter (process-wide switch, off at start; returns the previous setting).
  * Eq. 3 sums float32 terms whose order the paper does not fix; with float atomics that order, and so
  * the last bits of the result, change from run to run.  While the switch is on, robe_backward and

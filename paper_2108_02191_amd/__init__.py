@@ -47,6 +47,7 @@ class RobeHash(ctypes.Structure):
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
            "robe_forward_mixed", "robe_backward_mixed", "robe_array_to_bf16", "robe_forward_bf16",
+           "robe_sort_workspace_bytes", "robe_sort_pairs",
            "robe_set_reproducible", "robe_last_error")
 
 _lib = None
@@ -90,6 +91,12 @@ def lib() -> ctypes.CDLL:
         L.robe_forward_bf16.restype = ctypes.c_int
         L.robe_forward_bf16.argtypes = [HP, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        L.robe_sort_workspace_bytes.restype = ctypes.c_size_t
+        L.robe_sort_workspace_bytes.argtypes = [ctypes.c_uint64]
+        L.robe_sort_pairs.restype = ctypes.c_int
+        L.robe_sort_pairs.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                      ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_size_t,
+                                      ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
         L.robe_set_reproducible.restype = ctypes.c_int
         L.robe_set_reproducible.argtypes = [ctypes.c_int]
         L.robe_last_error.restype = ctypes.c_char_p
@@ -288,3 +295,19 @@ def robe_forward_bf16(h: RobeHash, array_bf16: torch.Tensor, indices: torch.Tens
                                    _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                    indices.numel(), batch, n_features, _dev(out, torch.float32, "out"), _stream()))
     return out
+
+
+def robe_sort_pairs(keys: torch.Tensor, vals: torch.Tensor, lo_bit: int, hi_bit: int):
+    """Stable sort of (key, value) pairs (int32 tensors holding 32-bit patterns) by key bits [lo_bit, hi_bit).
+    The inputs are overwritten; returns the sorted (keys, vals)."""
+    n = keys.numel()
+    if vals.numel() != n:
+        raise ValueError("keys and vals differ in length")
+    kb, vb = torch.empty_like(keys), torch.empty_like(vals)
+    need = int(lib().robe_sort_workspace_bytes(n))
+    ws = torch.empty(max(need, 1), dtype=torch.uint8, device=keys.device)
+    in_b = ctypes.c_int(0)
+    _check(lib().robe_sort_pairs(_dev(keys, torch.int32, "keys"), _dev(vals, torch.int32, "vals"),
+                                 _dev(kb, torch.int32, "keys_b"), _dev(vb, torch.int32, "vals_b"), n, lo_bit, hi_bit,
+                                 ws.data_ptr(), need, ctypes.byref(in_b), _stream()))
+    return (kb, vb) if in_b.value else (keys, vals)

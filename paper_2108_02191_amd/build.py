@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librobe.so")
 SOURCES = ["robe_api.hip"]
-HEADERS = ["robe_device.h", "robe_kernels.h", "robe_backward_dedup.h", "robe_backward_regions.h", os.path.join("..", "..", "include", "robe.h")]
+HEADERS = ["robe_device.h", "robe_kernels.h", "robe_backward_dedup.h", "robe_backward_regions.h", "robe_radix_sort.h", os.path.join("..", "..", "include", "robe.h")]
 
 
 def hipcc_command(out: str = LIB) -> list:

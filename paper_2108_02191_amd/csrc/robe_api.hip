@@ -18,6 +18,7 @@
 //   ROBE_TUNE_FUSED = regions | twostep          how robe_backward_adagrad runs
 //   ROBE_TUNE_RSHIFT = 10..15                    log2 of the region size of the region-sorted scatter
 //   ROBE_TUNE_KEY_BITS = 8..31                   key bits the backward sort looks at
+//   ROBE_TUNE_SORT = library                     the device library's radix sort instead of robe_radix_sort.h
 #include <hip/hip_runtime.h>
 
 #include <atomic>
@@ -33,6 +34,7 @@
 
 #include "robe_backward_dedup.h"
 #include "robe_backward_regions.h"
+#include "robe_radix_sort.h"
 
 namespace {
 
@@ -291,6 +293,48 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
 using TokenSortConfig = rocprim::radix_sort_config<rocprim::default_config, rocprim::default_config,
                                                    rocprim::default_config, 32768>;
 
+// Stable sort of n (key, value) pairs on key bits [lo, hi) with the kernels of robe_radix_sort.h.
+// The sorted pairs end in (keys_b, vals_b) after an odd number of passes, else in (keys_a, vals_a):
+// *in_b says which.  temp: radix_sort_temp_bytes(n) bytes, 256-byte aligned.
+size_t radix_sort_temp_bytes(uint64_t n)
+{
+    const uint64_t tiles = (n + robe::kSortTile - 1) / robe::kSortTile;
+    return (size_t)(robe::kDigits * tiles * 4 + 4 * robe::kDigits * 4);      // tile counts + totals of up to 4 passes
+}
+
+int launch_radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint32_t *vals_b, uint32_t n,
+                      uint32_t lo, uint32_t hi, void *temp, hipStream_t stream, bool *in_b)
+{
+    *in_b = false;
+    if (n == 0 || hi <= lo) return ROBE_OK;
+    const uint32_t passes = (hi - lo + 7) / 8;
+    if (passes > 4) return fail(ROBE_EINVAL, "internal: more than 32 key bits");
+    robe::SortPass sp;
+    sp.n = n;
+    sp.tiles = (uint32_t)(((uint64_t)n + robe::kSortTile - 1) / robe::kSortTile);
+    sp.tile_count = static_cast<uint32_t *>(temp);
+    uint32_t *totals = sp.tile_count + (size_t)robe::kDigits * sp.tiles;
+    uint32_t *ks = keys_a, *vs = vals_a, *kd = keys_b, *vd = vals_b;
+    for (uint32_t pass = 0; pass < passes; ++pass) {
+        sp.shift = lo + 8 * pass;
+        const uint32_t bits = hi - sp.shift < 8 ? hi - sp.shift : 8;
+        sp.mask = (1u << bits) - 1u;
+        sp.totals = totals + pass * robe::kDigits;
+        robe::sort_count_kernel<<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks);
+        if (int rc = check_launch("sort (count)")) return rc;
+        robe::sort_totals_kernel<<<dim3(robe::kDigits), dim3(robe::kSortBlock), 0, stream>>>(sp);
+        if (int rc = check_launch("sort (totals)")) return rc;
+        robe::sort_offsets_kernel<<<dim3(robe::kDigits), dim3(robe::kSortBlock), 0, stream>>>(sp);
+        if (int rc = check_launch("sort (offsets)")) return rc;
+        robe::sort_scatter_kernel<<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks, vs, kd, vd);
+        if (int rc = check_launch("sort (scatter)")) return rc;
+        uint32_t *t = ks; ks = kd; kd = t;
+        t = vs; vs = vd; vd = t;
+    }
+    *in_b = (passes & 1u) != 0;
+    return ROBE_OK;
+}
+
 struct BwdPlan {
     bool dedup;          // sort the tokens and combine identical ones
     bool regions;        // ... and then sort the blocks by destination region instead of using float atomics
@@ -352,6 +396,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
         (void)hipGetLastError();
         return pl;                                    // no device to ask: the caller cannot run the scatter either
     }
+    if (radix_sort_temp_bytes(n) > temp) temp = radix_sort_temp_bytes(n);      // room for either sort
     pl.dedup = true;
     size_t off = 0;
     pl.off_keys_in = off;  off = align_up(off + n * 4, 256);
@@ -429,7 +474,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     const robe::Params p = to_params(h);
     char *ws = static_cast<char *>(workspace);
     uint32_t *keys_in = reinterpret_cast<uint32_t *>(ws + pl.off_keys_in);
-    uint32_t *keys_out = reinterpret_cast<uint32_t *>(ws + pl.off_keys_out);
+    uint32_t *keys_out = reinterpret_cast<uint32_t *>(ws + pl.off_keys_out);    // the sorted pairs, after S2
     uint32_t *vals_in = reinterpret_cast<uint32_t *>(ws + pl.off_vals_in);
     uint32_t *vals_out = reinterpret_cast<uint32_t *>(ws + pl.off_vals_out);
     uint32_t *tok_bag = reinterpret_cast<uint32_t *>(ws + pl.off_tok_bag);
@@ -455,11 +500,23 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     else robe::token_keys_kernel<false, true><<<kgrid, kblock, 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
     if (int rc = check_launch("backward (keys)")) return rc;
 
-    // S2: sort (key, position) pairs by the top key_bits bits of the 31-bit key
-    size_t temp = pl.temp_bytes;
-    hipError_t st = rocprim::radix_sort_pairs<TokenSortConfig>(ws + pl.off_temp, temp, keys_in, keys_out, vals_in, vals_out,
-                                              (size_t)n, 31 - pl.key_bits, 31, stream);
-    if (st != hipSuccess) return fail(ROBE_EHIP, "backward (sort): %s", hipGetErrorString(st));
+    // S2: sort (key, value) pairs by the top key_bits bits of the 31-bit key
+    const char *which = getenv("ROBE_TUNE_SORT");
+    if (which && strcmp(which, "library") == 0) {
+        size_t temp = pl.temp_bytes;
+        hipError_t st = rocprim::radix_sort_pairs<TokenSortConfig>(ws + pl.off_temp, temp, keys_in, keys_out, vals_in, vals_out,
+                                                                   (size_t)n, 31 - pl.key_bits, 31, stream);
+        if (st != hipSuccess) return fail(ROBE_EHIP, "backward (sort): %s", hipGetErrorString(st));
+    } else {
+        bool in_b = false;
+        if (int rc = launch_radix_sort(keys_in, vals_in, keys_out, vals_out, n, 31 - pl.key_bits, 31, ws + pl.off_temp,
+                                       stream, &in_b))
+            return rc;
+        if (!in_b) {        // an even number of passes leaves the result in the first pair of buffers
+            keys_out = keys_in;
+            vals_out = vals_in;
+        }
+    }
 
     robe::Geom q;
     memset(&q, 0, sizeof(q));
@@ -753,6 +810,33 @@ int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const flo
     if (g_reproducible.load(std::memory_order_relaxed)) return fail_not_reproducible();
     return launch_mixed<true>(hash, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
                               grad_out, stream);
+}
+
+size_t robe_sort_workspace_bytes(uint64_t n)
+{
+    return align_up(radix_sort_temp_bytes(n), 256);
+}
+
+int robe_sort_pairs(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint32_t *vals_b, uint64_t n,
+                    uint32_t lo_bit, uint32_t hi_bit, void *workspace, size_t workspace_bytes, int *result_in_b,
+                    void *stream)
+{
+    if (result_in_b == nullptr) return fail(ROBE_EINVAL, "result_in_b is NULL");
+    *result_in_b = 0;
+    if (lo_bit > hi_bit || hi_bit > 32) return fail(ROBE_EINVAL, "need lo_bit <= hi_bit <= 32");
+    if (n >= 0xFFFFFFFFull) return fail(ROBE_EINVAL, "at most 2^32 - 2 pairs");
+    if (n == 0 || lo_bit == hi_bit) return ROBE_OK;
+    if (keys_a == nullptr || vals_a == nullptr || keys_b == nullptr || vals_b == nullptr)
+        return fail(ROBE_EINVAL, "a key or value buffer is NULL");
+    if (workspace == nullptr || workspace_bytes < radix_sort_temp_bytes(n))
+        return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", radix_sort_temp_bytes(n), workspace_bytes);
+    if (!aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
+    bool in_b = false;
+    if (int rc = launch_radix_sort(keys_a, vals_a, keys_b, vals_b, (uint32_t)n, lo_bit, hi_bit, workspace,
+                                   (hipStream_t)stream, &in_b))
+        return rc;
+    *result_in_b = in_b ? 1 : 0;
+    return ROBE_OK;
 }
 
 int robe_set_reproducible(int on)

@@ -1,0 +1,234 @@
+// Stable LSD radix sort of (key, value) pairs of 32-bit words on a range of key bits, for the token
+// sort of the backward pass (S2 in robe_backward_dedup.h).
+//
+// Eight bits per pass, four kernels per pass, no kernel ever waits for another workgroup:
+//
+//   count    a workgroup takes a tile of kSortTile pairs, counts the digits of its keys in LDS and
+//            writes the counts to tile_count[digit][tile].
+//   totals   one workgroup per digit sums the digit's row of tile counts.
+//   offsets  one workgroup per digit: where the digit starts (totals of the smaller digits) and an
+//            exclusive prefix over that digit's row of tile counts - the first output slot of every
+//            (digit, tile).
+//   scatter  a workgroup takes its tile again, ranks every pair among the tile's pairs of the same
+//            digit in input order (so the sort is stable), puts the tile into LDS in digit order and
+//            writes it out from there, a digit's pairs to consecutive slots.
+//
+// Inside a tile, wavefront w owns pairs [w * 1024, (w + 1) * 1024) and walks them 64 at a time, so the
+// input order is (wavefront, round, lane): a pair's rank is what earlier rounds of its wavefront
+// counted for the digit, plus the lanes below it in its own round with the same digit (found with one
+// ballot per digit bit), plus what the wavefronts before it hold.
+//
+// The device library's radix sort does the same job; it is kept as an alternative.  This one is
+// shorter on launches and fill operations for the sizes met here (10^5 .. 10^7 pairs) and records
+// nothing but kernels on the stream.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace robe {
+
+constexpr int kSortBlock = 256;                       // 4 wavefronts
+constexpr int kSortRounds = 16;                       // 64 pairs per wavefront and round
+constexpr uint32_t kSortTile = kSortBlock * kSortRounds;   // 4096 pairs
+constexpr uint32_t kDigits = 256;
+static_assert(kSortBlock == (int)kDigits, "one thread per digit in the per-digit steps");
+
+struct SortPass {
+    uint32_t shift;      // first key bit of this pass's digit
+    uint32_t mask;       // (1 << bits) - 1, bits <= 8
+    uint32_t n;          // pairs
+    uint32_t tiles;      // ceil(n / kSortTile)
+    uint32_t *tile_count;   // [kDigits][tiles]: counts, then first output slots
+    uint32_t *totals;       // [kDigits]
+};
+
+__global__ __launch_bounds__(kSortBlock) void sort_count_kernel(SortPass s, const uint32_t *__restrict__ keys)
+{
+    __shared__ uint32_t h[kDigits];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t tile = blockIdx.x;
+    const uint64_t base = (uint64_t)tile * kSortTile;
+    uint32_t k[kSortRounds];
+#pragma unroll
+    for (int i = 0; i < kSortRounds; ++i) {
+        const uint64_t at = base + (uint32_t)i * kSortBlock + threadIdx.x;
+        k[i] = at < s.n ? keys[at] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kSortRounds; ++i) {
+        const uint64_t at = base + (uint32_t)i * kSortBlock + threadIdx.x;
+        if (at < s.n) atomicAdd(&h[(k[i] >> s.shift) & s.mask], 1u);
+    }
+    __syncthreads();
+    s.tile_count[(uint64_t)threadIdx.x * s.tiles + tile] = h[threadIdx.x];
+}
+
+// One workgroup per digit: the digit's total over all tiles.  (Adding the tile counts to the totals
+// with atomics in the count kernel would put thousands of them on each of 256 addresses.)
+__global__ __launch_bounds__(kSortBlock) void sort_totals_kernel(SortPass s)
+{
+    __shared__ uint32_t part[kSortBlock];
+    const uint32_t *row = s.tile_count + (uint64_t)blockIdx.x * s.tiles;
+    uint32_t sum = 0;
+    for (uint32_t i = threadIdx.x; i < s.tiles; i += kSortBlock) sum += row[i];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (uint32_t off = kSortBlock / 2; off > 0; off >>= 1) {
+        if (threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) s.totals[blockIdx.x] = part[0];
+}
+
+// One workgroup per digit.
+constexpr int kOffsetItems = 8;   // tile counts per thread and step
+
+__global__ __launch_bounds__(kSortBlock) void sort_offsets_kernel(SortPass s)
+{
+    __shared__ uint32_t part[kSortBlock];
+    __shared__ uint32_t wave_total[4];
+    const uint32_t digit = blockIdx.x, t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    // where this digit starts: the totals of the smaller digits
+    part[t] = t < digit ? s.totals[t] : 0u;
+    __syncthreads();
+    for (uint32_t off = kSortBlock / 2; off > 0; off >>= 1) {
+        if (t < off) part[t] += part[t + off];
+        __syncthreads();
+    }
+    uint32_t carry = part[0];     // the same in every thread
+    // exclusive prefix over the digit's row of tile counts
+    uint32_t *row = s.tile_count + (uint64_t)digit * s.tiles;
+    for (uint32_t t0 = 0; t0 < s.tiles; t0 += kSortBlock * kOffsetItems) {     // same trip count for the whole workgroup
+        uint32_t c[kOffsetItems], sum = 0;
+#pragma unroll
+        for (int k = 0; k < kOffsetItems; ++k) {
+            const uint32_t i = t0 + t * kOffsetItems + (uint32_t)k;
+            c[k] = i < s.tiles ? row[i] : 0u;
+            sum += c[k];
+        }
+        uint32_t incl = sum;
+#pragma unroll
+        for (uint32_t off = 1; off < 64u; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        __syncthreads();                       // the previous step's reads of wave_total are over
+        if (lane == 63u) wave_total[wave] = incl;
+        __syncthreads();
+        uint32_t before = carry, total = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < 4u; ++w) {
+            const uint32_t x = wave_total[w];
+            before += w < wave ? x : 0u;
+            total += x;
+        }
+        uint32_t a = before + incl - sum;
+#pragma unroll
+        for (int k = 0; k < kOffsetItems; ++k) {
+            const uint32_t i = t0 + t * kOffsetItems + (uint32_t)k;
+            if (i < s.tiles) row[i] = a;
+            a += c[k];
+        }
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(SortPass s, const uint32_t *__restrict__ keys_in,
+                                                                  const uint32_t *__restrict__ vals_in,
+                                                                  uint32_t *__restrict__ keys_out,
+                                                                  uint32_t *__restrict__ vals_out)
+{
+    __shared__ uint32_t wave_count[4][kDigits];   // per wavefront: pairs of each digit so far; later: its base in the tile
+    __shared__ uint32_t digit_start[kDigits];     // first tile-local slot of each digit
+    __shared__ uint32_t digit_slot[kDigits];      // first output slot of this tile's pairs of each digit
+    __shared__ uint2 staged[kSortTile];           // the tile in digit order
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t tile = blockIdx.x;
+    const uint64_t base = (uint64_t)tile * kSortTile + (uint64_t)wave * (kSortRounds * 64u);
+    for (uint32_t d = t; d < 4u * kDigits; d += kSortBlock) (&wave_count[0][0])[d] = 0;
+    digit_slot[t] = s.tile_count[(uint64_t)t * s.tiles + tile];
+    __syncthreads();
+
+    uint32_t key[kSortRounds], val[kSortRounds], rank[kSortRounds];
+#pragma unroll
+    for (int i = 0; i < kSortRounds; ++i) {
+        const uint64_t at = base + (uint32_t)i * 64u + lane;
+        key[i] = at < s.n ? keys_in[at] : 0xFFFFFFFFu;
+        val[i] = at < s.n ? vals_in[at] : 0u;
+    }
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < kSortRounds; ++i) {
+        const uint64_t at = base + (uint32_t)i * 64u + lane;
+        const bool have = at < s.n;
+        const uint32_t digit = (key[i] >> s.shift) & s.mask;
+        // the lanes of this round that hold the same digit
+        uint64_t same = __ballot(have);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t bit = __ballot((digit >> b) & 1u);
+            same &= ((digit >> b) & 1u) ? bit : ~bit;
+        }
+        const uint32_t so_far = wave_count[wave][digit];        // every lane reads before the first lane of a set adds
+        rank[i] = so_far + (uint32_t)__popcll(same & below);
+        __builtin_amdgcn_wave_barrier();
+        if (have && (same & below) == 0) wave_count[wave][digit] = so_far + (uint32_t)__popcll(same);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    // per digit: the tile's count, every wavefront's base inside the digit, the digit's first slot
+    {
+        uint32_t a = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t c = wave_count[w][t];
+            wave_count[w][t] = a;
+            a += c;
+        }
+        digit_start[t] = a;              // count for now
+    }
+    __syncthreads();
+    {   // exclusive scan of the 256 digit counts
+        const uint32_t c = digit_start[t];
+        uint32_t incl = c;
+#pragma unroll
+        for (uint32_t off = 1; off < 64u; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        __shared__ uint32_t wave_total[4];
+        if (lane == 63u) wave_total[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < 4u; ++w) before += w < wave ? wave_total[w] : 0u;
+        digit_start[t] = before + incl - c;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortRounds; ++i) {
+        const uint64_t at = base + (uint32_t)i * 64u + lane;
+        if (at < s.n) {
+            const uint32_t digit = (key[i] >> s.shift) & s.mask;
+            staged[digit_start[digit] + wave_count[wave][digit] + rank[i]] = make_uint2(key[i], val[i]);
+        }
+    }
+    __syncthreads();
+    const uint64_t tile_base = (uint64_t)tile * kSortTile;
+    const uint32_t in_tile = s.n - tile_base < kSortTile ? (uint32_t)(s.n - tile_base) : kSortTile;
+#pragma unroll
+    for (int i = 0; i < kSortRounds; ++i) {
+        const uint32_t j = (uint32_t)i * kSortBlock + t;
+        if (j < in_tile) {
+            const uint2 kv = staged[j];
+            const uint32_t digit = (kv.x >> s.shift) & s.mask;
+            const uint32_t slot = digit_slot[digit] + (j - digit_start[digit]);
+            keys_out[slot] = kv.x;
+            vals_out[slot] = kv.y;
+        }
+    }
+}
+
+}  // namespace robe

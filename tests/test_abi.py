@@ -106,6 +106,13 @@ def test_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.robe_forward_bf16(ref, None, None, None, 0, 0, 2, None, None) == robe.ROBE_OK
     assert L.robe_array_to_bf16(None, fake, 8, None) == EINVAL
     assert L.robe_array_to_bf16(None, None, 0, None) == robe.ROBE_OK
+    # the sort primitive
+    flag = ctypes.c_int(7)
+    assert L.robe_sort_pairs(fake, fake, fake, fake, 10, 9, 8, fake, 1 << 20, ctypes.byref(flag), None) == EINVAL
+    assert L.robe_sort_pairs(fake, fake, fake, fake, 10, 0, 8, None, 0, ctypes.byref(flag), None) == EINVAL
+    assert L.robe_sort_pairs(fake, fake, fake, fake, 10, 0, 8, fake, 1 << 20, None, None) == EINVAL
+    assert L.robe_sort_pairs(None, None, None, None, 0, 0, 8, None, 0, ctypes.byref(flag), None) == robe.ROBE_OK and flag.value == 0
+    assert L.robe_sort_workspace_bytes(8_500_000) >= 256 * 4 * (8_500_000 // 4096)
     # the reproducibility switch is plain host state: returns the previous setting
     assert L.robe_set_reproducible(1) == 0
     assert L.robe_set_reproducible(0) == 1
