@@ -403,7 +403,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     pl.off_keys_out = off; off = align_up(off + n * 4, 256);
     pl.off_vals_in = off;  off = align_up(off + n * 4, 256);
     pl.off_vals_out = off; off = align_up(off + n * 4, 256);
-    pl.off_tok_bag = off;  if (bags) off = align_up(off + n * 4, 256);
+    pl.off_tok_bag = off;  if (bags && h->use_sign) off = align_up(off + n * 4, 256);   // sign off: the sorted value is the row
     pl.off_temp = off;     off = align_up(off + temp, 256);
     pl.temp_bytes = temp;
     pl.bytes = off;
