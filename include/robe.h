@@ -145,9 +145,9 @@ size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_fe
  * with no float atomic at all.  The sorted paths need the workspace and rows,
  * n_indices below 2^31 - 1.  With a CSR that is not non-decreasing, bag bounds
  * are clamped to [0, n_indices] so nothing outside the buffers is touched, but
- * which tokens such bags hold is unspecified here.  The sort step records
- * memset nodes on the stream, so a large robe_backward should not be captured
- * into a HIP graph.
+ * which tokens such bags hold is unspecified here.  Every route records kernels
+ * only on the stream (no fill or copy operations, no synchronisation), so the
+ * call may be captured into a HIP graph.
  *   workspace  device buffer of at least robe_workspace_bytes(...) bytes,
  *              256-byte aligned, contents undefined before and after; may be
  *              NULL when that size is 0
@@ -197,7 +197,7 @@ int robe_sgd_update(const robe_hash_t *hash, float *array, float *grad_array, fl
  *                  records; for problems too small or shapes too odd for the sorted path it holds
  *                  a gradient array instead and the two steps run one after the other)
  * Errors: ROBE_EINVAL (null pointers, eps <= 0, non-finite lr/eps, workspace too small), ROBE_EHIP.
- * Like robe_backward it should not be captured into a HIP graph.
+ * Like robe_backward it records kernels only and may be captured into a HIP graph.
  */
 size_t robe_fused_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices);
 int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,

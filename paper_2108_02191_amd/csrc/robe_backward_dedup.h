@@ -9,7 +9,7 @@
 //   S1 keys     every token gets the key th = (Bh*x + Ah*e + Dh) mod P - the token
 //               part of its offset hash, equal for equal (e, x) - and a value: its
 //               row of grad_out when the sign is off, its position when it is on.
-//   S2 sort     radix sort of (key, value) pairs (rocPRIM device primitive).
+//   S2 sort     stable radix sort of (key, value) pairs (robe_radix_sort.h, or the device library's).
 //   S3 combine  a group of G lanes walks G consecutive sorted tokens, adds the
 //               gradient rows of runs of identical tokens in registers, and issues
 //               the d atomics once per run.  A run longer than a group's walk (kWalk
