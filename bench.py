@@ -409,7 +409,8 @@ def main():
     for name in ("fwd", "bwd", "adagrad", "sgd", "bwd_adagrad"):
         if avg[name] > 0:
             gbs = alg[name] / (avg[name] * 1e-3) / 1e9
-            kernels[name] = {"ms": round(avg[name], 4), "algorithmic_GB": round(alg[name] / 1e9, 4),
+            kernels[name] = {"ms": round(avg[name], 4), "ms_median": round(float(np.median(k_ms[name])), 4),
+                             "ms_min": round(min(k_ms[name]), 4), "algorithmic_GB": round(alg[name] / 1e9, 4),
                              "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
                              "frac_of_device_copy": round(gbs / copy_gbs, 4)}
     in_step = [n for n in kernels if not (fused and n in ("bwd", "adagrad"))]

@@ -441,6 +441,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     // measured: it pays below about eight regions per workgroup slot (1024 slots), and in the
     // reproducible mode, whose rounds are longer
     r.fullest_first = (NR <= 8192 || g_reproducible.load(std::memory_order_relaxed)) ? 1u : 0u;
+    r.keep_rows = bags ? 1u : 0u;
     pl.spill_rows = (uint64_t)(512u / lg) * h->Z <= robe::kSpillFloats;
     pl.off_head = off;    off = align_up(off + n, 256);
     pl.off_src_row = off; off = align_up(off + n * 4, 256);

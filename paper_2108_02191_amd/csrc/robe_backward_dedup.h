@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
             }
             float v[kRowsInFlight][V];
 #pragma unroll
-            for (int u = 0; u < kRowsInFlight; ++u) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+            for (int u = 0; u < kRowsInFlight; ++u) load_row<V, false, BAGS>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
 #pragma unroll
             for (int u = 0; u < kRowsInFlight; ++u) {
                 if (!ok[u]) continue;

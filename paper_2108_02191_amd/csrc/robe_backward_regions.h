@@ -57,6 +57,7 @@ struct RegionPlan {
     uint32_t pos_per_block;  // sorted positions per workgroup in R2 / R4
     uint32_t lg_shift;       // log2 of the lanes per record in R5
     uint32_t fullest_first;  // 1: R5 takes the regions by descending size class instead of by address
+    uint32_t keep_rows;      // 1: gradient rows are read more than once (bags): R5 loads them with the default cache policy
     const uint32_t *keys;    // sorted keys
     uint8_t *head;           // [n]  1: a run starts here
     uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
             float v[kRowsAhead][V];
 #pragma unroll
             for (int u = 0; u < kRowsAhead; ++u) {
-                if (use[u]) load_row<V, false>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+                if (use[u]) load_row<V, false, BAGS>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
             }
 #pragma unroll
             for (int u = 0; u < kRowsAhead; ++u) {
@@ -651,7 +652,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                 for (int u = 0; u < kRecAhead; ++u) {
                     const float *base = src[u] < src_own ? grad_out + (uint64_t)src[u] * p.Z
                                                          : s.P + (uint64_t)(src[u] - src_own) * p.Z;
-                    v[u] = __builtin_nontemporal_load(base + j);
+                    v[u] = s.keep_rows ? base[j] : __builtin_nontemporal_load(base + j);
                 }
 #pragma unroll
                 for (int u = 0; u < kRecAhead; ++u) {

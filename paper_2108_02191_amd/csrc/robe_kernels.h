@@ -232,16 +232,22 @@ __device__ __forceinline__ void store_row(float *__restrict__ row, const Geom &q
     }
 }
 
-template <int V, bool CONSEC>
+// KEEP: the row will be read again soon (the tokens of a bag all read the bag's row), so it is loaded
+// with the default cache policy; otherwise it is streamed past the caches' resident lines.
+template <int V, bool CONSEC, bool KEEP = false>
 __device__ __forceinline__ void load_row(const float *__restrict__ row, const Geom &q, uint32_t grp, float (&v)[V])
 {
     if constexpr (CONSEC) {
-        const typename Vec<V>::A a = __builtin_nontemporal_load(reinterpret_cast<const typename Vec<V>::A *>(row + grp * V));
+        const typename Vec<V>::A *at = reinterpret_cast<const typename Vec<V>::A *>(row + grp * V);
+        const typename Vec<V>::A a = KEEP ? *at : __builtin_nontemporal_load(at);
 #pragma unroll
         for (int k = 0; k < V; ++k) v[k] = a[k];
     } else {
 #pragma unroll
-        for (int k = 0; k < V; ++k) v[k] = __builtin_nontemporal_load(row + grp + (uint32_t)k * q.G);
+        for (int k = 0; k < V; ++k) {
+            const float *at = row + grp + (uint32_t)k * q.G;
+            v[k] = KEEP ? *at : __builtin_nontemporal_load(at);
+        }
     }
 }
 
