@@ -855,12 +855,16 @@ static int launch_update(int rule, const robe_hash_t *hash, float *array, float 
     if (work < 1) work = 1;
     const uint64_t blocks = (work + robe::kBlock - 1) / robe::kBlock;   // <= 2^23 since m < 2^31
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
+    // An array of up to 128 MiB written with the default cache policy is still in the 256 MB last-level
+    // cache when the next forward pass gathers from it (measured on the 100 MB array: forward 0.29 ->
+    // 0.24 ms; no gain from 160 MB on, a loss from 400 MB on).
+    const bool keep = m <= (1ull << 25);
     if (rule == 0) {
-        if (vec) robe::update_kernel<4, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps);
-        else robe::update_kernel<1, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps);
+        if (vec) robe::update_kernel<4, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep);
+        else robe::update_kernel<1, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep);
     } else {
-        if (vec) robe::update_kernel<4, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f);
-        else robe::update_kernel<1, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f);
+        if (vec) robe::update_kernel<4, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f, keep);
+        else robe::update_kernel<1, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f, keep);
     }
     return check_launch(rule == 0 ? "adagrad" : "sgd");
 }

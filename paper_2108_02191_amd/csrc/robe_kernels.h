@@ -642,7 +642,9 @@ __device__ __forceinline__ void adagrad_one(float &w, float &s, float g, float l
 
 // One thread per vector of V slots, no loop: measured fastest on MI355X (deeper per-thread
 // unrolling lost to register pressure); streaming loads and stores keep the three arrays from
-// displacing each other in the caches.  The skip decision is taken per aligned group of kLineLanes
+// displacing each other in the caches.  keep_array: the array is small enough to stay in the
+// last-level cache until the next forward pass reads it, so it alone is read and written with
+// the default cache policy.  The skip decision is taken per aligned group of kLineLanes
 // lanes (64 bytes when V = 4, the granule that measured best among 16..256 bytes): a granule is
 // either rewritten whole or not touched at all, because partially written granules cost the
 // memory system far more than the bytes they save.
@@ -651,7 +653,8 @@ constexpr uint32_t kLineLanes = 4;
 // RULE 0: Adagrad (array, state, grad).  RULE 1: SGD (array, grad; `state` and `eps` unused).
 template <int V, int RULE>
 __global__ __launch_bounds__(kBlock) void update_kernel(float *__restrict__ array, float *__restrict__ state,
-                                                        float *__restrict__ grad, uint64_t m, float lr, float eps)
+                                                        float *__restrict__ grad, uint64_t m, float lr, float eps,
+                                                        bool keep_array)
 {
     typedef typename Vec<V>::A VT;
     const uint64_t nvec = m / V;
@@ -667,7 +670,9 @@ __global__ __launch_bounds__(kBlock) void update_kernel(float *__restrict__ arra
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t line_any = (__ballot(any) >> (lane & ~(kLineLanes - 1u))) & ((1ull << kLineLanes) - 1ull);
     if (in_range && line_any != 0) {  // an untouched granule: nothing read beyond the gradient, nothing written
-        VT w = __builtin_nontemporal_load(reinterpret_cast<const VT *>(array + it * V));
+        VT w;
+        if (keep_array) w = *reinterpret_cast<const VT *>(array + it * V);
+        else w = __builtin_nontemporal_load(reinterpret_cast<const VT *>(array + it * V));
         VT s;
         if constexpr (RULE == 0) s = __builtin_nontemporal_load(reinterpret_cast<const VT *>(state + it * V));
 #pragma unroll
@@ -684,7 +689,8 @@ __global__ __launch_bounds__(kBlock) void update_kernel(float *__restrict__ arra
             }
             g[k] = 0.0f;
         }
-        __builtin_nontemporal_store(w, reinterpret_cast<VT *>(array + it * V));
+        if (keep_array) *reinterpret_cast<VT *>(array + it * V) = w;
+        else __builtin_nontemporal_store(w, reinterpret_cast<VT *>(array + it * V));
         if constexpr (RULE == 0) __builtin_nontemporal_store(s, reinterpret_cast<VT *>(state + it * V));
         __builtin_nontemporal_store(g, reinterpret_cast<VT *>(grad + it * V));
     }
