@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0: as defined)")
     ap.add_argument("--m", type=int, default=0, help="override the array length in floats (0: as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reproducible", action="store_true",
+                    help="time the step with robe_set_reproducible(1): region-sorted backward, canonical addition order")
     ap.add_argument("--unfused", action="store_true",
                     help="time robe_backward and robe_adagrad_update as separate calls inside the step "
                          "(default: the fused robe_backward_adagrad; the separate calls are then timed beside it)")
@@ -201,6 +203,8 @@ def main():
     out = torch.empty((B, sum(w.dims)) if mixed else (B, F, w.d), dtype=torch.float32, device=dev)
     ga = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_bwd else None
     st = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_ada else None
+    if args.reproducible:
+        robe.robe_set_reproducible(True)        # before the workspace sizes: the mode changes the route
     ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n) for n in tokens) if (do_bwd and w.dims is None) else 0
     fused = do_ada and not args.unfused
     fws_bytes = max(robe.robe_fused_workspace_bytes(h, B, F, n) for n in tokens) if fused else 0
@@ -456,7 +460,7 @@ def main():
                    "n_features": F, "rows": rows, "tokens_per_step": tok, "bag_mean": w.bag_mean,
                    "ids": f"{w.id_dist}({w.zipf_alpha})" if w.id_dist == "zipf" else w.id_dist,
                    "use_sign": w.use_sign, "phases": w.phases, "id_batches": len(batches),
-                   "touched_slots": touched},
+                   "touched_slots": touched, "reproducible_mode": bool(args.reproducible)},
         "effective_GBps_whole_step": total_alg / (ms_per_step * 1e-3) / 1e9,
         "effective_frac_of_hbm_peak": total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "device_copy_GBps": round(copy_gbs, 1),

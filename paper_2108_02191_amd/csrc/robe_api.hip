@@ -335,6 +335,11 @@ int launch_radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint
     return ROBE_OK;
 }
 
+// An array of up to 128 MiB written with the default cache policy is still in the 256 MB last-level
+// cache when the next forward pass gathers from it (measured on the 100 MB array: forward 0.29 ->
+// 0.24 ms; no gain from 160 MB on, a loss from 400 MB on).  Larger arrays are streamed.
+const uint64_t kKeepArrayMax = 1ull << 25;
+
 struct BwdPlan {
     bool dedup;          // sort the tokens and combine identical ones
     bool regions;        // ... and then sort the blocks by destination region instead of using float atomics
@@ -530,6 +535,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     if (pl.regions) {
         robe::RegionPlan r = pl.rp;
         r.keys = keys_out;
+        r.keep_array = (rule == 1 && h->m <= kKeepArrayMax) ? 1u : 0u;
         r.head = reinterpret_cast<uint8_t *>(ws + pl.off_head);
         r.src_row = reinterpret_cast<uint32_t *>(ws + pl.off_src_row);
         r.run_tg = reinterpret_cast<uint32_t *>(ws + pl.off_run_tg);
@@ -855,10 +861,7 @@ static int launch_update(int rule, const robe_hash_t *hash, float *array, float 
     if (work < 1) work = 1;
     const uint64_t blocks = (work + robe::kBlock - 1) / robe::kBlock;   // <= 2^23 since m < 2^31
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
-    // An array of up to 128 MiB written with the default cache policy is still in the 256 MB last-level
-    // cache when the next forward pass gathers from it (measured on the 100 MB array: forward 0.29 ->
-    // 0.24 ms; no gain from 160 MB on, a loss from 400 MB on).
-    const bool keep = m <= (1ull << 25);
+    const bool keep = m <= kKeepArrayMax;
     if (rule == 0) {
         if (vec) robe::update_kernel<4, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep);
         else robe::update_kernel<1, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep);

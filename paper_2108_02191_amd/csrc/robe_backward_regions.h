@@ -58,6 +58,7 @@ struct RegionPlan {
     uint32_t lg_shift;       // log2 of the lanes per record in R5
     uint32_t fullest_first;  // 1: R5 takes the regions by descending size class instead of by address
     uint32_t keep_rows;      // 1: gradient rows are read more than once (bags): R5 loads them with the default cache policy
+    uint32_t keep_array;     // 1: R5 with the Adagrad rule leaves the array in the caches for the next forward pass (small arrays)
     const uint32_t *keys;    // sorted keys
     uint8_t *head;           // [n]  1: a run starts here
     uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
@@ -718,7 +719,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
         for (int u = 0; u < kWb; ++u) {
             if (touch[u]) {
                 const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
-                w[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
+                if (RULE == 1 && s.keep_array) w[u] = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
+                else w[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
                 if constexpr (RULE == 1) st[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(state + r0 + 4u * it));
             }
         }
@@ -739,7 +741,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                         st[u][k] = sk;
                     }
                 }
-                __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+                if (s.keep_array) *reinterpret_cast<V4 *>(dst + r0 + 4u * it) = w[u];
+                else __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
                 __builtin_nontemporal_store(st[u], reinterpret_cast<V4 *>(state + r0 + 4u * it));
             }
         }
