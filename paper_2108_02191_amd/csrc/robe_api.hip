@@ -123,7 +123,7 @@ bool tuned_layout(const char *var, const robe_hash_t *h, Layout *out)
     int V = 0, consec = 0;
     if (sscanf(s, "%d,%d", &V, &consec) != 2) return false;
     if (V == 0) { *out = {0, false, 0}; return true; }
-    if (V != 1 && V != 2 && V != 4) return false;
+    if (V != 1 && V != 2 && V != 4 && (consec || (V != 3 && V != 6 && V != 8))) return false;
     if (h->d % V) return false;
     const uint32_t G = h->d / V;
     if (!is_pow2(G) || G > 64) return false;
@@ -149,8 +149,9 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
             if (is_pow2(G) && G <= 64 && aligned(rows_ptr, 4 * (size_t)V)) return {V, true, G};
         }
     }
-    // backward (and forward when Z is too small): lanes of a group on consecutive addresses
-    for (int V : {1, 2, 4}) {
+    // backward (and forward when Z is too small): lanes of a group on consecutive addresses.  Three, six
+    // or eight elements per lane cover d = 3 * 2^k (24 .. 192), 384 and 512; four-byte accesses only.
+    for (int V : {1, 2, 3, 4, 6, 8}) {
         if (h->d % V) continue;
         const uint32_t G = h->d / V;
         if (is_pow2(G) && G <= 64) return {V, false, G};
@@ -266,17 +267,30 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
             switch (lay.V) {
                 case 1: ROBE_LAUNCH_TILE(1); break;
                 case 2: ROBE_LAUNCH_TILE(2); break;
+                case 3: ROBE_LAUNCH_TILE(3); break;
+                case 6: ROBE_LAUNCH_TILE(6); break;
+                case 8: ROBE_LAUNCH_TILE(8); break;
                 default: ROBE_LAUNCH_TILE(4); break;
             }
             return check_launch("backward (tiles)");
         }
     }
 #undef ROBE_LAUNCH_TILE
+    // three, six and eight elements per lane exist in the strided layout only
+#define ROBE_LAUNCH_S(V_)                                            \
+    do {                                                             \
+        if (sign) ROBE_LAUNCH(V_, false, true);                      \
+        else ROBE_LAUNCH(V_, false, false);                          \
+    } while (0)
     switch (lay.V) {
         case 1: ROBE_LAUNCH_CS(1); break;
         case 2: ROBE_LAUNCH_CS(2); break;
+        case 3: ROBE_LAUNCH_S(3); break;
+        case 6: ROBE_LAUNCH_S(6); break;
+        case 8: ROBE_LAUNCH_S(8); break;
         default: ROBE_LAUNCH_CS(4); break;
     }
+#undef ROBE_LAUNCH_S
 #undef ROBE_LAUNCH_CS
 #undef ROBE_LAUNCH
     return check_launch(BWD ? "backward" : "forward");
@@ -558,6 +572,9 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
         switch (pl.lay.V) {
             case 1: ROBE_COMBINE_ROWS(1); break;
             case 2: ROBE_COMBINE_ROWS(2); break;
+            case 3: ROBE_COMBINE_ROWS(3); break;
+            case 6: ROBE_COMBINE_ROWS(6); break;
+            case 8: ROBE_COMBINE_ROWS(8); break;
             default: ROBE_COMBINE_ROWS(4); break;
         }
 #undef ROBE_COMBINE_ROWS
@@ -619,6 +636,9 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     switch (pl.lay.V) {
         case 1: ROBE_COMBINE(1); break;
         case 2: ROBE_COMBINE(2); break;
+        case 3: ROBE_COMBINE(3); break;
+        case 6: ROBE_COMBINE(6); break;
+        case 8: ROBE_COMBINE(8); break;
         default: ROBE_COMBINE(4); break;
     }
 #undef ROBE_COMBINE

@@ -25,7 +25,7 @@ def dev(a):
 
 
 def draw_case(rng):
-    kind = rng.integers(0, 4)
+    kind = rng.integers(0, 5)
     if kind == 0:       # power-of-two shapes: the tiled kernels
         d = int(2 ** rng.integers(0, 9))
         Z = int(2 ** rng.integers(0, int(np.log2(d)) + 1))
@@ -35,6 +35,10 @@ def draw_case(rng):
     elif kind == 2:     # Z > d
         d = int(rng.integers(1, 17))
         Z = d * int(rng.integers(2, 9))
+    elif kind == 3:     # three, six or eight elements per lane
+        d = int(rng.choice([24, 48, 96, 192, 384, 512]))
+        divs = [z for z in range(1, d + 1) if d % z == 0]
+        Z = int(rng.choice(divs))
     else:               # the benchmark's shape family
         d, Z = 128, int(rng.choice([1, 8, 32, 128]))
     m = int(rng.choice([Z, Z + 1, 2 * Z + 3, 1000 + Z, 65_537 + Z, 1_000_003 + Z]))
