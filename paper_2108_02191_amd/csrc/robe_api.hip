@@ -156,7 +156,16 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
         const uint32_t G = h->d / V;
         if (is_pow2(G) && G <= 64) return {V, false, G};
     }
-    return {0, false, 0};
+    // Any other d up to 512: the smallest G * V >= d, the lane slots past d idle (d = 100: 2 x 64)
+    Layout best = {0, false, 0};
+    for (int V : {1, 2, 3, 4, 6, 8}) {
+        for (uint32_t G = 1; G <= 64; G <<= 1) {
+            if ((uint64_t)G * V < h->d) continue;
+            if (best.V == 0 || G * V < best.G * best.V || (G * V == best.G * (uint32_t)best.V && G > best.G)) best = {V, false, G};
+            break;
+        }
+    }
+    return best;
 }
 
 int env_int(const char *name, int dflt)
@@ -184,6 +193,7 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
     robe::Geom q;
     memset(&q, 0, sizeof(q));
     q.F = F;
+    q.d = h->d;
     q.batch = rows / (int64_t)F;
     q.F_in = view ? view->F_in : F;
     q.e0 = view ? view->e0 : 0u;
@@ -541,6 +551,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     robe::Geom q;
     memset(&q, 0, sizeof(q));
     q.F = F;
+    q.d = h->d;
     q.G = pl.lay.G;
     q.g_shift = log2u(pl.lay.G);
     const uint64_t blocks = ((uint64_t)n + robe::kBlock - 1) / robe::kBlock;   // one lane per sorted position

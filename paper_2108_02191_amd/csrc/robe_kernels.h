@@ -30,7 +30,8 @@ constexpr int kUnroll = 4;            // tokens in flight per lane group
 // Launch geometry, filled on the host.
 struct Geom {
     uint32_t F;        // number of tables (features)
-    uint32_t G;        // lanes per row, power of two, <= 64; d = G * V
+    uint32_t G;        // lanes per row, power of two, <= 64; G * V >= d
+    uint32_t d;        // elements per row; in the strided layout lane slots grp + k * G past it stay idle
     uint32_t g_shift;  // log2(G)
     uint32_t TL;       // rows per wavefront tile (single-hot kernels), multiple of 64/G, <= 64 (0: unused)
     uint32_t bpx;      // workgroups per XCD when rows are walked table by table (0: walk rows in memory order)
@@ -139,15 +140,20 @@ struct Lane {
     uint32_t cc[NH];                             // (Ch * c) mod P
     uint32_t jj[NH];                             // position inside the chunk
     uint32_t cg[SIGN ? V : 1];                   // (Cg * i) mod P per owned element
+    uint32_t live;                               // bit k: owned element k exists (strided layout with G * V > d)
+
+    __device__ __forceinline__ bool has(int k) const { return CONSEC || ((live >> k) & 1u) != 0u; }
 
     __device__ __forceinline__ void init(const Params &p, const Geom &q, uint32_t grp)
     {
+        live = 0;
 #pragma unroll
         for (int k = 0; k < NH; ++k) {
             const uint32_t i = CONSEC ? grp * V : grp + (uint32_t)k * q.G;
             const uint32_t c = i / p.Z;
             jj[k] = i - c * p.Z;
             cc[k] = mod_p((uint64_t)p.Ch * c);
+            if (!CONSEC && i < q.d) live |= 1u << k;
         }
         if constexpr (SIGN) {
 #pragma unroll
@@ -194,7 +200,7 @@ struct Lane {
             }
         } else {
 #pragma unroll
-            for (int k = 0; k < V; ++k) v[k] = widen(array[position(p, th, k, place)]);
+            for (int k = 0; k < V; ++k) v[k] = widen(array[position(p, th, k, place)]);   // idle slots read some valid slot
         }
         if constexpr (SIGN) {
 #pragma unroll
@@ -210,6 +216,7 @@ struct Lane {
 #pragma unroll
         for (int k = 0; k < V; ++k) {
             // CONSEC: every element wraps on its own
+            if (!has(k)) continue;
             const uint32_t pos = CONSEC ? wrap(pos0 + (uint32_t)k, p.m) : position(p, th, k, place);
             const float val = SIGN ? apply_sign(v[k], mask(tg, k)) : v[k];
             __hip_atomic_fetch_add(grad_array + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -228,7 +235,8 @@ __device__ __forceinline__ void store_row(float *__restrict__ row, const Geom &q
         __builtin_nontemporal_store(a, reinterpret_cast<typename Vec<V>::A *>(row + grp * V));
     } else {
 #pragma unroll
-        for (int k = 0; k < V; ++k) __builtin_nontemporal_store(v[k], row + grp + (uint32_t)k * q.G);
+        for (int k = 0; k < V; ++k)
+            if (grp + (uint32_t)k * q.G < q.d) __builtin_nontemporal_store(v[k], row + grp + (uint32_t)k * q.G);
     }
 }
 
@@ -245,7 +253,8 @@ __device__ __forceinline__ void load_row(const float *__restrict__ row, const Ge
     } else {
 #pragma unroll
         for (int k = 0; k < V; ++k) {
-            const float *at = row + grp + (uint32_t)k * q.G;
+            const uint32_t i = grp + (uint32_t)k * q.G;
+            const float *at = row + (i < q.d ? i : 0u);       // idle slots read element 0; nobody stores their value
             v[k] = KEEP ? *at : __builtin_nontemporal_load(at);
         }
     }

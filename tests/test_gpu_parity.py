@@ -57,13 +57,14 @@ def random_bags(rng, rows, card, mean, long_bag=0):
 
 
 # (m, d, Z): every lane layout (1/2/4 elements per lane, consecutive and strided; 3/6/8 strided: d = 6,
-# 12, 24, 48, 96, 192, 384, 512), the shape-generic kernel, arrays small enough that blocks wrap, Z = m,
-# Z = 1, Z = d, Z > d.
+# 12, 24, 48, 96, 192, 384, 512; lane groups wider than the row: d = 5, 100), the shape-generic kernel
+# (d > 512), arrays small enough that blocks wrap, Z = m, Z = 1, Z = d, Z > d.
 SHAPES = [
     (2**20, 16, 4), (1_000_003, 128, 32), (999_983, 128, 8), (500_000, 128, 128), (300_007, 128, 1),
     (37, 16, 8), (16, 16, 16), (64, 64, 64), (101, 8, 2), (50, 4, 1), (1000, 6, 2),
     (70_001, 96, 32), (4099, 12, 3), (9973, 256, 32), (100_000, 512, 128), (5, 5, 5), (1, 1, 1),
     (50_021, 384, 64), (33_331, 192, 48), (20_011, 48, 16), (9001, 24, 24), (777, 512, 1), (100_003, 100, 10),
+    (60_013, 120, 40), (30_011, 80, 80), (200_003, 640, 64), (5003, 513, 27),
     (1000, 4, 16), (37, 4, 16), (32, 8, 32), (100_003, 16, 64), (4099, 8, 24), (250_007, 128, 512),   # Z > d
     (2**31 - 1, 32, 16),
 ]

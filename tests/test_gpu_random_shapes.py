@@ -29,9 +29,9 @@ def draw_case(rng):
     if kind == 0:       # power-of-two shapes: the tiled kernels
         d = int(2 ** rng.integers(0, 9))
         Z = int(2 ** rng.integers(0, int(np.log2(d)) + 1))
-    elif kind == 1:     # arbitrary divisors: the shape-generic kernel
+    elif kind == 1:     # arbitrary divisors: lane groups wider than the row; beyond d = 512 the shape-generic kernel
         Z = int(rng.integers(1, 13))
-        d = Z * int(rng.integers(1, 9))
+        d = Z * int(rng.integers(1, 9)) * int(rng.choice([1, 1, 1, 7, 11]))
     elif kind == 2:     # Z > d
         d = int(rng.integers(1, 17))
         Z = d * int(rng.integers(2, 9))
