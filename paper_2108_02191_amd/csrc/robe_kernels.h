@@ -149,11 +149,14 @@ struct Lane {
         live = 0;
 #pragma unroll
         for (int k = 0; k < NH; ++k) {
-            const uint32_t i = CONSEC ? grp * V : grp + (uint32_t)k * q.G;
+            uint32_t i = CONSEC ? grp * V : grp + (uint32_t)k * q.G;
+            if (!CONSEC) {
+                if (i < q.d) live |= 1u << k;
+                else i = 0;       // an idle slot: it reads element 0's array slot (in bounds) and writes nothing
+            }
             const uint32_t c = i / p.Z;
             jj[k] = i - c * p.Z;
             cc[k] = mod_p((uint64_t)p.Ch * c);
-            if (!CONSEC && i < q.d) live |= 1u << k;
         }
         if constexpr (SIGN) {
 #pragma unroll
