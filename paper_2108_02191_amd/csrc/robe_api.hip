@@ -346,8 +346,6 @@ int launch_radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint
         sp.totals = totals + pass * robe::kDigits;
         robe::sort_count_kernel<<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks);
         if (int rc = check_launch("sort (count)")) return rc;
-        robe::sort_totals_kernel<<<dim3(robe::kDigits), dim3(robe::kSortBlock), 0, stream>>>(sp);
-        if (int rc = check_launch("sort (totals)")) return rc;
         robe::sort_offsets_kernel<<<dim3(robe::kDigits), dim3(robe::kSortBlock), 0, stream>>>(sp);
         if (int rc = check_launch("sort (offsets)")) return rc;
         robe::sort_scatter_kernel<<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks, vs, kd, vd);

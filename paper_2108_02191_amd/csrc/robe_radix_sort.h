@@ -1,17 +1,16 @@
 // Stable LSD radix sort of (key, value) pairs of 32-bit words on a range of key bits, for the token
 // sort of the backward pass (S2 in robe_backward_dedup.h).
 //
-// Eight bits per pass, four kernels per pass, no kernel ever waits for another workgroup:
+// Eight bits per pass, three kernels per pass, no kernel ever waits for another workgroup:
 //
 //   count    a workgroup takes a tile of kSortTile pairs, counts the digits of its keys in LDS and
 //            writes the counts to tile_count[digit][tile].
-//   totals   one workgroup per digit sums the digit's row of tile counts.
-//   offsets  one workgroup per digit: where the digit starts (totals of the smaller digits) and an
-//            exclusive prefix over that digit's row of tile counts - the first output slot of every
-//            (digit, tile).
-//   scatter  a workgroup takes its tile again, ranks every pair among the tile's pairs of the same
-//            digit in input order (so the sort is stable), puts the tile into LDS in digit order and
-//            writes it out from there, a digit's pairs to consecutive slots.
+//   offsets  one workgroup per digit: an exclusive prefix over that digit's row of tile counts -
+//            how many pairs of the digit the tiles before hold - and the digit's total.
+//   scatter  a workgroup takes its tile again, finds where every digit starts (an exclusive scan of
+//            the 256 totals), ranks every pair among the tile's pairs of the same digit in input
+//            order (so the sort is stable), puts the tile into LDS in digit order and writes it out
+//            from there, a digit's pairs to consecutive slots.
 //
 // Inside a tile, wavefront w owns pairs [w * 1024, (w + 1) * 1024) and walks them 64 at a time, so the
 // input order is (wavefront, round, lane): a pair's rank is what earlier rounds of its wavefront
@@ -38,8 +37,8 @@ struct SortPass {
     uint32_t mask;       // (1 << bits) - 1, bits <= 8
     uint32_t n;          // pairs
     uint32_t tiles;      // ceil(n / kSortTile)
-    uint32_t *tile_count;   // [kDigits][tiles]: counts, then first output slots
-    uint32_t *totals;       // [kDigits]
+    uint32_t *tile_count;   // [kDigits][tiles]: counts, then the digit's pairs in the tiles before
+    uint32_t *totals;       // [kDigits]: pairs of each digit
 };
 
 __global__ __launch_bounds__(kSortBlock) void sort_count_kernel(SortPass s, const uint32_t *__restrict__ keys)
@@ -64,21 +63,29 @@ __global__ __launch_bounds__(kSortBlock) void sort_count_kernel(SortPass s, cons
     s.tile_count[(uint64_t)threadIdx.x * s.tiles + tile] = h[threadIdx.x];
 }
 
-// One workgroup per digit: the digit's total over all tiles.  (Adding the tile counts to the totals
-// with atomics in the count kernel would put thousands of them on each of 256 addresses.)
-__global__ __launch_bounds__(kSortBlock) void sort_totals_kernel(SortPass s)
+// Exclusive prefix of one value per thread over the workgroup's 256 threads.  `wave_total` is LDS for
+// four words; the call ends with a barrier, so it may be reused right after.
+__device__ __forceinline__ uint32_t exclusive_scan_256(uint32_t v, uint32_t *wave_total, uint32_t &total)
 {
-    __shared__ uint32_t part[kSortBlock];
-    const uint32_t *row = s.tile_count + (uint64_t)blockIdx.x * s.tiles;
-    uint32_t sum = 0;
-    for (uint32_t i = threadIdx.x; i < s.tiles; i += kSortBlock) sum += row[i];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    for (uint32_t off = kSortBlock / 2; off > 0; off >>= 1) {
-        if (threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
-        __syncthreads();
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (uint32_t off = 1; off < 64u; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
     }
-    if (threadIdx.x == 0) s.totals[blockIdx.x] = part[0];
+    if (lane == 63u) wave_total[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    total = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < 4u; ++w) {
+        const uint32_t x = wave_total[w];
+        before += w < wave ? x : 0u;
+        total += x;
+    }
+    __syncthreads();
+    return before + incl - v;
 }
 
 // One workgroup per digit.
@@ -86,18 +93,9 @@ constexpr int kOffsetItems = 8;   // tile counts per thread and step
 
 __global__ __launch_bounds__(kSortBlock) void sort_offsets_kernel(SortPass s)
 {
-    __shared__ uint32_t part[kSortBlock];
     __shared__ uint32_t wave_total[4];
-    const uint32_t digit = blockIdx.x, t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    // where this digit starts: the totals of the smaller digits
-    part[t] = t < digit ? s.totals[t] : 0u;
-    __syncthreads();
-    for (uint32_t off = kSortBlock / 2; off > 0; off >>= 1) {
-        if (t < off) part[t] += part[t + off];
-        __syncthreads();
-    }
-    uint32_t carry = part[0];     // the same in every thread
-    // exclusive prefix over the digit's row of tile counts
+    const uint32_t digit = blockIdx.x, t = threadIdx.x;
+    uint32_t carry = 0;           // the same in every thread
     uint32_t *row = s.tile_count + (uint64_t)digit * s.tiles;
     for (uint32_t t0 = 0; t0 < s.tiles; t0 += kSortBlock * kOffsetItems) {     // same trip count for the whole workgroup
         uint32_t c[kOffsetItems], sum = 0;
@@ -107,23 +105,8 @@ __global__ __launch_bounds__(kSortBlock) void sort_offsets_kernel(SortPass s)
             c[k] = i < s.tiles ? row[i] : 0u;
             sum += c[k];
         }
-        uint32_t incl = sum;
-#pragma unroll
-        for (uint32_t off = 1; off < 64u; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
-        }
-        __syncthreads();                       // the previous step's reads of wave_total are over
-        if (lane == 63u) wave_total[wave] = incl;
-        __syncthreads();
-        uint32_t before = carry, total = 0;
-#pragma unroll
-        for (uint32_t w = 0; w < 4u; ++w) {
-            const uint32_t x = wave_total[w];
-            before += w < wave ? x : 0u;
-            total += x;
-        }
-        uint32_t a = before + incl - sum;
+        uint32_t total;
+        uint32_t a = carry + exclusive_scan_256(sum, wave_total, total);
 #pragma unroll
         for (int k = 0; k < kOffsetItems; ++k) {
             const uint32_t i = t0 + t * kOffsetItems + (uint32_t)k;
@@ -132,6 +115,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_offsets_kernel(SortPass s)
         }
         carry += total;
     }
+    if (t == 0) s.totals[digit] = carry;
 }
 
 __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(SortPass s, const uint32_t *__restrict__ keys_in,
@@ -146,8 +130,13 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(SortPass s, co
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x;
     const uint64_t base = (uint64_t)tile * kSortTile + (uint64_t)wave * (kSortRounds * 64u);
+    __shared__ uint32_t wave_total[4];
     for (uint32_t d = t; d < 4u * kDigits; d += kSortBlock) (&wave_count[0][0])[d] = 0;
-    digit_slot[t] = s.tile_count[(uint64_t)t * s.tiles + tile];
+    {   // a digit's pairs start after all pairs of the smaller digits, then after the digit's pairs in the tiles before
+        uint32_t all;
+        const uint32_t before_tiles = s.tile_count[(uint64_t)t * s.tiles + tile];
+        digit_slot[t] = exclusive_scan_256(s.totals[t], wave_total, all) + before_tiles;
+    }
     __syncthreads();
 
     uint32_t key[kSortRounds], val[kSortRounds], rank[kSortRounds];
@@ -191,20 +180,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(SortPass s, co
     }
     __syncthreads();
     {   // exclusive scan of the 256 digit counts
+        uint32_t all;
         const uint32_t c = digit_start[t];
-        uint32_t incl = c;
-#pragma unroll
-        for (uint32_t off = 1; off < 64u; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
-        }
-        __shared__ uint32_t wave_total[4];
-        if (lane == 63u) wave_total[wave] = incl;
-        __syncthreads();
-        uint32_t before = 0;
-#pragma unroll
-        for (uint32_t w = 0; w < 4u; ++w) before += w < wave ? wave_total[w] : 0u;
-        digit_start[t] = before + incl - c;
+        digit_start[t] = exclusive_scan_256(c, wave_total, all);
     }
     __syncthreads();
 #pragma unroll
