@@ -344,7 +344,8 @@ int launch_radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint
         const uint32_t bits = hi - sp.shift < 8 ? hi - sp.shift : 8;
         sp.mask = (1u << bits) - 1u;
         sp.totals = totals + pass * robe::kDigits;
-        robe::sort_count_kernel<<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks);
+        if (pass == 0) robe::sort_count_kernel<false><<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks);
+        else robe::sort_count_kernel<true><<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks);
         if (int rc = check_launch("sort (count)")) return rc;
         robe::sort_offsets_kernel<<<dim3(robe::kDigits), dim3(robe::kSortBlock), 0, stream>>>(sp);
         if (int rc = check_launch("sort (offsets)")) return rc;
