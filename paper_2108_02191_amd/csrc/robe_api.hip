@@ -519,7 +519,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
         const uint64_t avg = ((uint64_t)n_indices + rows - 1) / rows;
         while (g_shift < 6 && (1ull << g_shift) < avg) ++g_shift;
     }
-    const uint64_t key_threads = (uint64_t)rows << g_shift;
+    const uint64_t key_threads = bags ? (((uint64_t)rows + robe::kKeyBags - 1) / robe::kKeyBags) << g_shift : (uint64_t)rows;
     uint64_t key_blocks = (key_threads + 255) / 256;
     if (key_blocks > 65536) key_blocks = 65536;
     const dim3 kgrid((uint32_t)key_blocks), kblock(256);

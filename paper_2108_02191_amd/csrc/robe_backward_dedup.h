@@ -36,7 +36,11 @@ constexpr int kRowsInFlight = 8;   // gradient rows a lane group loads before it
 constexpr int kWalk = 1;           // stretches of G sorted positions a lane group walks before it flushes its open run
                                    // (longer walks measured slower here: fewer, longer-lived groups)
 
-// S1.  Bags: a group of G lanes per bag, grid-stride over bags; single-hot: one lane per lookup.
+// S1.  Bags: a group of G lanes takes kKeyBags consecutive bags at a time (their bounds, then their
+// first G tokens each, are loaded together: a wavefront that did one bag and left spent its life in
+// two dependent trips to memory), grid-stride over such sets; single-hot: one lane per lookup.
+constexpr int kKeyBags = 4;        // eight measured the same, sixteen slower
+
 template <bool BAGS, bool ROWVAL>
 __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, uint32_t g_shift,
                                                          const int64_t *__restrict__ indices,
@@ -48,19 +52,45 @@ __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, u
     const uint32_t G = 1u << g_shift;
     const uint32_t lane = threadIdx.x & (G - 1u);
     const uint64_t groups = ((uint64_t)gridDim.x * 256u) >> g_shift;
-    for (uint64_t bag = ((uint64_t)blockIdx.x * 256u + threadIdx.x) >> g_shift; bag < rows; bag += groups) {
-        int64_t t0 = (int64_t)bag, t1 = (int64_t)bag + 1;
-        if constexpr (BAGS) {
-            t0 = offsets[bag];
-            t1 = offsets[bag + 1];
-            t0 = t0 < 0 ? 0 : (t0 > (int64_t)n_indices ? (int64_t)n_indices : t0);
-            t1 = t1 < t0 ? t0 : (t1 > (int64_t)n_indices ? (int64_t)n_indices : t1);
+    const uint64_t group = ((uint64_t)blockIdx.x * 256u + threadIdx.x) >> g_shift;
+    if constexpr (!BAGS) {
+        for (uint64_t k = group; k < rows; k += groups) {      // G = 1: one lookup per lane
+            keys[k] = staged_h(p, indices[k], (uint32_t)k % F);
+            vals[k] = (uint32_t)k;
         }
-        const uint32_t e = (uint32_t)bag % F;
-        for (int64_t t = t0 + lane; t < t1; t += G) {
-            keys[t] = staged_h(p, indices[t], e);
-            vals[t] = ROWVAL ? (uint32_t)bag : (uint32_t)t;
-            if constexpr (BAGS && !ROWVAL) tok_bag[t] = (uint32_t)bag;
+    } else {
+        for (uint64_t bag0 = group * kKeyBags; bag0 < rows; bag0 += groups * kKeyBags) {
+            int64_t t0[kKeyBags], t1[kKeyBags];
+#pragma unroll
+            for (int j = 0; j < kKeyBags; ++j) {
+                const uint64_t bag = bag0 + j < rows ? bag0 + j : rows - 1u;
+                t0[j] = offsets[bag];
+                t1[j] = offsets[bag + 1];
+            }
+            int64_t x[kKeyBags];
+#pragma unroll
+            for (int j = 0; j < kKeyBags; ++j) {
+                t0[j] = t0[j] < 0 ? 0 : (t0[j] > (int64_t)n_indices ? (int64_t)n_indices : t0[j]);
+                t1[j] = t1[j] < t0[j] ? t0[j] : (t1[j] > (int64_t)n_indices ? (int64_t)n_indices : t1[j]);
+                if (bag0 + j >= rows) t1[j] = t0[j];           // past the last bag: nothing to do
+                x[j] = t0[j] + lane < t1[j] ? indices[t0[j] + lane] : 0;
+            }
+#pragma unroll
+            for (int j = 0; j < kKeyBags; ++j) {
+                const uint32_t bag = (uint32_t)(bag0 + j);
+                const uint32_t e = bag % F;
+                int64_t t = t0[j] + lane;
+                if (t < t1[j]) {
+                    keys[t] = staged_h(p, x[j], e);
+                    vals[t] = ROWVAL ? bag : (uint32_t)t;
+                    if constexpr (!ROWVAL) tok_bag[t] = bag;
+                }
+                for (t += G; t < t1[j]; t += G) {              // bags longer than the lane group
+                    keys[t] = staged_h(p, indices[t], e);
+                    vals[t] = ROWVAL ? bag : (uint32_t)t;
+                    if constexpr (!ROWVAL) tok_bag[t] = bag;
+                }
+            }
         }
     }
 }
