@@ -349,7 +349,7 @@ int launch_radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint
         if (int rc = check_launch("sort (count)")) return rc;
         robe::sort_offsets_kernel<<<dim3(robe::kDigits), dim3(robe::kSortBlock), 0, stream>>>(sp);
         if (int rc = check_launch("sort (offsets)")) return rc;
-        robe::sort_scatter_kernel<<<dim3(sp.tiles), dim3(robe::kSortBlock), 0, stream>>>(sp, ks, vs, kd, vd);
+        robe::sort_scatter_kernel<robe::kScatterBlock><<<dim3(sp.tiles), dim3(robe::kScatterBlock), 0, stream>>>(sp, ks, vs, kd, vd);
         if (int rc = check_launch("sort (scatter)")) return rc;
         uint32_t *t = ks; ks = kd; kd = t;
         t = vs; vs = vd; vd = t;

@@ -12,8 +12,8 @@
 //            order (so the sort is stable), puts the tile into LDS in digit order and writes it out
 //            from there, a digit's pairs to consecutive slots.
 //
-// Inside a tile, wavefront w owns pairs [w * 1024, (w + 1) * 1024) and walks them 64 at a time, so the
-// input order is (wavefront, round, lane): a pair's rank is what earlier rounds of its wavefront
+// Inside a tile, wavefront w of the scatter kernel owns pairs [w * 512, (w + 1) * 512) and walks
+// them 64 at a time, so the input order is (wavefront, round, lane): a pair's rank is what earlier rounds of its wavefront
 // counted for the digit, plus the lanes below it in its own round with the same digit (found with one
 // ballot per digit bit), plus what the wavefronts before it hold.
 //
@@ -26,8 +26,8 @@
 
 namespace robe {
 
-constexpr int kSortBlock = 256;                       // 4 wavefronts
-constexpr int kSortRounds = 16;                       // 64 pairs per wavefront and round
+constexpr int kSortBlock = 256;                       // count and offsets kernels: 4 wavefronts
+constexpr int kSortRounds = 16;                       // count kernel: keys per thread
 constexpr uint32_t kSortTile = kSortBlock * kSortRounds;   // 4096 pairs
 constexpr uint32_t kDigits = 256;
 static_assert(kSortBlock == (int)kDigits, "one thread per digit in the per-digit steps");
@@ -83,9 +83,10 @@ __global__ __launch_bounds__(kSortBlock) void sort_count_kernel(SortPass s, cons
     s.tile_count[(uint64_t)threadIdx.x * s.tiles + tile] = h[threadIdx.x];
 }
 
-// Exclusive prefix of one value per thread over the workgroup's 256 threads.  `wave_total` is LDS for
-// four words; the call ends with a barrier, so it may be reused right after.
-__device__ __forceinline__ uint32_t exclusive_scan_256(uint32_t v, uint32_t *wave_total, uint32_t &total)
+// Exclusive prefix of one value per thread over the workgroup's BLOCK threads.  `wave_total` is LDS
+// for BLOCK / 64 words; the call ends with a barrier, so it may be reused right after.
+template <int BLOCK>
+__device__ __forceinline__ uint32_t exclusive_scan_block(uint32_t v, uint32_t *wave_total, uint32_t &total)
 {
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     uint32_t incl = v;
@@ -99,7 +100,7 @@ __device__ __forceinline__ uint32_t exclusive_scan_256(uint32_t v, uint32_t *wav
     uint32_t before = 0;
     total = 0;
 #pragma unroll
-    for (uint32_t w = 0; w < 4u; ++w) {
+    for (uint32_t w = 0; w < (uint32_t)BLOCK / 64u; ++w) {
         const uint32_t x = wave_total[w];
         before += w < wave ? x : 0u;
         total += x;
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_offsets_kernel(SortPass s)
             sum += c[k];
         }
         uint32_t total;
-        uint32_t a = carry + exclusive_scan_256(sum, wave_total, total);
+        uint32_t a = carry + exclusive_scan_block<kSortBlock>(sum, wave_total, total);
 #pragma unroll
         for (int k = 0; k < kOffsetItems; ++k) {
             const uint32_t i = t0 + t * kOffsetItems + (uint32_t)k;
@@ -138,37 +139,45 @@ __global__ __launch_bounds__(kSortBlock) void sort_offsets_kernel(SortPass s)
     if (t == 0) s.totals[digit] = carry;
 }
 
-__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(SortPass s, const uint32_t *__restrict__ keys_in,
-                                                                  const uint32_t *__restrict__ vals_in,
-                                                                  uint32_t *__restrict__ keys_out,
-                                                                  uint32_t *__restrict__ vals_out)
+// BLOCK threads take a tile of kSortTile pairs, kSortTile / BLOCK rounds of 64 per wavefront.
+// Measured on 8.5 M pairs: 512 threads (74 registers, six wavefronts per SIMD) 2 us per pass faster
+// than 256 (128 registers, four per SIMD); 1024 slower again.
+constexpr int kScatterBlock = 512;
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void sort_scatter_kernel(SortPass s, const uint32_t *__restrict__ keys_in,
+                                                             const uint32_t *__restrict__ vals_in,
+                                                             uint32_t *__restrict__ keys_out,
+                                                             uint32_t *__restrict__ vals_out)
 {
-    __shared__ uint32_t wave_count[4][kDigits];   // per wavefront: pairs of each digit so far; later: its base in the tile
-    __shared__ uint32_t digit_start[kDigits];     // first tile-local slot of each digit
-    __shared__ uint32_t digit_slot[kDigits];      // first output slot of this tile's pairs of each digit
-    __shared__ uint2 staged[kSortTile];           // the tile in digit order
+    constexpr int ROUNDS = (int)kSortTile / BLOCK, WAVES = BLOCK / 64;
+    static_assert(BLOCK >= (int)kDigits && BLOCK * ROUNDS == (int)kSortTile, "a thread per digit, whole rounds");
+    __shared__ uint32_t wave_count[WAVES][kDigits];   // per wavefront: pairs of each digit so far; later: its base in the tile
+    __shared__ uint32_t digit_slot[kDigits];          // first output slot of this tile's pairs of each digit; later: minus the digit's first tile-local slot
+    __shared__ uint2 staged[kSortTile];               // the tile in digit order
+    __shared__ uint32_t wave_total[WAVES];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x;
-    const uint64_t base = (uint64_t)tile * kSortTile + (uint64_t)wave * (kSortRounds * 64u);
-    __shared__ uint32_t wave_total[4];
-    for (uint32_t d = t; d < 4u * kDigits; d += kSortBlock) (&wave_count[0][0])[d] = 0;
+    const uint64_t base = (uint64_t)tile * kSortTile + (uint64_t)wave * (ROUNDS * 64u);
+    for (uint32_t d = t; d < (uint32_t)WAVES * kDigits; d += BLOCK) (&wave_count[0][0])[d] = 0;
     {   // a digit's pairs start after all pairs of the smaller digits, then after the digit's pairs in the tiles before
         uint32_t all;
-        const uint32_t before_tiles = s.tile_count[(uint64_t)t * s.tiles + tile];
-        digit_slot[t] = exclusive_scan_256(s.totals[t], wave_total, all) + before_tiles;
+        const uint32_t before_tiles = t < kDigits ? s.tile_count[(uint64_t)t * s.tiles + tile] : 0u;
+        const uint32_t before_digits = exclusive_scan_block<BLOCK>(t < kDigits ? s.totals[t] : 0u, wave_total, all);
+        if (t < kDigits) digit_slot[t] = before_digits + before_tiles;
     }
     __syncthreads();
 
-    uint32_t key[kSortRounds], val[kSortRounds], rank[kSortRounds];
+    uint32_t key[ROUNDS], val[ROUNDS], rank[ROUNDS];
 #pragma unroll
-    for (int i = 0; i < kSortRounds; ++i) {
+    for (int i = 0; i < ROUNDS; ++i) {
         const uint64_t at = base + (uint32_t)i * 64u + lane;
         key[i] = at < s.n ? keys_in[at] : 0xFFFFFFFFu;
         val[i] = at < s.n ? vals_in[at] : 0u;
     }
     const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int i = 0; i < kSortRounds; ++i) {
+    for (int i = 0; i < ROUNDS; ++i) {
         const uint64_t at = base + (uint32_t)i * 64u + lane;
         const bool have = at < s.n;
         const uint32_t digit = (key[i] >> s.shift) & s.mask;
@@ -188,41 +197,45 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(SortPass s, co
     }
     __syncthreads();
     // per digit: the tile's count, every wavefront's base inside the digit, the digit's first slot
-    {
-        uint32_t a = 0;
+    uint32_t in_digit = 0;
+    if (t < kDigits) {
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < WAVES; ++w) {
             const uint32_t c = wave_count[w][t];
-            wave_count[w][t] = a;
-            a += c;
+            wave_count[w][t] = in_digit;
+            in_digit += c;
         }
-        digit_start[t] = a;              // count for now
     }
-    __syncthreads();
-    {   // exclusive scan of the 256 digit counts
+    {   // exclusive scan of the 256 digit counts: where each digit starts in the tile.  Folded into the
+        // two tables the loops below look up once per pair: a wavefront's first tile-local slot of a
+        // digit, and the distance from a digit's tile-local slots to its output slots.
         uint32_t all;
-        const uint32_t c = digit_start[t];
-        digit_start[t] = exclusive_scan_256(c, wave_total, all);
+        const uint32_t start = exclusive_scan_block<BLOCK>(in_digit, wave_total, all);
+        if (t < kDigits) {
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) wave_count[w][t] += start;
+            digit_slot[t] -= start;
+        }
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < kSortRounds; ++i) {
+    for (int i = 0; i < ROUNDS; ++i) {
         const uint64_t at = base + (uint32_t)i * 64u + lane;
         if (at < s.n) {
             const uint32_t digit = (key[i] >> s.shift) & s.mask;
-            staged[digit_start[digit] + wave_count[wave][digit] + rank[i]] = make_uint2(key[i], val[i]);
+            staged[wave_count[wave][digit] + rank[i]] = make_uint2(key[i], val[i]);
         }
     }
     __syncthreads();
     const uint64_t tile_base = (uint64_t)tile * kSortTile;
     const uint32_t in_tile = s.n - tile_base < kSortTile ? (uint32_t)(s.n - tile_base) : kSortTile;
 #pragma unroll
-    for (int i = 0; i < kSortRounds; ++i) {
-        const uint32_t j = (uint32_t)i * kSortBlock + t;
+    for (int i = 0; i < ROUNDS; ++i) {
+        const uint32_t j = (uint32_t)i * BLOCK + t;
         if (j < in_tile) {
             const uint2 kv = staged[j];
             const uint32_t digit = (kv.x >> s.shift) & s.mask;
-            const uint32_t slot = digit_slot[digit] + (j - digit_start[digit]);
+            const uint32_t slot = digit_slot[digit] + j;      // wraps like the subtraction above: the sum is the slot
             keys_out[slot] = kv.x;
             vals_out[slot] = kv.y;
         }
