@@ -592,8 +592,6 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
 
         // R2..R4: records sorted by region
         const size_t lds_bin = (size_t)r.NR * 4;
-        robe::fill_u32_kernel<<<dim3((r.NR + 255) / 256), dim3(256), 0, stream>>>(r.counts, r.NR, 0u);
-        if (int rc = check_launch("backward (clear counts)")) return rc;
         if (int rc = allow_lds(robe::region_bin_kernel<false, false>, lds_bin, "backward (count)")) return rc;
         robe::region_bin_kernel<false, false><<<dim3(r.bin_blocks), dim3(robe::kBinBlock), lds_bin, stream>>>(p, r);
         if (int rc = check_launch("backward (count)")) return rc;

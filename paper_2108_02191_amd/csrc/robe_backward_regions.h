@@ -119,6 +119,8 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
     const uint32_t base_lane = lane - grp;
     const uint32_t n = s.n;
     const uint64_t thread_id = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    // the record counts of R2 start at zero (this kernel is the last one before it)
+    for (uint64_t i = thread_id; i < s.NR; i += (uint64_t)gridDim.x * kBlock) s.counts[i] = 0;
     if ((thread_id - lane) * kStretch >= n) return;     // the whole wavefront is past the end
     const uint64_t i_first = (thread_id - grp) * kStretch;   // first sorted position of this group's walk
 
