@@ -879,8 +879,10 @@ int robe_set_reproducible(int on)
     return g_reproducible.exchange(on ? 1 : 0);
 }
 
+// clear_grad: leave grad_array zeroed (the entry points' contract); false for a gradient array that
+// lives in a workspace and is cleared before every use anyway.
 static int launch_update(int rule, const robe_hash_t *hash, float *array, float *state, float *grad_array,
-                         float lr, float eps, void *stream)
+                         float lr, float eps, void *stream, bool clear_grad = true)
 {
     const uint64_t m = hash->m;
     hipStream_t s = (hipStream_t)stream;
@@ -891,11 +893,11 @@ static int launch_update(int rule, const robe_hash_t *hash, float *array, float 
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
     const bool keep = m <= kKeepArrayMax;
     if (rule == 0) {
-        if (vec) robe::update_kernel<4, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep);
-        else robe::update_kernel<1, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep);
+        if (vec) robe::update_kernel<4, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep, clear_grad);
+        else robe::update_kernel<1, 0><<<grid, block, 0, s>>>(array, state, grad_array, m, lr, eps, keep, clear_grad);
     } else {
-        if (vec) robe::update_kernel<4, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f, keep);
-        else robe::update_kernel<1, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f, keep);
+        if (vec) robe::update_kernel<4, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f, keep, clear_grad);
+        else robe::update_kernel<1, 1><<<grid, block, 0, s>>>(array, nullptr, grad_array, m, lr, 0.0f, keep, clear_grad);
     }
     return check_launch(rule == 0 ? "adagrad" : "sgd");
 }
@@ -987,7 +989,7 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const 
     else
         rc = launch_rows<true>(hash, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, grad_out, s);
     if (rc) return rc;
-    return launch_update(0, hash, array, state, grad, lr, eps, stream);
+    return launch_update(0, hash, array, state, grad, lr, eps, stream, false);
 }
 
 }  // extern "C"

@@ -666,7 +666,7 @@ constexpr uint32_t kLineLanes = 4;
 template <int V, int RULE>
 __global__ __launch_bounds__(kBlock) void update_kernel(float *__restrict__ array, float *__restrict__ state,
                                                         float *__restrict__ grad, uint64_t m, float lr, float eps,
-                                                        bool keep_array)
+                                                        bool keep_array, bool clear_grad)
 {
     typedef typename Vec<V>::A VT;
     const uint64_t nvec = m / V;
@@ -704,7 +704,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(float *__restrict__ arra
         if (keep_array) *reinterpret_cast<VT *>(array + it * V) = w;
         else __builtin_nontemporal_store(w, reinterpret_cast<VT *>(array + it * V));
         if constexpr (RULE == 0) __builtin_nontemporal_store(s, reinterpret_cast<VT *>(state + it * V));
-        __builtin_nontemporal_store(g, reinterpret_cast<VT *>(grad + it * V));
+        if (clear_grad) __builtin_nontemporal_store(g, reinterpret_cast<VT *>(grad + it * V));
     }
     // tail (m not a multiple of V): first threads of block 0
     if (V > 1 && blockIdx.x == 0) {
