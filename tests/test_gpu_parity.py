@@ -475,6 +475,36 @@ def test_fused_backward_adagrad_small_problems_take_the_two_step_route(m, d, Z, 
     assert bool((Md == 1).all()) and bool((sd == 1).all())
 
 
+@pytest.mark.parametrize("m,d,Z,B,F,bags", [(50_021, 16, 4, 9, 26, False), (100_003, 128, 32, 40, 26, True)])
+def test_two_step_route_twice_on_one_workspace(m, d, Z, B, F, bags):
+    # The route's gradient array lives at the front of the workspace and is left holding the first
+    # call's gradient; the second call must start from zeros all the same.  Exact (small-integer)
+    # gradients, two Adagrad steps, against the oracle's two steps.
+    h, H = both_hashes(m + 3 * B, m, d, Z, 0)
+    rng = np.random.default_rng(m)
+    M0 = rng.standard_normal(m).astype(np.float32)
+    Md, sd = to_dev(M0), torch.zeros(m, dtype=torch.float32, device=DEV)
+    Mo, so = M0.copy(), np.zeros(m, dtype=np.float32)
+    n_max = 4 * B * F + 64
+    need = robe.robe_fused_workspace_bytes(h, B, F, n_max)
+    assert need >= 4 * m
+    ws = torch.full((need,), 0x3F, dtype=torch.uint8, device=DEV)      # every float 0.747: not zeros
+    for step in range(2):
+        if bags:
+            ids, off = random_bags(rng, B * F, 60, 3.0, long_bag=40)
+            assert ids.size <= n_max
+        else:
+            ids, off = rng.integers(0, 60, size=(B, F), dtype=np.int64), None
+        Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+        robe.robe_backward_adagrad(h, to_dev(Gi), to_dev(ids), to_dev(off), B, F, Md, sd, 0.01, 1e-8, workspace=ws)
+        g, _ = oracle.backward(H, Gi, ids, off, B, F)
+        assert np.array_equal(g, np.round(g))
+        oracle.adagrad(Mo, so, g.astype(np.float32), 0.01, 1e-8)
+        Mg, sg = Md.cpu().numpy(), sd.cpu().numpy()
+        assert bits_equal(sg, so), step                     # the accumulator is exact: sums of squares of small integers
+        assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(Mo) + 0.02) + TINY), step
+
+
 @pytest.mark.parametrize("env,val", [("ROBE_TUNE_FWD", "4,1"), ("ROBE_TUNE_FWD", "2,1"), ("ROBE_TUNE_FWD", "1,1"),
                                      ("ROBE_TUNE_FWD", "4,0"), ("ROBE_TUNE_FWD", "2,0"), ("ROBE_TUNE_FWD", "0,0"),
                                      ("ROBE_TUNE_BWD", "4,1"), ("ROBE_TUNE_BWD", "2,1"), ("ROBE_TUNE_BWD", "4,0"),
