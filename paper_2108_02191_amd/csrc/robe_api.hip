@@ -372,7 +372,7 @@ struct BwdPlan {
     size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_tok_bag, off_temp, temp_bytes, bytes;
     // regions only
     robe::RegionPlan rp;
-    size_t off_head, off_src_row, off_run_tg, off_P, off_counts, off_starts, off_cursors, off_rec, off_rec_tg;
+    size_t off_head, off_src_row, off_run_tg, off_P, off_counts, off_starts, off_wg_first, off_rec, off_rec_tg;
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -477,7 +477,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     pl.off_P = off;       off = align_up(off + p_rows * h->d * 4, 256);
     pl.off_counts = off;  off = align_up(off + NR * 4, 256);
     pl.off_starts = off;  off = align_up(off + (NR + 1) * 4, 256);
-    pl.off_cursors = off; off = align_up(off + NR * 4, 256);
+    pl.off_wg_first = off; off = align_up(off + (size_t)r.bin_blocks * NR * 4, 256);
     pl.off_rec = off;     off = align_up(off + 2 * n * C * 8, 256);
     pl.off_rec_tg = off;  if (h->use_sign) off = align_up(off + 2 * n * C * 4, 256);
     pl.bytes = off;
@@ -566,7 +566,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
         r.P = reinterpret_cast<float *>(ws + pl.off_P);
         r.counts = reinterpret_cast<uint32_t *>(ws + pl.off_counts);
         r.starts = reinterpret_cast<uint32_t *>(ws + pl.off_starts);
-        r.cursors = reinterpret_cast<uint32_t *>(ws + pl.off_cursors);
+        r.wg_first = reinterpret_cast<uint32_t *>(ws + pl.off_wg_first);
         r.rec = reinterpret_cast<uint2 *>(ws + pl.off_rec);
         r.rec_tg = reinterpret_cast<uint32_t *>(ws + pl.off_rec_tg);
 

@@ -64,7 +64,8 @@ struct RegionPlan {
     uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
     uint32_t *run_tg;        // [n]  at run starts: token part of the sign hash (sign on only)
     float *P;                // [(n + 1) / 2][d] summed rows of the runs longer than one
-    uint32_t *counts, *starts, *cursors;   // [NR], [NR + 1], [NR]; after R3 counts holds the order of the regions for R5
+    uint32_t *counts, *starts;   // [NR], [NR + 1]; after R3 counts holds the order of the regions for R5
+    uint32_t *wg_first;      // [bin_blocks][NR]: R2 -> R4, see region_bin_kernel
     uint2 *rec;              // [<= 2 * n * C] (offset, source block | part flag)
     uint32_t *rec_tg;        // sign on only
 };
@@ -254,24 +255,27 @@ __device__ __forceinline__ void for_each_block(const Params &p, const RegionPlan
     }
 }
 
+// R2 counts this workgroup's records per region in LDS and adds the counts to the regions' totals;
+// what each addition returns - how many records of the region the workgroups before it (in arrival
+// order) hold - is kept in wg_first[workgroup][region].  R4, launched with the same grid after the
+// prefix sums of R3, starts its LDS cursors at starts[region] + wg_first and writes every record in
+// one sweep, with no further global atomics.
 template <bool SIGN, bool SCATTER>
 __global__ __launch_bounds__(kBinBlock) void region_bin_kernel(Params p, RegionPlan s)
 {
-    extern __shared__ uint32_t hist[];  // NR counters
-    for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) hist[r] = 0;
-    __syncthreads();
-    for_each_block<false>(p, s, [&](uint32_t, uint32_t, uint32_t r, uint32_t, uint32_t) { atomicAdd(&hist[r], 1u); });
-    __syncthreads();
+    extern __shared__ uint32_t hist[];  // NR counters (R2) or cursors (R4)
+    uint32_t *mine = s.wg_first + (uint64_t)blockIdx.x * s.NR;
     if constexpr (!SCATTER) {
+        for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) hist[r] = 0;
+        __syncthreads();
+        for_each_block<false>(p, s, [&](uint32_t, uint32_t, uint32_t r, uint32_t, uint32_t) { atomicAdd(&hist[r], 1u); });
+        __syncthreads();
         for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) {
             const uint32_t c = hist[r];
-            if (c) atomicAdd(&s.counts[r], c);
+            if (c) mine[r] = atomicAdd(&s.counts[r], c);     // regions without records of this workgroup: never read
         }
     } else {
-        for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) {
-            const uint32_t c = hist[r];
-            hist[r] = c ? atomicAdd(&s.cursors[r], c) : 0u;  // first slot of this workgroup in region r
-        }
+        for (uint32_t r = threadIdx.x; r < s.NR; r += kBinBlock) hist[r] = s.starts[r] + mine[r];
         __syncthreads();
         const uint32_t cap = s.starts[s.NR];                 // all records counted by R2
         for_each_block<SIGN>(p, s, [&](uint32_t o, uint32_t src, uint32_t r, uint32_t part, uint32_t tg) {
@@ -284,7 +288,7 @@ __global__ __launch_bounds__(kBinBlock) void region_bin_kernel(Params p, RegionP
     }
 }
 
-// R3: one workgroup.  starts / cursors: exclusive prefix of counts, grand total in starts[NR];
+// R3: one workgroup.  starts: exclusive prefix of counts, grand total in starts[NR];
 // then the order in which R5 takes the regions.
 constexpr uint32_t kScanPer = kMaxRegions / 1024u;
 
@@ -350,7 +354,6 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
         const uint32_t i = k * 1024u + t;
         if (i < s.NR) {
             s.starts[i] = at[k];
-            s.cursors[i] = at[k];
         }
     }
     if (t == 0) s.starts[s.NR] = total;
