@@ -232,25 +232,41 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
 // R2 / R4.  Walk this workgroup's sorted positions; call f(offset, source block, region, part flag,
 // sign term) for every block of every run, twice when the block leaves its region.
 // ---------------------------------------------------------------------------------------------
+constexpr int kBinAhead = 4;
+
 template <bool SIGN, typename F>
 __device__ __forceinline__ void for_each_block(const Params &p, const RegionPlan &s, F f)
 {
     const uint64_t b = (uint64_t)blockIdx.x * s.pos_per_block;
     uint64_t e = b + s.pos_per_block;
     if (e > s.n) e = s.n;
-    for (uint64_t i = b + threadIdx.x; i < e; i += kBinBlock) {
-        if (!s.head[i]) continue;
-        const uint32_t th = s.keys[i];
-        const uint32_t src0 = s.src_row[i] * p.C;
-        const uint32_t tg = SIGN ? s.run_tg[i] : 0u;
-        uint32_t cc = 0;  // (Ch * c) mod P, built up by addition
-        for (uint32_t c = 0; c < p.C; ++c) {
-            const uint32_t o = offset_of(p, th, cc);
-            const uint32_t r = o >> s.r_shift;
-            f(o, src0 + c, r, 0u, tg);
-            const uint64_t r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
-            if ((uint64_t)o + p.Z > r_end) f(o, src0 + c, r_end == p.m ? 0u : r + 1u, kPartBit, tg);
-            cc = add_p(cc, p.Ch);
+    // kBinAhead positions per thread and trip, their flag, key and source row all requested at once
+    // (for positions that head no run the last two are read for nothing: a thread that asked for the
+    // flag first and the rest after spent the sweep in two dependent trips to memory per position)
+    for (uint64_t i0 = b + threadIdx.x; i0 < e; i0 += (uint64_t)kBinBlock * kBinAhead) {
+        uint32_t hd[kBinAhead], th[kBinAhead], sr[kBinAhead], tgv[kBinAhead];
+#pragma unroll
+        for (int u = 0; u < kBinAhead; ++u) {
+            const uint64_t i = i0 + (uint64_t)u * kBinBlock;
+            const uint64_t at = i < e ? i : i0;               // i0 < e: a position of this workgroup
+            hd[u] = i < e ? s.head[at] : 0u;
+            th[u] = s.keys[at];
+            sr[u] = s.src_row[at];
+            tgv[u] = SIGN ? s.run_tg[at] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kBinAhead; ++u) {
+            if (!hd[u]) continue;
+            const uint32_t src0 = sr[u] * p.C;
+            uint32_t cc = 0;  // (Ch * c) mod P, built up by addition
+            for (uint32_t c = 0; c < p.C; ++c) {
+                const uint32_t o = offset_of(p, th[u], cc);
+                const uint32_t r = o >> s.r_shift;
+                f(o, src0 + c, r, 0u, tgv[u]);
+                const uint64_t r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
+                if ((uint64_t)o + p.Z > r_end) f(o, src0 + c, r_end == p.m ? 0u : r + 1u, kPartBit, tgv[u]);
+                cc = add_p(cc, p.Ch);
+            }
         }
     }
 }
