@@ -7,7 +7,8 @@
 // Tuning knobs, read from the environment at call time (for experiments and for
 // tests that must reach every kernel variant; the defaults are the measured
 // best choices):
-//   ROBE_TUNE_FWD, ROBE_TUNE_BWD = "V,consec"   lane layout: V in {1,2,4} elements per lane,
+//   ROBE_TUNE_FWD, ROBE_TUNE_BWD = "V,consec"   lane layout: V in {1,2,4} elements per lane (also 3, 6, 8
+//                                               when strided), d / V a power of two <= 64;
 //                                               consec 1 = consecutive elements of one chunk,
 //                                               0 = strided; "0,0" = shape-generic kernel
 //   ROBE_TUNE_TL                                 lookups per wavefront tile (single-hot kernels)
