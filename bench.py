@@ -49,6 +49,8 @@ def parse():
                     help="capture the step (one per id batch) into a HIP graph and time replays beside the eager steps")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="target oracle time per phase")
     ap.add_argument("--id-batches", type=int, default=2, help="distinct id batches rotated across steps")
+    ap.add_argument("--opt", action="append", default=[], metavar="FIELD=VALUE",
+                    help="set a field of the robe_options_t passed to every call (e.g. --opt backward_route=2)")
     ap.add_argument("--copy-calib-mb", type=int, default=0,
                     help="before the warm-up, run one plain device copy of this many MiB: a dispatch of known "
                          "size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters in a --pmc run")
@@ -97,7 +99,7 @@ def cpu_baseline(w, M, ids, off, G, target_s):
     import numpy as np
     import oracle
     H = oracle.init_hash(w.hash_seed, w.m, w.d, w.Z, w.use_sign)
-    threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
+    threads = max(1, oracle.max_threads())      # every host core the OpenMP runtime offers; the count is reported
     F = w.n_features
     if w.dims is not None or w.array_dtype == "bf16":
         threads = 1             # the oracle's mixed-dimension and bf16 loops are sequential
@@ -203,11 +205,13 @@ def main():
     out = torch.empty((B, sum(w.dims)) if mixed else (B, F, w.d), dtype=torch.float32, device=dev)
     ga = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_bwd else None
     st = torch.zeros(w.m, dtype=torch.float32, device=dev) if do_ada else None
+    fields = {k: int(v) for k, v in (kv.split("=", 1) for kv in args.opt)}
     if args.reproducible:
-        robe.robe_set_reproducible(True)        # before the workspace sizes: the mode changes the route
-    ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n) for n in tokens) if (do_bwd and w.dims is None) else 0
+        fields["reproducible"] = 1
+    opt = robe.options(**fields) if fields else None
+    ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n, opt) for n in tokens) if (do_bwd and w.dims is None) else 0
     fused = do_ada and not args.unfused
-    fws_bytes = max(robe.robe_fused_workspace_bytes(h, B, F, n) for n in tokens) if fused else 0
+    fws_bytes = max(robe.robe_fused_workspace_bytes(h, B, F, n, opt) for n in tokens) if fused else 0
     ws = torch.empty(max(ws_bytes, fws_bytes, 1), dtype=torch.uint8, device=dev) if max(ws_bytes, fws_bytes) else None
 
     stream = torch.cuda.current_stream()
@@ -217,26 +221,26 @@ def main():
         if ev:
             ev[0].record(stream)
         if mixed:
-            robe.robe_forward_mixed(h, w.dims, Md, idd, offd, B, out=out)
+            robe.robe_forward_mixed(h, w.dims, Md, idd, offd, B, out=out, options=opt)
         elif bf16:
-            robe.robe_forward_bf16(h, Mb, idd, offd, B, F, out=out)
+            robe.robe_forward_bf16(h, Mb, idd, offd, B, F, out=out, options=opt)
         else:
-            robe.robe_forward(h, Md, idd, offd, B, F, out=out)
+            robe.robe_forward(h, Md, idd, offd, B, F, out=out, options=opt)
         if ev:
             ev[1].record(stream)
         if mixed:
-            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga)
+            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga, options=opt)
             if ev:
                 ev[2].record(stream)
             ga.zero_()
             if ev:
                 ev[3].record(stream)
         elif fused:
-            robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Md, st, w.lr, w.eps, workspace=ws)
+            robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Md, st, w.lr, w.eps, workspace=ws, options=opt)
             if ev:
                 ev[3].record(stream)
         elif do_bwd:
-            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
+            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws, options=opt)
             if ev:
                 ev[2].record(stream)
             if do_ada:
@@ -253,9 +257,9 @@ def main():
     if do_bwd:
         idd, offd = dev_batches[0]
         if mixed:
-            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga)
+            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga, options=opt)
         else:
-            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
+            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws, options=opt)
         touched = int((ga != 0).sum().item())
         ga.zero_()
 
@@ -274,9 +278,6 @@ def main():
 
     graph_ms = None
     if args.graph:
-        if os.environ.get("ROBE_TUNE_SORT") == "library":
-            print("--graph: the device library's sort records fill operations; use the built-in sort", file=sys.stderr)
-            sys.exit(2)
         side = torch.cuda.Stream()
         side.wait_stream(stream)
         graph = torch.cuda.CUDAGraph()
@@ -321,7 +322,7 @@ def main():
             idd, offd = dev_batches[k % len(dev_batches)]
             e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             e[0].record(stream)
-            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws)
+            robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws, options=opt)
             e[1].record(stream)
             robe.robe_adagrad_update(h, Md, st, ga, w.lr, w.eps)
             e[2].record(stream)
@@ -460,7 +461,7 @@ def main():
                    "n_features": F, "rows": rows, "tokens_per_step": tok, "bag_mean": w.bag_mean,
                    "ids": f"{w.id_dist}({w.zipf_alpha})" if w.id_dist == "zipf" else w.id_dist,
                    "use_sign": w.use_sign, "phases": w.phases, "id_batches": len(batches),
-                   "touched_slots": touched, "reproducible_mode": bool(args.reproducible)},
+                   "touched_slots": touched, "reproducible_mode": bool(args.reproducible), "options": fields},
         "effective_GBps_whole_step": total_alg / (ms_per_step * 1e-3) / 1e9,
         "effective_frac_of_hbm_peak": total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "device_copy_GBps": round(copy_gbs, 1),

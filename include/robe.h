@@ -27,6 +27,10 @@
  *     aborts.  robe_last_error() gives the text of the calling thread's most
  *     recent failure.  Arguments are validated on the host before anything is
  *     launched; a failed call launches nothing.
+ *   - Calls that launch kernels take a `const robe_options_t *options`; NULL means
+ *     the defaults (every field zero).  Options are read during the call only and
+ *     are the only thing besides the arguments that a call depends on: the library
+ *     keeps no process-wide settings and reads no environment variables.
  *   - Token ids are int64 and are read as unsigned 64-bit integers in the hash
  *     formulas (a negative id is the integer id + 2^64).  No cardinality is
  *     needed: hashing accepts any id.
@@ -81,6 +85,72 @@ typedef struct robe_hash_t {
 } robe_hash_t;
 
 /*
+ * Per-call choices.  All-zero is "let the library decide" for every field; a value the field does
+ * not define makes the call fail with ROBE_EINVAL.  Apart from `reproducible` they exist for
+ * measurements and for tests that must reach every kernel variant; results are the same to
+ * rounding whatever is chosen.
+ *
+ *   reproducible   1: run-to-run reproducible backward.  Eq. 3 sums float32 terms in an order the
+ *                  paper does not fix; with float atomics that order, and so the last bits of the
+ *                  result, change from run to run.  With this set, robe_backward, robe_backward_mixed
+ *                  and robe_backward_adagrad take the route that has no float atomic (blocks sorted by
+ *                  destination region, one workgroup per region) and add every slice's blocks in a
+ *                  canonical order: the same call on the same inputs on the same device gives the same
+ *                  bits every time.  It costs a few per cent on large problems, more on small ones, and
+ *                  the larger workspace (pass the same options to the workspace query).  A shape or
+ *                  size that route cannot take (see robe_backward) fails with ROBE_EINVAL rather than
+ *                  giving up reproducibility.  Forward and the update rules are reproducible always.
+ *   backward_route ROBE_ROUTE_AUTO, or a request for one scatter strategy: _DIRECT (one float atomic
+ *                  per element), _COMBINE (tokens sorted, repeated tokens summed, atomics once per
+ *                  distinct token) or _REGIONS (no float atomics).  A request that the shape or size
+ *                  cannot follow falls back to _DIRECT (the workspace query then reports 0 bytes);
+ *                  `reproducible` overrides it.
+ *   fused_route    how robe_backward_adagrad runs: ROBE_ROUTE_AUTO, _REGIONS (scatter and update in
+ *                  one pass) or _TWO_STEP (scatter into a gradient array in the workspace, then the
+ *                  update kernel).
+ *   fwd_elems, fwd_strided / bwd_elems, bwd_strided
+ *                  lane layout of the gather / direct-scatter kernels: elements per lane (1, 2 or 4;
+ *                  also 3, 6, 8 when strided; d / elems must be a power of two <= 64), owned as
+ *                  consecutive elements of one chunk (strided = 0) or as elements lane + k * lanes
+ *                  (strided = 1).  elems = -1 selects the shape-generic kernel, 0 the default.
+ *   tile_lookups   lookups per wavefront tile of the single-hot kernels (a multiple of 64 / lanes, <= 64)
+ *   row_order      ROBE_ROWS_AUTO, _MEMORY (rows in memory order), _BY_TABLE (table by table, one
+ *                  eighth of that order per XCD, when the launch is large enough to matter) or
+ *                  _BY_TABLE_ALWAYS
+ *   tile_combine   direct single-hot scatter: 0 by size, 1 never, 2 always combine the duplicates of
+ *                  every tile of 64 lookups before the atomics
+ *   region_shift   log2 of the region size in floats for ROBE_ROUTE_REGIONS, 10..15
+ *   key_bits       most significant bits of the 31-bit token key that the sort looks at, 8..31
+ *   region_records 0 by size, 1: ROBE_ROUTE_REGIONS writes a region-sorted copy of the block records,
+ *                  2: the region workgroups look their blocks up in the sorted token list instead
+ */
+typedef struct robe_options_t {
+    int32_t reproducible;
+    int32_t backward_route;
+    int32_t fused_route;
+    int32_t fwd_elems, fwd_strided;
+    int32_t bwd_elems, bwd_strided;
+    int32_t tile_lookups;
+    int32_t row_order;
+    int32_t tile_combine;
+    int32_t region_shift;
+    int32_t key_bits;
+    int32_t region_records;
+    int32_t reserved[3];      /* must be zero */
+} robe_options_t;
+
+#define ROBE_ROUTE_AUTO      0
+#define ROBE_ROUTE_DIRECT    1
+#define ROBE_ROUTE_COMBINE   2
+#define ROBE_ROUTE_REGIONS   3
+#define ROBE_ROUTE_TWO_STEP  4
+
+#define ROBE_ROWS_AUTO             0
+#define ROBE_ROWS_MEMORY           1
+#define ROBE_ROWS_BY_TABLE         2
+#define ROBE_ROWS_BY_TABLE_ALWAYS  3
+
+/*
  * Draw the hash coefficients from a seed (host only; Section 3.2: "randomly
  * chosen values").  The stream is SplitMix64 (Steele, Lea, Flood 2014) started
  * at state `seed`; eight successive outputs r give, in this order,
@@ -115,21 +185,23 @@ int robe_offsets(const robe_hash_t *hash, const int64_t *indices, int64_t n, int
  *                    [0, n_indices] on the device, so a malformed CSR cannot
  *                    read outside `indices`.
  *   out        device float[batch][n_features][d], fully overwritten
+ *   options    NULL or host robe_options_t (fwd_elems, fwd_strided, tile_lookups, row_order are read)
  * Errors: ROBE_EINVAL, ROBE_EHIP.  batch == 0 is a no-op.
  */
 int robe_forward(const robe_hash_t *hash, const float *array,
                  const int64_t *indices, const int64_t *offsets, int64_t n_indices,
-                 int64_t batch, int32_t n_features, float *out, void *stream);
+                 int64_t batch, int32_t n_features, float *out,
+                 const robe_options_t *options, void *stream);
 
 /*
- * Bytes of device workspace robe_backward needs for this problem size, for
- * either kind of input (single-hot or bags); 0 when none is needed (small
- * problems scatter directly).  The size depends on the problem size and on the
- * reproducible switch (robe_set_reproducible): ask after setting it.  Needs the current device (it asks the sort
- * primitive for its temporary-storage size); returns 0 on invalid arguments
- * or when no device is present.
+ * Bytes of device workspace robe_backward needs for this problem size and these options, for
+ * either kind of input (single-hot or bags), written to *bytes (host); 0 when none is needed
+ * (small problems scatter directly).  Host arithmetic only: no device is touched.
+ * Errors: ROBE_EINVAL (bad hash, sizes or options, bytes == NULL; options->reproducible set for a
+ * shape or size that has no reproducible route); *bytes is 0 then.
  */
-size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices);
+int robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices,
+                         const robe_options_t *options, size_t *bytes);
 
 /*
  * Backward scatter-add (Eq. 3):
@@ -138,17 +210,21 @@ size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_fe
  * token per row).  Accumulates onto the caller's grad_array (device float[m]);
  * the order of the float32 additions is not fixed, so results agree with an
  * exact sum only to rounding.  Small scatters issue one float atomic per
- * element.  Larger ones first combine the gradient rows of repeated tokens
+ * element (ROBE_ROUTE_DIRECT).  Larger ones first combine the gradient rows of repeated tokens
  * (sort by the token part of the hash, run-wise sums) and issue the atomics
- * once per run; the largest (arrays of 2^26 slots or more with 2^21 tokens or
- * more) then sort the blocks by destination region and sum each region in LDS,
- * with no float atomic at all.  The sorted paths need the workspace and rows,
- * n_indices below 2^31 - 1.  With a CSR that is not non-decreasing, bag bounds
+ * once per run (ROBE_ROUTE_COMBINE); the largest (arrays of 2^26 slots or more with 2^21 tokens or
+ * more) then collect the blocks by destination region and sum each region in LDS,
+ * with no float atomic at all (ROBE_ROUTE_REGIONS; the route of the reproducible option).  The
+ * sorted routes need the workspace, rows and n_indices below 2^31 - 1, d <= 512 and Z <= d;
+ * ROBE_ROUTE_REGIONS also needs d / Z and the lane group to be powers of two, at most 2^30 array
+ * slots, and a region size (2^10 .. 2^15 floats, at least 2 Z) that leaves the array's last region
+ * either full or at least Z floats long.
+ * With a CSR that is not non-decreasing, bag bounds
  * are clamped to [0, n_indices] so nothing outside the buffers is touched, but
  * which tokens such bags hold is unspecified here.  Every route records kernels
  * only on the stream (no fill or copy operations, no synchronisation), so the
  * call may be captured into a HIP graph.
- *   workspace  device buffer of at least robe_workspace_bytes(...) bytes,
+ *   workspace  device buffer of at least robe_workspace_bytes(...) bytes (same options),
  *              256-byte aligned, contents undefined before and after; may be
  *              NULL when that size is 0
  * Errors: ROBE_EINVAL (also: workspace too small), ROBE_EHIP.
@@ -156,7 +232,8 @@ size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_fe
 int robe_backward(const robe_hash_t *hash, const float *grad_out,
                   const int64_t *indices, const int64_t *offsets, int64_t n_indices,
                   int64_t batch, int32_t n_features, float *grad_array,
-                  void *workspace, size_t workspace_bytes, void *stream);
+                  void *workspace, size_t workspace_bytes,
+                  const robe_options_t *options, void *stream);
 
 /*
  * Sparse Adagrad step on the touched slots (Duchi, Hazan, Singer 2011; the
@@ -187,23 +264,26 @@ int robe_sgd_update(const robe_hash_t *hash, float *array, float *grad_array, fl
  * Fused training step: backward scatter-add (Eq. 3) and the Adagrad update in one pass, for a
  * gradient array that would otherwise start from zero.  The result is that of
  *   robe_backward(..., grad_array = zeros, ...) followed by robe_adagrad_update(array, state, grad_array)
- * to the same rounding caveats, but for large problems the gradient never exists in device memory:
- * the blocks are sorted by destination, every region of the array is summed in LDS by the one
- * workgroup that owns it, and that workgroup updates array and state directly.  Slots that receive
- * no gradient are left bit-for-bit unchanged.
+ * to the same rounding caveats, but on large arrays the gradient never exists in device memory:
+ * the blocks are collected by destination region, every region of the array is summed in LDS by the
+ * one workgroup that owns it, and that workgroup updates array and state directly.  Slots that
+ * receive no gradient are left bit-for-bit unchanged, and regions that receive none are not read.
  *   array, state   device float[m], updated in place
- *   workspace      device buffer of at least robe_fused_workspace_bytes(...) bytes, 256-byte aligned
- *                  (it holds the sort buffers, the summed rows of repeated tokens and the block
- *                  records; for problems too small or shapes too odd for the sorted path it holds
- *                  a gradient array instead and the two steps run one after the other)
+ *   workspace      device buffer of at least robe_fused_workspace_bytes(...) bytes (same options),
+ *                  256-byte aligned (it holds the sort buffers, the summed rows of repeated tokens and
+ *                  the block records; for problems too small or shapes too odd for the sorted path it
+ *                  holds a gradient array instead and the two steps run one after the other)
+ * robe_fused_workspace_bytes is host arithmetic like robe_workspace_bytes and fails the same way.
  * Errors: ROBE_EINVAL (null pointers, eps <= 0, non-finite lr/eps, workspace too small), ROBE_EHIP.
  * Like robe_backward it records kernels only and may be captured into a HIP graph.
  */
-size_t robe_fused_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices);
+int robe_fused_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices,
+                               const robe_options_t *options, size_t *bytes);
 int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
                           const int64_t *indices, const int64_t *offsets, int64_t n_indices,
                           int64_t batch, int32_t n_features, float *array, float *state,
-                          float lr, float eps, void *workspace, size_t workspace_bytes, void *stream);
+                          float lr, float eps, void *workspace, size_t workspace_bytes,
+                          const robe_options_t *options, void *stream);
 
 /*
  * Tables of different embedding dimensions sharing the one array (Section 3.2, "Multiple embedding
@@ -214,16 +294,19 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
  * table f at column dims[0] + ... + dims[f-1].  indices / offsets / n_indices / batch are as in
  * robe_forward; dims is a HOST array of n_features entries, read during the call only.
  * One launch is made per run of consecutive tables of equal dimension.  robe_backward_mixed
- * accumulates onto grad_array like robe_backward, always with float atomics (no workspace; it is
- * refused while the reproducible switch is on); follow it with robe_adagrad_update / robe_sgd_update.
+ * accumulates onto grad_array like robe_backward, always with float atomics (no workspace; it fails
+ * with ROBE_EINVAL when options->reproducible is set); follow it with robe_adagrad_update /
+ * robe_sgd_update.
  * Errors: ROBE_EINVAL (also: a dims entry that is zero or not a multiple of Z), ROBE_EHIP.
  */
 int robe_forward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *array,
                        const int64_t *indices, const int64_t *offsets, int64_t n_indices,
-                       int64_t batch, int32_t n_features, float *out, void *stream);
+                       int64_t batch, int32_t n_features, float *out,
+                       const robe_options_t *options, void *stream);
 int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out,
                         const int64_t *indices, const int64_t *offsets, int64_t n_indices,
-                        int64_t batch, int32_t n_features, float *grad_array, void *stream);
+                        int64_t batch, int32_t n_features, float *grad_array,
+                        const robe_options_t *options, void *stream);
 
 /*
  * Low-precision array (Section 2 notes that quantisation can be applied together with the method;
@@ -238,7 +321,8 @@ int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const flo
 int robe_array_to_bf16(const float *src, uint16_t *dst, uint64_t n, void *stream);
 int robe_forward_bf16(const robe_hash_t *hash, const uint16_t *array,
                       const int64_t *indices, const int64_t *offsets, int64_t n_indices,
-                      int64_t batch, int32_t n_features, float *out, void *stream);
+                      int64_t batch, int32_t n_features, float *out,
+                      const robe_options_t *options, void *stream);
 
 /*
  * The stable radix sort the backward pass sorts its tokens with, on its own (a testing aid, like
@@ -253,23 +337,6 @@ size_t robe_sort_workspace_bytes(uint64_t n);
 int robe_sort_pairs(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint32_t *vals_b, uint64_t n,
                     uint32_t lo_bit, uint32_t hi_bit, void *workspace, size_t workspace_bytes, int *result_in_b,
                     void *stream);
-
-/*
- * Run-to-run reproducible scatter (process-wide switch, off at start; returns the previous setting).
- * Eq. 3 sums float32 terms whose order the paper does not fix; with float atomics that order, and so
- * the last bits of the result, change from run to run.  While the switch is on, robe_backward and
- * robe_backward_adagrad always take the route that has no float atomic (blocks sorted by destination
- * region, one workgroup per region) and put every slice's blocks into a canonical order before adding
- * them, so the same call on the same inputs on the same device gives the same bits every time.  The
- * price is a few per cent of time on large problems, more on small ones (where the atomics would have
- * been faster), and the larger workspace: ask robe_workspace_bytes / robe_fused_workspace_bytes after
- * setting the switch.  Shapes that route cannot handle (Z > d, d / Z or the lane group not a power of
- * two, more than 2^30 array slots) make the two calls fail with ROBE_EINVAL instead of silently
- * giving up reproducibility.  The forward pass and the two update rules are reproducible always.
- * Set it before the calls it should govern: calls that run concurrently with the change may use
- * either setting.
- */
-int robe_set_reproducible(int on);
 
 /* Text of the calling thread's most recent error ("" if none).  Never NULL. */
 const char *robe_last_error(void);

@@ -44,11 +44,24 @@ class RobeHash(ctypes.Structure):
         return max(1, self.d // self.Z)
 
 
+class RobeOptions(ctypes.Structure):
+    """Mirror of ``robe_options_t``: per-call choices, all-zero = the library's defaults."""
+    _fields_ = [("reproducible", ctypes.c_int32), ("backward_route", ctypes.c_int32), ("fused_route", ctypes.c_int32),
+                ("fwd_elems", ctypes.c_int32), ("fwd_strided", ctypes.c_int32),
+                ("bwd_elems", ctypes.c_int32), ("bwd_strided", ctypes.c_int32),
+                ("tile_lookups", ctypes.c_int32), ("row_order", ctypes.c_int32), ("tile_combine", ctypes.c_int32),
+                ("region_shift", ctypes.c_int32), ("key_bits", ctypes.c_int32), ("region_records", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 3)]
+
+
+ROUTE_AUTO, ROUTE_DIRECT, ROUTE_COMBINE, ROUTE_REGIONS, ROUTE_TWO_STEP = 0, 1, 2, 3, 4
+ROWS_AUTO, ROWS_MEMORY, ROWS_BY_TABLE, ROWS_BY_TABLE_ALWAYS = 0, 1, 2, 3
+
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
            "robe_forward_mixed", "robe_backward_mixed", "robe_array_to_bf16", "robe_forward_bf16",
            "robe_sort_workspace_bytes", "robe_sort_pairs",
-           "robe_set_reproducible", "robe_last_error")
+           "robe_last_error")
 
 _lib = None
 
@@ -67,38 +80,35 @@ def lib() -> ctypes.CDLL:
         L.robe_init_hash.argtypes = [u64, u64, u32, u32, ctypes.c_int, HP]
         L.robe_offsets.restype = ctypes.c_int
         L.robe_offsets.argtypes = [HP, vp, i64, i32, vp, vp, vp]
+        OP = ctypes.POINTER(RobeOptions)
+        szp = ctypes.POINTER(ctypes.c_size_t)
         L.robe_forward.restype = ctypes.c_int
-        L.robe_forward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp]
-        L.robe_workspace_bytes.restype = ctypes.c_size_t
-        L.robe_workspace_bytes.argtypes = [HP, i64, i32, i64]
+        L.robe_forward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, OP, vp]
+        L.robe_workspace_bytes.restype = ctypes.c_int
+        L.robe_workspace_bytes.argtypes = [HP, i64, i32, i64, OP, szp]
         L.robe_backward.restype = ctypes.c_int
-        L.robe_backward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_size_t, vp]
+        L.robe_backward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_size_t, OP, vp]
         L.robe_adagrad_update.restype = ctypes.c_int
         L.robe_adagrad_update.argtypes = [HP, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp]
         L.robe_sgd_update.restype = ctypes.c_int
         L.robe_sgd_update.argtypes = [HP, vp, vp, ctypes.c_float, vp]
-        L.robe_fused_workspace_bytes.restype = ctypes.c_size_t
-        L.robe_fused_workspace_bytes.argtypes = [HP, i64, i32, i64]
+        L.robe_fused_workspace_bytes.restype = ctypes.c_int
+        L.robe_fused_workspace_bytes.argtypes = [HP, i64, i32, i64, OP, szp]
         L.robe_backward_adagrad.restype = ctypes.c_int
         L.robe_backward_adagrad.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_float, ctypes.c_float,
-                                            vp, ctypes.c_size_t, vp]
+                                            vp, ctypes.c_size_t, OP, vp]
         for fn in (L.robe_forward_mixed, L.robe_backward_mixed):
             fn.restype = ctypes.c_int
-            fn.argtypes = [HP, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
-                           ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+            fn.argtypes = [HP, vp, vp, vp, vp, i64, i64, i32, vp, OP, vp]
         L.robe_array_to_bf16.restype = ctypes.c_int
-        L.robe_array_to_bf16.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+        L.robe_array_to_bf16.argtypes = [vp, vp, u64, vp]
         L.robe_forward_bf16.restype = ctypes.c_int
-        L.robe_forward_bf16.argtypes = [HP, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
-                                        ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        L.robe_forward_bf16.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, OP, vp]
         L.robe_sort_workspace_bytes.restype = ctypes.c_size_t
-        L.robe_sort_workspace_bytes.argtypes = [ctypes.c_uint64]
+        L.robe_sort_workspace_bytes.argtypes = [u64]
         L.robe_sort_pairs.restype = ctypes.c_int
-        L.robe_sort_pairs.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
-                                      ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_size_t,
-                                      ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
-        L.robe_set_reproducible.restype = ctypes.c_int
-        L.robe_set_reproducible.argtypes = [ctypes.c_int]
+        L.robe_sort_pairs.argtypes = [vp, vp, vp, vp, u64, u32, u32, vp, ctypes.c_size_t,
+                                      ctypes.POINTER(ctypes.c_int), vp]
         L.robe_last_error.restype = ctypes.c_char_p
         L.robe_last_error.argtypes = []
         _lib = L
@@ -138,8 +148,23 @@ def robe_offsets(h: RobeHash, indices: torch.Tensor, n_features: int, want_signs
     return (off, sg) if want_signs else off
 
 
+def _opt(options: Optional[RobeOptions]):
+    return None if options is None else ctypes.byref(options)
+
+
+def options(**fields) -> RobeOptions:
+    """A ``robe_options_t`` with the given fields set and every other field at its default (0)."""
+    o = RobeOptions()
+    for k, v in fields.items():
+        if k not in {f[0] for f in RobeOptions._fields_} or k == "reserved":
+            raise TypeError(f"robe_options_t has no field {k!r}")
+        setattr(o, k, int(v))
+    return o
+
+
 def robe_forward(h: RobeHash, array: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
-                 batch: int, n_features: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                 batch: int, n_features: int, out: Optional[torch.Tensor] = None,
+                 options: Optional[RobeOptions] = None) -> torch.Tensor:
     if array.numel() != h.m:
         raise ValueError("array length differs from hash.m")
     if offsets is not None and offsets.numel() != batch * n_features + 1:
@@ -150,17 +175,28 @@ def robe_forward(h: RobeHash, array: torch.Tensor, indices: torch.Tensor, offset
         raise ValueError("out has the wrong size")
     _check(lib().robe_forward(ctypes.byref(h), _dev(array, torch.float32, "array"),
                               _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
-                              indices.numel(), batch, n_features, _dev(out, torch.float32, "out"), _stream()))
+                              indices.numel(), batch, n_features, _dev(out, torch.float32, "out"), _opt(options), _stream()))
     return out
 
 
-def robe_workspace_bytes(h: RobeHash, batch: int, n_features: int, n_indices: int) -> int:
-    return int(lib().robe_workspace_bytes(ctypes.byref(h), batch, n_features, n_indices))
+def robe_workspace_bytes(h: RobeHash, batch: int, n_features: int, n_indices: int,
+                         options: Optional[RobeOptions] = None) -> int:
+    need = ctypes.c_size_t(0)
+    _check(lib().robe_workspace_bytes(ctypes.byref(h), batch, n_features, n_indices, _opt(options), ctypes.byref(need)))
+    return int(need.value)
+
+
+def _workspace(workspace: Optional[torch.Tensor], need: int, device):
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_len = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return workspace, ws_ptr, ws_len
 
 
 def robe_backward(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
                   batch: int, n_features: int, grad_array: torch.Tensor,
-                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                  workspace: Optional[torch.Tensor] = None, options: Optional[RobeOptions] = None) -> torch.Tensor:
     """grad_array += scatter of grad_out (in place); returns grad_array."""
     if grad_array.numel() != h.m:
         raise ValueError("grad_array length differs from hash.m")
@@ -168,15 +204,12 @@ def robe_backward(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, of
         raise ValueError("grad_out has the wrong size")
     if offsets is not None and offsets.numel() != batch * n_features + 1:
         raise ValueError("offsets must hold batch*n_features + 1 entries")
-    need = robe_workspace_bytes(h, batch, n_features, indices.numel())
-    if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=grad_array.device)
-    ws_ptr = None if workspace is None else workspace.data_ptr()
-    ws_len = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    need = robe_workspace_bytes(h, batch, n_features, indices.numel(), options) if workspace is None else 0
+    workspace, ws_ptr, ws_len = _workspace(workspace, need, grad_array.device)
     _check(lib().robe_backward(ctypes.byref(h), _dev(grad_out, torch.float32, "grad_out"),
                                _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                indices.numel(), batch, n_features, _dev(grad_array, torch.float32, "grad_array"),
-                               ws_ptr, ws_len, _stream()))
+                               ws_ptr, ws_len, _opt(options), _stream()))
     return grad_array
 
 
@@ -198,13 +231,17 @@ def robe_sgd_update(h: RobeHash, array: torch.Tensor, grad_array: torch.Tensor, 
                                  _dev(grad_array, torch.float32, "grad_array"), lr, _stream()))
 
 
-def robe_fused_workspace_bytes(h: RobeHash, batch: int, n_features: int, n_indices: int) -> int:
-    return int(lib().robe_fused_workspace_bytes(ctypes.byref(h), batch, n_features, n_indices))
+def robe_fused_workspace_bytes(h: RobeHash, batch: int, n_features: int, n_indices: int,
+                               options: Optional[RobeOptions] = None) -> int:
+    need = ctypes.c_size_t(0)
+    _check(lib().robe_fused_workspace_bytes(ctypes.byref(h), batch, n_features, n_indices, _opt(options), ctypes.byref(need)))
+    return int(need.value)
 
 
 def robe_backward_adagrad(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
                           batch: int, n_features: int, array: torch.Tensor, state: torch.Tensor,
-                          lr: float, eps: float, workspace: Optional[torch.Tensor] = None) -> None:
+                          lr: float, eps: float, workspace: Optional[torch.Tensor] = None,
+                          options: Optional[RobeOptions] = None) -> None:
     """Backward scatter-add and Adagrad update in one call (array and state updated in place)."""
     for t, name in ((array, "array"), (state, "state")):
         if t.numel() != h.m:
@@ -213,20 +250,12 @@ def robe_backward_adagrad(h: RobeHash, grad_out: torch.Tensor, indices: torch.Te
         raise ValueError("grad_out has the wrong size")
     if offsets is not None and offsets.numel() != batch * n_features + 1:
         raise ValueError("offsets must hold batch*n_features + 1 entries")
-    need = robe_fused_workspace_bytes(h, batch, n_features, indices.numel())
-    if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=array.device)
-    ws_ptr = None if workspace is None else workspace.data_ptr()
-    ws_len = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    need = robe_fused_workspace_bytes(h, batch, n_features, indices.numel(), options) if workspace is None else 0
+    workspace, ws_ptr, ws_len = _workspace(workspace, need, array.device)
     _check(lib().robe_backward_adagrad(ctypes.byref(h), _dev(grad_out, torch.float32, "grad_out"),
                                        _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                        indices.numel(), batch, n_features, _dev(array, torch.float32, "array"),
-                                       _dev(state, torch.float32, "state"), lr, eps, ws_ptr, ws_len, _stream()))
-
-
-def robe_set_reproducible(on: bool) -> bool:
-    """Process-wide switch for the run-to-run reproducible scatter; returns the previous setting."""
-    return bool(lib().robe_set_reproducible(1 if on else 0))
+                                       _dev(state, torch.float32, "state"), lr, eps, ws_ptr, ws_len, _opt(options), _stream()))
 
 
 def _dims_array(dims):
@@ -235,7 +264,8 @@ def _dims_array(dims):
 
 
 def robe_forward_mixed(h: RobeHash, dims, array: torch.Tensor, indices: torch.Tensor,
-                       offsets: Optional[torch.Tensor], batch: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                       offsets: Optional[torch.Tensor], batch: int, out: Optional[torch.Tensor] = None,
+                       options: Optional[RobeOptions] = None) -> torch.Tensor:
     """Forward for tables of different dimensions: returns float32[batch, sum(dims)]."""
     F, D = len(dims), int(sum(dims))
     if array.numel() != h.m:
@@ -249,12 +279,13 @@ def robe_forward_mixed(h: RobeHash, dims, array: torch.Tensor, indices: torch.Te
     da = _dims_array(dims)
     _check(lib().robe_forward_mixed(ctypes.byref(h), ctypes.cast(da, ctypes.c_void_p), _dev(array, torch.float32, "array"),
                                     _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
-                                    indices.numel(), batch, F, _dev(out, torch.float32, "out"), _stream()))
+                                    indices.numel(), batch, F, _dev(out, torch.float32, "out"), _opt(options), _stream()))
     return out
 
 
 def robe_backward_mixed(h: RobeHash, dims, grad_out: torch.Tensor, indices: torch.Tensor,
-                        offsets: Optional[torch.Tensor], batch: int, grad_array: torch.Tensor) -> None:
+                        offsets: Optional[torch.Tensor], batch: int, grad_array: torch.Tensor,
+                        options: Optional[RobeOptions] = None) -> None:
     """Backward for tables of different dimensions (accumulates onto grad_array)."""
     F, D = len(dims), int(sum(dims))
     if grad_array.numel() != h.m:
@@ -266,7 +297,8 @@ def robe_backward_mixed(h: RobeHash, dims, grad_out: torch.Tensor, indices: torc
     da = _dims_array(dims)
     _check(lib().robe_backward_mixed(ctypes.byref(h), ctypes.cast(da, ctypes.c_void_p), _dev(grad_out, torch.float32, "grad_out"),
                                      _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
-                                     indices.numel(), batch, F, _dev(grad_array, torch.float32, "grad_array"), _stream()))
+                                     indices.numel(), batch, F, _dev(grad_array, torch.float32, "grad_array"),
+                                     _opt(options), _stream()))
 
 
 def robe_array_to_bf16(array: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -281,7 +313,8 @@ def robe_array_to_bf16(array: torch.Tensor, out: Optional[torch.Tensor] = None) 
 
 
 def robe_forward_bf16(h: RobeHash, array_bf16: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
-                      batch: int, n_features: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                      batch: int, n_features: int, out: Optional[torch.Tensor] = None,
+                      options: Optional[RobeOptions] = None) -> torch.Tensor:
     """robe_forward on an array of bfloat16 bit patterns (int16 tensor of length m)."""
     if array_bf16.numel() != h.m:
         raise ValueError("array length differs from hash.m")
@@ -293,7 +326,7 @@ def robe_forward_bf16(h: RobeHash, array_bf16: torch.Tensor, indices: torch.Tens
         raise ValueError("out has the wrong size")
     _check(lib().robe_forward_bf16(ctypes.byref(h), _dev(array_bf16, torch.int16, "array"),
                                    _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
-                                   indices.numel(), batch, n_features, _dev(out, torch.float32, "out"), _stream()))
+                                   indices.numel(), batch, n_features, _dev(out, torch.float32, "out"), _opt(options), _stream()))
     return out
 
 

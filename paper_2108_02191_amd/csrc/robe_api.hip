@@ -1,28 +1,13 @@
 // C ABI of the ROBE-Z library (see include/robe.h): argument validation,
 // launch geometry and kernel selection.  All device work is in robe_kernels.h
 // (forward, direct backward, update rules), robe_backward_dedup.h (sorted
-// backward with float atomics) and robe_backward_regions.h (sorted backward
-// without them, fused Adagrad).
+// backward with float atomics), robe_backward_regions.h (sorted backward
+// without them, fused Adagrad) and robe_radix_sort.h (the token sort).
 //
-// Tuning knobs, read from the environment at call time (for experiments and for
-// tests that must reach every kernel variant; the defaults are the measured
-// best choices):
-//   ROBE_TUNE_FWD, ROBE_TUNE_BWD = "V,consec"   lane layout: V in {1,2,4} elements per lane (also 3, 6, 8
-//                                               when strided), d / V a power of two <= 64;
-//                                               consec 1 = consecutive elements of one chunk,
-//                                               0 = strided; "0,0" = shape-generic kernel
-//   ROBE_TUNE_TL                                 lookups per wavefront tile (single-hot kernels)
-//   ROBE_TUNE_XCD = 0 | 1 | 2                    row order: memory order / table by table per XCD /
-//                                               the latter even for tiny launches
-//   ROBE_TUNE_BWD_MODE = direct | dedup | regions   backward scatter strategy
-//   ROBE_TUNE_BWD_TILE = 0 | 2                   direct single-hot backward never / always with the per-tile combining
-//   ROBE_TUNE_FUSED = regions | twostep          how robe_backward_adagrad runs
-//   ROBE_TUNE_RSHIFT = 10..15                    log2 of the region size of the region-sorted scatter
-//   ROBE_TUNE_KEY_BITS = 8..31                   key bits the backward sort looks at
-//   ROBE_TUNE_SORT = library                     the device library's radix sort instead of robe_radix_sort.h
+// Nothing here is process-wide state: every choice a call makes follows from
+// its arguments and its robe_options_t (NULL = all defaults).
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -31,8 +16,6 @@
 
 #include "../../include/robe.h"
 #include "robe_kernels.h"
-#include <rocprim/device/device_radix_sort.hpp>
-
 #include "robe_backward_dedup.h"
 #include "robe_backward_regions.h"
 #include "robe_radix_sort.h"
@@ -40,7 +23,6 @@
 namespace {
 
 thread_local char g_err[512] = "";
-std::atomic<int> g_reproducible{0};   // robe_set_reproducible
 
 int fail(int code, const char *fmt, ...)
 {
@@ -109,6 +91,56 @@ bool is_pow2(uint32_t v) { return v && !(v & (v - 1)); }
 uint32_t log2u(uint32_t v) { uint32_t s = 0; while ((1u << s) < v) ++s; return s; }
 bool aligned(const void *ptr, size_t a) { return ((uintptr_t)ptr % a) == 0; }
 
+// A call's options, checked and with defaults filled in (see robe_options_t in the header).
+struct Opt {
+    bool reproducible = false;
+    int bwd_route = ROBE_ROUTE_AUTO, fused_route = ROBE_ROUTE_AUTO;
+    int fwd_elems = 0, fwd_strided = 0, bwd_elems = 0, bwd_strided = 0;
+    int tile_lookups = 0, row_order = ROBE_ROWS_AUTO, tile_combine = 0, region_shift = 0, key_bits = 0;
+    int region_records = 0;
+};
+
+bool elems_ok(int v, int strided)
+{
+    if (v == 0 || v == -1) return true;
+    if (v == 1 || v == 2 || v == 4) return true;
+    return strided && (v == 3 || v == 6 || v == 8);
+}
+
+int read_options(const robe_options_t *o, Opt *out)
+{
+    *out = Opt();
+    if (o == nullptr) return ROBE_OK;
+    if ((o->reproducible | 1) != 1) return fail(ROBE_EINVAL, "options: reproducible = %d is neither 0 nor 1", o->reproducible);
+    if (o->backward_route < ROBE_ROUTE_AUTO || o->backward_route > ROBE_ROUTE_REGIONS)
+        return fail(ROBE_EINVAL, "options: backward_route = %d is not a scatter strategy", o->backward_route);
+    if (o->fused_route != ROBE_ROUTE_AUTO && o->fused_route != ROBE_ROUTE_REGIONS && o->fused_route != ROBE_ROUTE_TWO_STEP)
+        return fail(ROBE_EINVAL, "options: fused_route = %d is none of AUTO, REGIONS, TWO_STEP", o->fused_route);
+    if ((o->fwd_strided | 1) != 1 || (o->bwd_strided | 1) != 1) return fail(ROBE_EINVAL, "options: fwd_strided / bwd_strided must be 0 or 1");
+    if (!elems_ok(o->fwd_elems, o->fwd_strided) || !elems_ok(o->bwd_elems, o->bwd_strided))
+        return fail(ROBE_EINVAL, "options: elements per lane must be -1, 0, 1, 2, 4 (or 3, 6, 8 when strided)");
+    if (o->tile_lookups < 0 || o->tile_lookups > 64) return fail(ROBE_EINVAL, "options: tile_lookups = %d outside 0..64", o->tile_lookups);
+    if (o->row_order < ROBE_ROWS_AUTO || o->row_order > ROBE_ROWS_BY_TABLE_ALWAYS) return fail(ROBE_EINVAL, "options: row_order = %d", o->row_order);
+    if (o->tile_combine < 0 || o->tile_combine > 2) return fail(ROBE_EINVAL, "options: tile_combine = %d outside 0..2", o->tile_combine);
+    if (o->region_shift != 0 && (o->region_shift < 10 || o->region_shift > 15))
+        return fail(ROBE_EINVAL, "options: region_shift = %d outside 10..15", o->region_shift);
+    if (o->key_bits != 0 && (o->key_bits < 8 || o->key_bits > 31)) return fail(ROBE_EINVAL, "options: key_bits = %d outside 8..31", o->key_bits);
+    if (o->region_records < 0 || o->region_records > 2) return fail(ROBE_EINVAL, "options: region_records = %d outside 0..2", o->region_records);
+    if (o->reserved[0] | o->reserved[1] | o->reserved[2]) return fail(ROBE_EINVAL, "options: reserved fields must be zero");
+    out->reproducible = o->reproducible != 0;
+    out->bwd_route = o->backward_route;
+    out->fused_route = o->fused_route;
+    out->fwd_elems = o->fwd_elems; out->fwd_strided = o->fwd_strided;
+    out->bwd_elems = o->bwd_elems; out->bwd_strided = o->bwd_strided;
+    out->tile_lookups = o->tile_lookups;
+    out->row_order = o->row_order;
+    out->tile_combine = o->tile_combine;
+    out->region_shift = o->region_shift;
+    out->key_bits = o->key_bits;
+    out->region_records = o->region_records;
+    return ROBE_OK;
+}
+
 // Which elements a lane owns.  V == 0 means "use the shape-generic kernel".
 struct Layout {
     int V;
@@ -116,29 +148,26 @@ struct Layout {
     uint32_t G;
 };
 
-// Optional override for experiments: ROBE_TUNE_FWD / ROBE_TUNE_BWD = "V,consec" (e.g. "4,1").
-bool tuned_layout(const char *var, const robe_hash_t *h, Layout *out)
+// The layout the options ask for, if they ask for one (elems != 0): ROBE_EINVAL when the shape or
+// the alignment of the rows cannot take it.
+int requested_layout(int elems, int strided, const robe_hash_t *h, const void *rows_ptr, Layout *out)
 {
-    const char *s = getenv(var);
-    if (!s) return false;
-    int V = 0, consec = 0;
-    if (sscanf(s, "%d,%d", &V, &consec) != 2) return false;
-    if (V == 0) { *out = {0, false, 0}; return true; }
-    if (V != 1 && V != 2 && V != 4 && (consec || (V != 3 && V != 6 && V != 8))) return false;
-    if (h->d % V) return false;
+    if (elems == -1) { *out = {0, false, 0}; return ROBE_OK; }
+    const int V = elems;
+    const bool consec = strided == 0;
+    if (h->d % V) return fail(ROBE_EINVAL, "options: %d elements per lane do not divide d = %u", V, h->d);
     const uint32_t G = h->d / V;
-    if (!is_pow2(G) || G > 64) return false;
-    if (consec && h->Z <= h->d && h->Z % V) return false;
-    *out = {V, consec != 0, G};
-    return true;
+    if (!is_pow2(G) || G > 64) return fail(ROBE_EINVAL, "options: d / elements per lane = %u is not a power of two <= 64", G);
+    if (consec && h->Z <= h->d && h->Z % V) return fail(ROBE_EINVAL, "options: %d consecutive elements per lane do not divide Z = %u", V, h->Z);
+    if (consec && !aligned(rows_ptr, 4 * (size_t)V)) return fail(ROBE_EINVAL, "options: rows are not aligned for %d-element vectors", V);
+    *out = {V, consec, G};
+    return ROBE_OK;
 }
 
-Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
+int pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr, const Opt &opt, Layout *out)
 {
-    Layout t;
-    if (tuned_layout(bwd ? "ROBE_TUNE_BWD" : "ROBE_TUNE_FWD", h, &t)) {
-        if (!t.consec || aligned(rows_ptr, 4 * (size_t)t.V)) return t;
-    }
+    const int elems = bwd ? opt.bwd_elems : opt.fwd_elems;
+    if (elems != 0) return requested_layout(elems, bwd ? opt.bwd_strided : opt.fwd_strided, h, rows_ptr, out);
     // (blocks larger than embeddings, Z > d: an embedding is one contiguous piece of its chunk, so
     // any V that divides d stays inside it)
     const int vs[3] = {4, 2, 1};
@@ -147,7 +176,7 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
         for (int V : vs) {
             if ((h->Z <= h->d && h->Z % V) || h->d % V) continue;
             const uint32_t G = h->d / V;
-            if (is_pow2(G) && G <= 64 && aligned(rows_ptr, 4 * (size_t)V)) return {V, true, G};
+            if (is_pow2(G) && G <= 64 && aligned(rows_ptr, 4 * (size_t)V)) { *out = {V, true, G}; return ROBE_OK; }
         }
     }
     // backward (and forward when Z is too small): lanes of a group on consecutive addresses.  Three, six
@@ -155,7 +184,7 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
     for (int V : {1, 2, 3, 4, 6, 8}) {
         if (h->d % V) continue;
         const uint32_t G = h->d / V;
-        if (is_pow2(G) && G <= 64) return {V, false, G};
+        if (is_pow2(G) && G <= 64) { *out = {V, false, G}; return ROBE_OK; }
     }
     // Any other d up to 512: the smallest G * V >= d, the lane slots past d idle (d = 100: 2 x 64)
     Layout best = {0, false, 0};
@@ -166,13 +195,8 @@ Layout pick_layout(const robe_hash_t *h, bool bwd, const void *rows_ptr)
             break;
         }
     }
-    return best;
-}
-
-int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return v ? atoi(v) : dflt;
+    *out = best;
+    return ROBE_OK;
 }
 
 // Where a launch's tables sit inside a sample's input row and output row (see robe::Geom).
@@ -182,12 +206,13 @@ struct TableView {
 };
 
 template <bool BWD, typename AT = float>
-int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, const int64_t *offsets,
+int launch_rows(const robe_hash_t *h, const Opt &opt, const AT *src, const int64_t *indices, const int64_t *offsets,
                 int64_t n_indices, int64_t rows, uint32_t F, float *dst, const void *rows_ptr, hipStream_t stream,
                 const TableView *view = nullptr)
 {
     const robe::Params p = to_params(h);
-    const Layout lay = pick_layout(h, BWD, rows_ptr);
+    Layout lay;
+    if (int rc = pick_layout(h, BWD, rows_ptr, opt, &lay)) return rc;
     const bool sign = h->use_sign != 0;
     const bool bags = offsets != nullptr;
 
@@ -218,22 +243,21 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
     const uint32_t step = 64u / lay.G;
     // one pass of the gather loop per wavefront tile measured best (more, shorter wavefronts)
     q.TL = step * robe::kUnroll >= 64u ? 64u : step * robe::kUnroll;
-    if (const char *s = getenv("ROBE_TUNE_TL")) {
-        const int tl = atoi(s);
-        if (tl >= (int)step && tl <= 64 && tl % (int)step == 0) q.TL = (uint32_t)tl;
+    if (opt.tile_lookups) {
+        if (opt.tile_lookups < (int)step || opt.tile_lookups % (int)step != 0)
+            return fail(ROBE_EINVAL, "options: tile_lookups = %d is not a multiple of %u", opt.tile_lookups, step);
+        q.TL = (uint32_t)opt.tile_lookups;
     }
-    // single-hot backward: tiles of 64 lookups whose duplicates are combined before the atomics
-    // (ROBE_TUNE_BWD_TILE=0: the plain scatter)
+    // single-hot backward: tiles of 64 lookups whose duplicates are combined before the atomics,
     // from 32768 lookups on: below that the 64-lookup tiles leave too few wavefronts (measured at
     // d = 128: 26624 lookups 27 us plain, 32 us tiled; 53248 lookups 56 us plain, 38 us tiled).
-    // ROBE_TUNE_BWD_TILE=2 forces it.
-    const int tile_mode = env_int("ROBE_TUNE_BWD_TILE", 1);
-    const bool tile = BWD && !bags && !lay.consec && (tile_mode == 2 || (tile_mode == 1 && rows >= 32768));
+    // options->tile_combine: 1 never, 2 always.
+    const bool tile = BWD && !bags && !lay.consec && (opt.tile_combine == 2 || (opt.tile_combine == 0 && rows >= 32768));
     const int64_t rows_per_wave = tile ? 64 : (bags ? (int64_t)step : (int64_t)q.TL);
     const int64_t waves = (rows + rows_per_wave - 1) / rows_per_wave;
     int64_t blocks = (waves + robe::kWavesPerBlock - 1) / robe::kWavesPerBlock;
     // Walk the rows table by table, one eighth of that order per XCD (see RowWalk), unless the launch
-    // is too small to matter.  ROBE_TUNE_XCD=0 keeps the memory order.
+    // is too small to matter.  options->row_order overrides.
     q.bpx = 0;
     // It pays where array reads dominate the traffic: bags (many blocks read per row written) and
     // blocks of at most one 64-byte sector (several sectors fetched per sector used).  For single-hot
@@ -242,8 +266,9 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
     // token arrive close together in time and their same-address atomics serialise (measured 30 % slower).
     // With tiles that combine their duplicates it is the other way round: a tile of one table holds
     // many copies of that table's frequent tokens.
-    const int xcd_mode = env_int("ROBE_TUNE_XCD", ((!BWD && (bags || h->Z * 4 <= 64)) || tile) ? 1 : 0);   // 2: even for tiny launches
-    if (F >= 2 && ((xcd_mode == 1 && blocks >= 64) || xcd_mode == 2)) {
+    int order = opt.row_order;
+    if (order == ROBE_ROWS_AUTO) order = ((!BWD && (bags || h->Z * 4 <= 64)) || tile) ? ROBE_ROWS_BY_TABLE : ROBE_ROWS_MEMORY;
+    if (F >= 2 && ((order == ROBE_ROWS_BY_TABLE && blocks >= 64) || order == ROBE_ROWS_BY_TABLE_ALWAYS)) {
         q.bpx = (uint32_t)((blocks + robe::kXcds - 1) / robe::kXcds);
         blocks = (int64_t)q.bpx * robe::kXcds;
     }
@@ -312,12 +337,6 @@ int launch_rows(const robe_hash_t *h, const AT *src, const int64_t *indices, con
 // Backward with duplicate tokens combined: plan (shared by robe_workspace_bytes
 // and robe_backward) and launch.
 // ---------------------------------------------------------------------------
-// The library's default switches to a merge sort below 2^20 items, which for these (key, value)
-// pairs takes about twenty small kernels; the one-sweep radix sort it uses above that is faster
-// here from a few ten thousand items on (measured: 852 K pairs, 146 us against about 40 us).
-using TokenSortConfig = rocprim::radix_sort_config<rocprim::default_config, rocprim::default_config,
-                                                   rocprim::default_config, 32768>;
-
 // Stable sort of n (key, value) pairs on key bits [lo, hi) with the kernels of robe_radix_sort.h.
 // The sorted pairs end in (keys_b, vals_b) after an odd number of passes, else in (keys_a, vals_a):
 // *in_b says which.  temp: radix_sort_temp_bytes(n) bytes, 256-byte aligned.
@@ -378,11 +397,9 @@ struct BwdPlan {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Decide between the direct scatter and the combine-duplicates one, and lay out the workspace.
-// ROBE_TUNE_BWD_MODE = direct | dedup overrides the size heuristic (not the hard limits).
-// Whether the region-sorted scatter replaces the float atomics when nothing is forced.  Measured:
+// Whether the region-sorted scatter replaces the float atomics when nothing is requested.  Measured:
 // 11 % faster on the 1 GB array with 8.5 M tokens, but 80 % slower on the 100 MB array with 1.7 M
-// tokens (few regions, a fixed cost per region), and it needs ten times the workspace.
+// tokens (few regions, a fixed cost per region), and it needs several times the workspace.
 bool regions_by_default(const robe_hash_t *h, int64_t n_indices)
 {
     return h->m >= (1ull << 26) && n_indices >= (1ll << 21);
@@ -390,42 +407,55 @@ bool regions_by_default(const robe_hash_t *h, int64_t n_indices)
 
 int fail_not_reproducible()
 {
-    return fail(ROBE_EINVAL, "reproducible mode: this shape or size has no route without float atomics "
-                             "(it needs Z <= d, d / Z and the lane group a power of two, at most 2^30 array slots "
-                             "and 32-bit record counts)");
+    return fail(ROBE_EINVAL, "reproducible option: this shape or size has no route without float atomics "
+                             "(it needs Z <= d <= 512, d / Z and the lane group a power of two, at most 2^30 array slots, "
+                             "32-bit record counts and a region size that leaves no short last region)");
 }
 
-BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, bool bags, const void *grad_out,
-                      bool need_regions = false)
+// Region size for the region-sorted scatter: 2^shift floats.  A region must hold two blocks, the
+// array at most kMaxRegions regions, and the last region must be full or at least Z floats long (a
+// block that starts in the region before it must end inside it).  0: no size fits.
+uint32_t pick_region_shift(const robe_hash_t *h, int requested)
+{
+    auto fits = [&](uint32_t shift) {
+        const uint64_t R = 1ull << shift, NR = (h->m + R - 1) >> shift, last = h->m - ((NR - 1) << shift);
+        return NR <= robe::kMaxRegions && R >= 2ull * h->Z && (NR == 1 || last == R || last >= h->Z);
+    };
+    if (requested) return fits((uint32_t)requested) ? (uint32_t)requested : 0u;
+    for (uint32_t shift = 13; shift <= 15; ++shift)
+        if (fits(shift)) return shift;
+    for (uint32_t shift = 12; shift >= 10; --shift)
+        if (fits(shift)) return shift;
+    return 0;
+}
+
+// Decide between the direct scatter, the combine-duplicates one and the region-sorted one, and lay
+// out the workspace.  Host arithmetic only, so that the workspace queries and the calls agree.
+// need_regions: the caller (the fused step) wants the region-sorted scatter whatever the size.
+BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_t n_indices, bool bags,
+                      const void *grad_out, bool need_regions = false)
 {
     BwdPlan pl;
     memset(&pl, 0, sizeof(pl));
-    const char *mode = getenv("ROBE_TUNE_BWD_MODE");
-    if (mode && strcmp(mode, "direct") == 0 && !g_reproducible.load(std::memory_order_relaxed)) return pl;
-    if (g_reproducible.load(std::memory_order_relaxed)) {
+    int route = opt.bwd_route;
+    if (opt.reproducible) {
         need_regions = true;   // the only route without float atomics
-        mode = nullptr;
+        route = ROBE_ROUTE_AUTO;
     }
-    const bool forced = need_regions || (mode && (strcmp(mode, "dedup") == 0 || strcmp(mode, "regions") == 0));
+    if (route == ROBE_ROUTE_DIRECT && !need_regions) return pl;
+    const bool forced = need_regions || route == ROBE_ROUTE_COMBINE || route == ROBE_ROUTE_REGIONS;
     // 32-bit positions and row numbers
     if (rows < 1 || n_indices < 1 || rows >= 0x7FFFFFFFll || n_indices >= 0x7FFFFFFFll) return pl;
-    pl.lay = pick_layout(h, true, grad_out);
+    if (pick_layout(h, true, grad_out, opt, &pl.lay) != ROBE_OK) return pl;   // the launch reports the bad layout
     if (pl.lay.V == 0 || pl.lay.consec || h->Z > h->d) return pl;   // shapes the sorted routes do not handle
     // sorting costs about 0.1 ms plus 45 ns per thousand tokens: not worth it for small scatters
     if (!forced && (uint64_t)n_indices * h->d < (1ull << 25)) return pl;
     // Sorting on the top 24 key bits is one radix pass cheaper; tokens that share those bits merely
     // interleave and are merged less often, which stays rare while there are far fewer tokens than 2^24.
-    pl.key_bits = (uint32_t)env_int("ROBE_TUNE_KEY_BITS", n_indices <= (1ll << 24) ? 24 : 31);
-    if (pl.key_bits < 8 || pl.key_bits > 31) pl.key_bits = 31;
+    pl.key_bits = opt.key_bits ? (uint32_t)opt.key_bits : (n_indices <= (1ll << 24) ? 24u : 31u);
 
     const size_t n = (size_t)n_indices;
-    size_t temp = 0;
-    uint32_t *nul = nullptr;
-    if (rocprim::radix_sort_pairs<TokenSortConfig>(nullptr, temp, nul, nul, nul, nul, n, 31 - pl.key_bits, 31) != hipSuccess) {
-        (void)hipGetLastError();
-        return pl;                                    // no device to ask: the caller cannot run the scatter either
-    }
-    if (radix_sort_temp_bytes(n) > temp) temp = radix_sort_temp_bytes(n);      // room for either sort
+    const size_t temp = radix_sort_temp_bytes(n);
     pl.dedup = true;
     size_t off = 0;
     pl.off_keys_in = off;  off = align_up(off + n * 4, 256);
@@ -437,25 +467,34 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     pl.temp_bytes = temp;
     pl.bytes = off;
 
-    // Region-sorted scatter on top of the combined runs.  ROBE_TUNE_BWD_MODE = regions forces it,
-    // = dedup keeps the float atomics.
-    const bool want_regions = need_regions || (mode ? strcmp(mode, "regions") == 0 : regions_by_default(h, n_indices));
+    // Region-sorted scatter on top of the combined runs.
+    const bool want_regions = need_regions || (route == ROBE_ROUTE_AUTO ? regions_by_default(h, n_indices) : route == ROBE_ROUTE_REGIONS);
     if (!want_regions) return pl;
     const uint64_t C = h->d / h->Z;                       // Z <= d here (lay.V != 0)
-    uint32_t shift = (uint32_t)env_int("ROBE_TUNE_RSHIFT", 0);
-    if (shift < 10 || shift > 15) {
-        shift = 13;
-        while (shift < 15 && ((h->m + (1ull << shift) - 1) >> shift) > robe::kMaxRegions) ++shift;
-    }
+    const uint32_t shift = pick_region_shift(h, opt.region_shift);
+    if (shift == 0) return pl;
     const uint64_t NR = (h->m + (1ull << shift) - 1) >> shift;
-    uint32_t lg = 8;  // lanes per record in the reduce kernel: at most 64 groups per workgroup
-    while (lg < 64 && lg < h->Z) lg <<= 1;
+    uint32_t lg = 8;  // lanes per record in the reduce kernel: at most 64 groups per workgroup, a group inside one wavefront
+    while (lg < robe::kMaxRecordLanes && lg < h->Z) lg <<= 1;
+    static_assert(robe::kMaxRecordLanes <= 64 && (robe::kMaxRecordLanes & (robe::kMaxRecordLanes - 1)) == 0,
+                  "a lane group of the reduce kernel is a power of two and never spans two wavefronts");
     const uint32_t grp_shift = 9 - log2u(lg);
     const uint64_t p_rows = (n + 1) / 2;
-    if (NR > robe::kMaxRegions || (1ull << shift) < 2ull * h->Z || shift < grp_shift ||
-        (1u << (shift - grp_shift)) < h->Z ||               // a slice of the region must hold one block
+    if (shift < grp_shift || (1u << (shift - grp_shift)) < h->Z ||               // a slice of the region must hold one block
         ((uint64_t)rows + p_rows) * C >= 0x7FFFFFFFull || 2ull * n * C >= 0xFFFFFFFFull)
         return pl;
+    // The reproducible order splits an overfull region into at most 2^kMaxClassShift classes of at most
+    // one round's records each.  Refuse what could come near that: one and a half times the average
+    // region (hashed offsets spread evenly; a block in Z / R leaves a second record), plus every run of
+    // the most frequent token (one per kStretch * G copies) in one region, against six tenths of the room.
+    if (opt.reproducible) {
+        const uint64_t batch = h->use_sign ? robe::rec_batch<true>() : robe::rec_batch<false>();
+        const uint64_t room = ((batch << robe::kMaxClassShift) * 6) / 10;
+        const uint64_t R = 1ull << shift, span = R < h->m ? R : h->m;
+        const uint64_t avg = (n * C * (span + h->Z) / span + NR - 1) / NR;
+        const uint64_t worst = avg + avg / 2 + 2ull * C * (n / ((uint64_t)robe::kStretch * pl.lay.G) + 1);
+        if (worst > room) return pl;
+    }
     pl.regions = true;
     robe::RegionPlan &r = pl.rp;
     r.r_shift = shift;
@@ -469,7 +508,7 @@ BwdPlan plan_backward(const robe_hash_t *h, int64_t rows, int64_t n_indices, boo
     r.lg_shift = log2u(lg);
     // measured: it pays below about eight regions per workgroup slot (1024 slots), and in the
     // reproducible mode, whose rounds are longer
-    r.fullest_first = (NR <= 8192 || g_reproducible.load(std::memory_order_relaxed)) ? 1u : 0u;
+    r.fullest_first = (NR <= 8192 || opt.reproducible) ? 1u : 0u;
     r.keep_rows = bags ? 1u : 0u;
     pl.spill_rows = (uint64_t)(512u / lg) * h->Z <= robe::kSpillFloats;
     pl.off_head = off;    off = align_up(off + n, 256);
@@ -496,7 +535,7 @@ int allow_lds(K kernel, size_t bytes, const char *what)
 }
 
 // rule 0: grad_array += scatter.  rule 1 (regions only): Adagrad on (array = dst, state) with the scatter as gradient.
-int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *grad_out, const int64_t *indices,
+int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &pl, const float *grad_out, const int64_t *indices,
                           const int64_t *offsets, int64_t n_indices, int64_t rows, uint32_t F,
                           float *grad_array, void *workspace, hipStream_t stream,
                           int rule = 0, float *state = nullptr, float lr = 0.0f, float eps = 0.0f)
@@ -531,13 +570,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
     if (int rc = check_launch("backward (keys)")) return rc;
 
     // S2: sort (key, value) pairs by the top key_bits bits of the 31-bit key
-    const char *which = getenv("ROBE_TUNE_SORT");
-    if (which && strcmp(which, "library") == 0) {
-        size_t temp = pl.temp_bytes;
-        hipError_t st = rocprim::radix_sort_pairs<TokenSortConfig>(ws + pl.off_temp, temp, keys_in, keys_out, vals_in, vals_out,
-                                                                   (size_t)n, 31 - pl.key_bits, 31, stream);
-        if (st != hipSuccess) return fail(ROBE_EHIP, "backward (sort): %s", hipGetErrorString(st));
-    } else {
+    {
         bool in_b = false;
         if (int rc = launch_radix_sort(keys_in, vals_in, keys_out, vals_out, n, 31 - pl.key_bits, 31, ws + pl.off_temp,
                                        stream, &in_b))
@@ -612,7 +645,7 @@ int launch_dedup_backward(const robe_hash_t *h, const BwdPlan &pl, const float *
                                + (pl.spill_rows ? (size_t)robe::kSpillFloats * 4 : 0);
         const int vec_ok = aligned(grad_array, 16) && (rule == 0 || aligned(state, 16)) ? 1 : 0;
         const dim3 rgrid(r.NR), rblock(robe::kReduceBlock);
-        const bool canon = g_reproducible.load(std::memory_order_relaxed) != 0;
+        const bool canon = opt.reproducible;
 #define ROBE_REDUCE_C(S_, R_, C_, P_)                                                                                 \
     do {                                                                                                              \
         if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_, C_, P_>, lds_red, "backward (reduce)")) return rc;  \
@@ -674,7 +707,7 @@ int check_rows(const robe_hash_t *h, const int64_t *indices, const int64_t *offs
 // Tables of mixed dimensions: one launch per run of consecutive tables of one dimension, each a view
 // into the [batch][n_features] inputs and the [batch][sum(dims)] rows.
 template <bool BWD>
-int launch_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *src, const int64_t *indices,
+int launch_mixed(const robe_hash_t *hash, const Opt &opt, const uint32_t *dims, const float *src, const int64_t *indices,
                         const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features, float *dst,
                         const float *rows_ptr, void *stream)
 {
@@ -702,7 +735,7 @@ int launch_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *src
         // the vector layouts need every row start of this view on a vector boundary
         const uintptr_t probe = (uintptr_t)rows_ptr | (uintptr_t)(D * 4) | (uintptr_t)(col * 4);
         const uint32_t Fv = (uint32_t)(f1 - f0);
-        if (int rc = launch_rows<BWD>(&h, src, indices, offsets, n_indices, batch * (int64_t)Fv, Fv, dst,
+        if (int rc = launch_rows<BWD>(&h, opt, src, indices, offsets, n_indices, batch * (int64_t)Fv, Fv, dst,
                                       reinterpret_cast<const void *>(probe), (hipStream_t)stream, &view))
             return rc;
         col += (int64_t)Fv * dims[f0];
@@ -764,27 +797,33 @@ int robe_offsets(const robe_hash_t *hash, const int64_t *indices, int64_t n, int
 }
 
 int robe_forward(const robe_hash_t *hash, const float *array, const int64_t *indices, const int64_t *offsets,
-                 int64_t n_indices, int64_t batch, int32_t n_features, float *out, void *stream)
+                 int64_t n_indices, int64_t batch, int32_t n_features, float *out,
+                 const robe_options_t *options, void *stream)
 {
     int64_t rows = 0;
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
     if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
     if (rows == 0) return ROBE_OK;
     if (array == nullptr) return fail(ROBE_EINVAL, "array is NULL");
     if (out == nullptr) return fail(ROBE_EINVAL, "out is NULL");
     if (!aligned(array, 4) || !aligned(out, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
-    return launch_rows<false>(hash, array, indices, offsets, n_indices, rows, (uint32_t)n_features, out, out, (hipStream_t)stream);
+    return launch_rows<false>(hash, opt, array, indices, offsets, n_indices, rows, (uint32_t)n_features, out, out, (hipStream_t)stream);
 }
 
 int robe_forward_bf16(const robe_hash_t *hash, const uint16_t *array, const int64_t *indices, const int64_t *offsets,
-                      int64_t n_indices, int64_t batch, int32_t n_features, float *out, void *stream)
+                      int64_t n_indices, int64_t batch, int32_t n_features, float *out,
+                      const robe_options_t *options, void *stream)
 {
     int64_t rows = 0;
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
     if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
     if (rows == 0) return ROBE_OK;
     if (array == nullptr) return fail(ROBE_EINVAL, "array is NULL");
     if (out == nullptr) return fail(ROBE_EINVAL, "out is NULL");
     if (!aligned(array, 2) || !aligned(out, 4)) return fail(ROBE_EINVAL, "array must be 2-byte and out 4-byte aligned");
-    return launch_rows<false, uint16_t>(hash, array, indices, offsets, n_indices, rows, (uint32_t)n_features, out, out,
+    return launch_rows<false, uint16_t>(hash, opt, array, indices, offsets, n_indices, rows, (uint32_t)n_features, out, out,
                                         (hipStream_t)stream);
 }
 
@@ -800,51 +839,74 @@ int robe_array_to_bf16(const float *src, uint16_t *dst, uint64_t n, void *stream
     return check_launch("array to bfloat16");
 }
 
-size_t robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices)
+// Shared argument checks of the two workspace queries.
+static int check_query(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices,
+                       const robe_options_t *options, size_t *bytes, Opt *opt)
 {
-    if (hash == nullptr || check_hash(hash) != ROBE_OK || batch < 0 || n_features < 1 || n_indices < 0) return 0;
-    if (batch > (int64_t)0x7FFFFFFFFFFFll / n_features) return 0;
+    if (bytes == nullptr) return fail(ROBE_EINVAL, "bytes is NULL");
+    *bytes = 0;
+    if (int rc = read_options(options, opt)) return rc;
+    if (int rc = check_hash(hash)) return rc;
+    if (batch < 0 || n_features < 1 || n_indices < 0) return fail(ROBE_EINVAL, "batch and n_indices must be >= 0 and n_features >= 1");
+    if (batch > (int64_t)0x7FFFFFFFFFFFll / n_features) return fail(ROBE_EINVAL, "batch * n_features overflows");
+    return ROBE_OK;
+}
+
+int robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices,
+                         const robe_options_t *options, size_t *bytes)
+{
+    Opt opt;
+    if (int rc = check_query(hash, batch, n_features, n_indices, options, bytes, &opt)) return rc;
     // sized for bags and for an aligned grad_out; robe_backward never needs more than this
-    const BwdPlan pl = plan_backward(hash, batch * (int64_t)n_features, n_indices, true, nullptr);
-    return pl.dedup ? pl.bytes : 0;
+    const int64_t rows = batch * (int64_t)n_features;
+    const BwdPlan pl = plan_backward(hash, opt, rows, n_indices, true, nullptr);
+    if (opt.reproducible && !pl.regions && rows > 0 && n_indices > 0) return fail_not_reproducible();
+    *bytes = pl.dedup ? pl.bytes : 0;
+    return ROBE_OK;
 }
 
 int robe_backward(const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
                   int64_t n_indices, int64_t batch, int32_t n_features, float *grad_array,
-                  void *workspace, size_t workspace_bytes, void *stream)
+                  void *workspace, size_t workspace_bytes, const robe_options_t *options, void *stream)
 {
     int64_t rows = 0;
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
     if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
-    const BwdPlan pl = plan_backward(hash, rows, n_indices, offsets != nullptr, grad_out);
+    const BwdPlan pl = plan_backward(hash, opt, rows, n_indices, offsets != nullptr, grad_out);
     if (pl.dedup) {
         if (workspace == nullptr || workspace_bytes < pl.bytes)
             return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", pl.bytes, workspace_bytes);
         if (!aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
     }
-    if (rows == 0) return ROBE_OK;
+    if (rows == 0 || n_indices == 0) return ROBE_OK;      // nothing to scatter
     if (grad_out == nullptr) return fail(ROBE_EINVAL, "grad_out is NULL");
     if (grad_array == nullptr) return fail(ROBE_EINVAL, "grad_array is NULL");
     if (!aligned(grad_out, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
-    if (g_reproducible.load(std::memory_order_relaxed) && !pl.regions) return fail_not_reproducible();
+    if (opt.reproducible && !pl.regions) return fail_not_reproducible();
     if (pl.dedup)
-        return launch_dedup_backward(hash, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
+        return launch_dedup_backward(hash, opt, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
                                       grad_array, workspace, (hipStream_t)stream);
-    return launch_rows<true>(hash, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad_array, grad_out, (hipStream_t)stream);
+    return launch_rows<true>(hash, opt, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad_array, grad_out, (hipStream_t)stream);
 }
 
 int robe_forward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *array, const int64_t *indices,
                        const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features, float *out,
-                       void *stream)
+                       const robe_options_t *options, void *stream)
 {
-    return launch_mixed<false>(hash, dims, array, indices, offsets, n_indices, batch, n_features, out, out, stream);
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
+    return launch_mixed<false>(hash, opt, dims, array, indices, offsets, n_indices, batch, n_features, out, out, stream);
 }
 
 int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out, const int64_t *indices,
                         const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features,
-                        float *grad_array, void *stream)
+                        float *grad_array, const robe_options_t *options, void *stream)
 {
-    if (g_reproducible.load(std::memory_order_relaxed)) return fail_not_reproducible();
-    return launch_mixed<true>(hash, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
+    if (opt.reproducible) return fail_not_reproducible();
+    return launch_mixed<true>(hash, opt, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
                               grad_out, stream);
 }
 
@@ -873,11 +935,6 @@ int robe_sort_pairs(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint32
         return rc;
     *result_in_b = in_b ? 1 : 0;
     return ROBE_OK;
-}
-
-int robe_set_reproducible(int on)
-{
-    return g_reproducible.exchange(on ? 1 : 0);
 }
 
 // clear_grad: leave grad_array zeroed (the entry points' contract); false for a gradient array that
@@ -922,41 +979,47 @@ int robe_sgd_update(const robe_hash_t *hash, float *array, float *grad_array, fl
     return launch_update(1, hash, array, nullptr, grad_array, lr, 0.0f, stream);
 }
 
-// The fused step uses the region-sorted scatter when it applies and is worth its dozen launches;
-// otherwise a gradient array in the workspace and the two separate steps.
-static bool fused_plan(const robe_hash_t *hash, int64_t rows, int64_t n_indices, bool bags, const void *grad_out,
-                       BwdPlan *pl, size_t *scratch_bytes)
+// The fused step uses the region-sorted scatter when it applies and is worth its launches;
+// otherwise a gradient array in the workspace and the two separate steps.  On arrays of 2^26 slots
+// or more the two-step route would fill and sweep all m slots, which alone costs more than the
+// region route's fixed part, so there the region route is taken whatever the batch size.
+static bool fused_plan(const robe_hash_t *hash, const Opt &opt, int64_t rows, int64_t n_indices, bool bags,
+                       const void *grad_out, BwdPlan *pl, size_t *scratch_bytes)
 {
     *scratch_bytes = 0;
-    // ROBE_TUNE_FUSED = regions | twostep overrides the choice (regions still needs n * d >= 2^22).
-    const char *how = getenv("ROBE_TUNE_FUSED");
-    const bool repro = g_reproducible.load(std::memory_order_relaxed) != 0;
-    const bool want = how ? strcmp(how, "regions") == 0 : regions_by_default(hash, n_indices);
-    if (repro || (want && (uint64_t)n_indices * hash->d >= (1ull << 22))) {
-        *pl = plan_backward(hash, rows, n_indices, bags, grad_out, true);
+    const bool want = opt.fused_route == ROBE_ROUTE_AUTO ? hash->m >= (1ull << 26) : opt.fused_route == ROBE_ROUTE_REGIONS;
+    if (opt.reproducible || want) {
+        *pl = plan_backward(hash, opt, rows, n_indices, bags, grad_out, true);
         if (pl->regions) return true;
     }
-    *pl = plan_backward(hash, rows, n_indices, bags, grad_out);
+    *pl = plan_backward(hash, opt, rows, n_indices, bags, grad_out);
     if (pl->regions) { pl->regions = false; }            // the two-step fallback adds onto a gradient array
     *scratch_bytes = align_up((size_t)hash->m * 4, 256);
     return false;
 }
 
-size_t robe_fused_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices)
+int robe_fused_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_features, int64_t n_indices,
+                               const robe_options_t *options, size_t *bytes)
 {
-    if (hash == nullptr || check_hash(hash) != ROBE_OK || batch < 0 || n_features < 1 || n_indices < 0) return 0;
-    if (batch > (int64_t)0x7FFFFFFFFFFFll / n_features) return 0;
+    Opt opt;
+    if (int rc = check_query(hash, batch, n_features, n_indices, options, bytes, &opt)) return rc;
     BwdPlan pl;
     size_t scratch = 0;
-    fused_plan(hash, batch * (int64_t)n_features, n_indices, true, nullptr, &pl, &scratch);
-    return scratch + ((pl.dedup || pl.regions) ? pl.bytes : 0);
+    const int64_t rows = batch * (int64_t)n_features;
+    const bool fused = fused_plan(hash, opt, rows, n_indices, true, nullptr, &pl, &scratch);
+    if (opt.reproducible && !fused && rows > 0 && n_indices > 0) return fail_not_reproducible();
+    *bytes = scratch + ((pl.dedup || pl.regions) ? pl.bytes : 0);
+    return ROBE_OK;
 }
 
 int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
                           int64_t n_indices, int64_t batch, int32_t n_features, float *array, float *state,
-                          float lr, float eps, void *workspace, size_t workspace_bytes, void *stream)
+                          float lr, float eps, void *workspace, size_t workspace_bytes,
+                          const robe_options_t *options, void *stream)
 {
     int64_t rows = 0;
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
     if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
     if (array == nullptr || state == nullptr) return fail(ROBE_EINVAL, "array or state is NULL");
     if (!std::isfinite(lr) || !std::isfinite(eps) || !(eps > 0.0f)) return fail(ROBE_EINVAL, "need finite lr and eps > 0");
@@ -966,15 +1029,15 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const 
     if (!aligned(grad_out, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
     BwdPlan pl;
     size_t scratch = 0;
-    const bool fused = fused_plan(hash, rows, n_indices, offsets != nullptr, grad_out, &pl, &scratch);
-    if (g_reproducible.load(std::memory_order_relaxed) && !fused) return fail_not_reproducible();
+    const bool fused = fused_plan(hash, opt, rows, n_indices, offsets != nullptr, grad_out, &pl, &scratch);
+    if (opt.reproducible && !fused) return fail_not_reproducible();
     const size_t need = scratch + ((pl.dedup || pl.regions) ? pl.bytes : 0);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need))
         return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     if (need > 0 && !aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     if (fused)
-        return launch_dedup_backward(hash, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
+        return launch_dedup_backward(hash, opt, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
                                      array, workspace, s, 1, state, lr, eps);
     // two steps through a gradient array at the front of the workspace
     float *grad = static_cast<float *>(workspace);
@@ -986,9 +1049,9 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const 
     char *rest = static_cast<char *>(workspace) + scratch;
     int rc;
     if (pl.dedup)
-        rc = launch_dedup_backward(hash, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, rest, s);
+        rc = launch_dedup_backward(hash, opt, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, rest, s);
     else
-        rc = launch_rows<true>(hash, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, grad_out, s);
+        rc = launch_rows<true>(hash, opt, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, grad_out, s);
     if (rc) return rc;
     return launch_update(0, hash, array, state, grad, lr, eps, stream, false);
 }

@@ -34,6 +34,8 @@ constexpr int kRowsAhead = 8;          // gradient rows a lane group requests be
 constexpr int kStretch = 8;            // stretches of G sorted positions a lane group walks in R1
 constexpr int kBinBlock = 1024;        // R2 / R4
 constexpr int kReduceBlock = 512;      // R5 (the slice arithmetic assumes 2^9)
+constexpr uint32_t kMaxRecordLanes = 64;   // lanes per record in R5: a lane group must stay inside one wavefront
+static_assert(kReduceBlock == 512 && kReduceBlock % 64 == 0, "R5: 2^9 threads, whole wavefronts");
 // Records sorted and applied per round in R5 (at most 2 per thread).  32 KB region + batch (8 bytes
 // a record, 12 with the sign term) + counters + spill-over rows stay under 40 KB: four workgroups per CU.
 template <bool SIGN>
@@ -423,10 +425,11 @@ __device__ __forceinline__ float signed_block_value(const Params &p, float v, ui
     }
 }
 
-// Class of a record among 2^shift classes: a fixed hash of its source word.
-__device__ __forceinline__ uint32_t record_class(uint32_t y, uint32_t shift)
+// Class of a record among 2^shift classes: a fixed hash of its offset and source word.  (Two records
+// that agree in both come from copies of one token in one bag and are interchangeable.)
+__device__ __forceinline__ uint32_t record_class(uint2 rec, uint32_t shift)
 {
-    return (y * 0x9E3779B1u) >> (32u - shift);
+    return ((rec.y * 0x9E3779B1u) ^ (rec.x * 0x85EBCA6Bu + 0xC2B2AE35u) * 0x27D4EB2Fu) >> (32u - shift);
 }
 
 template <bool SIGN, int RULE, bool CANON, bool SPILL>
@@ -479,9 +482,11 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
 
     // Which records go into which round must not depend on the order in which the records were
     // written (that order comes from integer atomics and changes from run to run): a region with more
-    // than one round's worth of records is split into classes by a hash of the record's source word,
-    // with as many classes as it takes for every class to fit one round.  If even kMaxClasses classes
-    // do not do it (hundreds of blocks per slot), the rounds follow the storage order instead.
+    // than one round's worth of records is split into classes by a hash of the record, with as many
+    // classes as it takes for every class to fit one round.  The host refuses reproducible calls whose
+    // regions could need more than 2^kMaxClassShift classes; should one turn up all the same (ids
+    // chosen against the hash), its slots receive NaN instead of a sum whose bits could change from
+    // run to run.
     const uint32_t count = re - rb;
     uint32_t cls_shift = 0;
     bool by_class = false;
@@ -496,7 +501,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             if (threadIdx.x == 0) *sel = 0;
             __syncthreads();
             for (uint32_t k = threadIdx.x; k < count; k += kReduceBlock)
-                atomicAdd(&hist[record_class(s.rec[rb + k].y, cls_shift)], 1u);
+                atomicAdd(&hist[record_class(s.rec[rb + k], cls_shift)], 1u);
             __syncthreads();
             for (uint32_t i = threadIdx.x; i < ncls; i += kReduceBlock)
                 if (hist[i] > (uint32_t)kRecBatch) *sel = 1;      // a class that does not fit one round
@@ -507,7 +512,12 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             }
         }
     }
-    const uint32_t rounds = by_class ? (1u << cls_shift) : (count + kRecBatch - 1u) / kRecBatch;
+    const bool poison = CANON && count > (uint32_t)kRecBatch && !by_class;
+    const uint32_t rounds = poison ? 0u : (by_class ? (1u << cls_shift) : (count + kRecBatch - 1u) / kRecBatch);
+    if (poison) {
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = __uint_as_float(0x7FC00000u);
+    }
 
     for (uint32_t round = 0; round < rounds; ++round) {
         if (threadIdx.x < groups) cnt[threadIdx.x] = 0;
@@ -519,7 +529,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             // stage this round's class in the batch area, in any order
             for (uint32_t k = threadIdx.x; k < count; k += kReduceBlock) {
                 const uint2 x = s.rec[rb + k];
-                if (record_class(x.y, cls_shift) != round) continue;
+                if (record_class(x, cls_shift) != round) continue;
                 const uint32_t at = atomicAdd(sel, 1u);
                 if (at < (uint32_t)kRecBatch) {
                     srt[at] = x;
@@ -644,6 +654,11 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
         //    Elements at or past the slice end belong to the next group's slice: they are summed in the
         //    group's own spill-over row (first element past the end first) and added in pass 3, or,
         //    when there is no room for such rows, read again in pass 3.
+        //    The read-modify-writes below are plain LDS accesses, and a group's next record may hit a
+        //    slot that another lane of the group wrote for the record before.  That is ordered because a
+        //    lane group never spans two wavefronts (LG <= 64, groups aligned to LG) and a wavefront's LDS
+        //    accesses are performed in program order for all of its lanes; the wave_barrier between
+        //    records keeps the compiler from moving one record's accesses across another's.
         const uint32_t lb = pre[grp], le = pre[grp + 1];
         if constexpr (SPILL) {
             for (uint32_t j = j0; j < p.Z; j += LG) acc[spill_at + j] = 0.0f;
@@ -689,6 +704,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                             if (a < slice_end) acc[a] += val;
                         }
                     }
+                    __builtin_amdgcn_wave_barrier();
                 }
             }
         }

@@ -78,12 +78,11 @@ def test_graph_replays_of_a_small_step_match_eager_calls(name):
 
 
 @pytest.mark.parametrize("fused", [False, True])
-def test_graph_replays_of_a_sorted_backward_match_eager_calls(fused, monkeypatch):
+def test_graph_replays_of_a_sorted_backward_match_eager_calls(fused):
     # Large enough for the sorted routes (token sort, combine, then atomics or the region route): they
     # record kernels only, so the whole training step can be captured.  Small-integer gradients make
     # the scatter exact, so every replay must reproduce the eager result bit for bit.
-    if fused:
-        monkeypatch.setenv("ROBE_TUNE_FUSED", "regions")
+    opt = robe.options(fused_route=robe.ROUTE_REGIONS)
     m, d, Z, B, F = 3_000_017, 128, 32, 12_000, 26
     h = robe.robe_init_hash(5, m, d, Z, 1)
     H = oracle.init_hash(5, m, d, Z, 1)
@@ -97,15 +96,15 @@ def test_graph_replays_of_a_sorted_backward_match_eager_calls(fused, monkeypatch
     idd = torch.zeros((B, F), dtype=torch.int64, device=DEV)
     Gd = torch.from_numpy(G).to(DEV)
     out = torch.empty((B, F, d), dtype=torch.float32, device=DEV)
-    need = max(robe.robe_workspace_bytes(h, B, F, B * F), robe.robe_fused_workspace_bytes(h, B, F, B * F))
+    need = max(robe.robe_workspace_bytes(h, B, F, B * F, opt), robe.robe_fused_workspace_bytes(h, B, F, B * F, opt))
     ws = torch.empty(need, dtype=torch.uint8, device=DEV)
 
     def step():
         robe.robe_forward(h, Md, idd, None, B, F, out=out)
         if fused:
-            robe.robe_backward_adagrad(h, Gd, idd, None, B, F, Md, st, 0.01, 1e-8, workspace=ws)
+            robe.robe_backward_adagrad(h, Gd, idd, None, B, F, Md, st, 0.01, 1e-8, workspace=ws, options=opt)
         else:
-            robe.robe_backward(h, Gd, idd, None, B, F, ga, workspace=ws)
+            robe.robe_backward(h, Gd, idd, None, B, F, ga, workspace=ws, options=opt)
             robe.robe_adagrad_update(h, Md, st, ga, 0.01, 1e-8)
 
     side = torch.cuda.Stream()

@@ -102,7 +102,7 @@ def test_mixed_with_equal_dimensions_is_the_plain_forward_bitwise():
     assert bits_equal(a, b)
 
 
-def test_mixed_rejects_bad_dimensions_and_the_reproducible_switch():
+def test_mixed_rejects_bad_dimensions_and_the_reproducible_option():
     h, _ = hashes(1, 1000, 4, 0, 16)
     ids = dev(np.zeros((2, 3), dtype=np.int64))
     M = torch.zeros(1000, dtype=torch.float32, device=DEV)
@@ -110,10 +110,7 @@ def test_mixed_rejects_bad_dimensions_and_the_reproducible_switch():
         with pytest.raises(robe.RobeError) as ei:
             robe.robe_forward_mixed(h, dims, M, ids, None, 2)
         assert ei.value.code == robe.ROBE_EINVAL
-    robe.robe_set_reproducible(True)
-    try:
-        with pytest.raises(robe.RobeError):
-            robe.robe_backward_mixed(h, [16, 4, 4], torch.zeros((2, 24), dtype=torch.float32, device=DEV), ids, None, 2, M)
-    finally:
-        robe.robe_set_reproducible(False)
+    with pytest.raises(robe.RobeError):
+        robe.robe_backward_mixed(h, [16, 4, 4], torch.zeros((2, 24), dtype=torch.float32, device=DEV), ids, None, 2, M,
+                                 options=robe.options(reproducible=1))
     assert robe.robe_forward_mixed(h, [16, 4, 4], M, dev(np.zeros((0, 3), dtype=np.int64)), None, 0).shape == (0, 24)

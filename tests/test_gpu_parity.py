@@ -31,6 +31,9 @@ def to_dev(a):
     return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
+ROUTES = {"direct": robe.ROUTE_DIRECT, "dedup": robe.ROUTE_COMBINE, "regions": robe.ROUTE_REGIONS}
+
+
 def both_hashes(seed, m, d, Z, sign):
     h = robe.robe_init_hash(seed, m, d, Z, sign)
     H = oracle.init_hash(seed, m, d, Z, sign)
@@ -150,9 +153,9 @@ def test_bag_of_one_token_equals_single_hot_bitwise():
     assert bits_equal(single.cpu().numpy(), bags.cpu().numpy())
 
 
-def check_backward(h, H, G, ids, off, B, F):
+def check_backward(h, H, G, ids, off, B, F, options=None):
     ga = torch.zeros(H.m, dtype=torch.float32, device=DEV)
-    robe.robe_backward(h, to_dev(G), to_dev(ids), to_dev(off), B, F, ga)
+    robe.robe_backward(h, to_dev(G), to_dev(ids), to_dev(off), B, F, ga, options=options)
     got = ga.cpu().numpy().astype(np.float64)
     want, S = oracle.backward(H, G, ids, off, B, F, threads=1)
     err = np.abs(got - want)
@@ -164,56 +167,56 @@ def check_backward(h, H, G, ids, off, B, F):
 @pytest.mark.parametrize("mode", ["direct", "dedup", "regions"])
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,d,Z", SHAPES[:-1])
-def test_backward_single_hot_and_bags(m, d, Z, sign, mode, monkeypatch):
-    # both scatter strategies: per-element atomics, and sort-by-destination + LDS accumulation
-    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
+def test_backward_single_hot_and_bags(m, d, Z, sign, mode):
+    # every scatter strategy: per-element atomics, duplicates combined first, and the region route
+    # (shapes a sorted route cannot take fall back to the atomics)
+    opt = robe.options(backward_route=ROUTES[mode])
     h, H = both_hashes(17 * m + Z, m, d, Z, sign)
     B, F = 23, 26
     rng = np.random.default_rng(d * 3 + Z)
     G = rng.standard_normal((B, F, d)).astype(np.float32)
     ids = rng.integers(0, 40, size=(B, F), dtype=np.int64)     # few tokens: heavy collisions
-    check_backward(h, H, G, ids, None, B, F)
+    check_backward(h, H, G, ids, None, B, F, opt)
     idsb, off = random_bags(rng, B * F, 200, 5.0, long_bag=150)
-    check_backward(h, H, G, idsb, off, B, F)
+    check_backward(h, H, G, idsb, off, B, F, opt)
     # small-integer gradients: float32 sums are exact in any order -> bit-exact scatter
     Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
-    got, want = check_backward(h, H, Gi, idsb, off, B, F)
+    got, want = check_backward(h, H, Gi, idsb, off, B, F, opt)
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("tile,xcd", [("2", "0"), ("2", "2"), ("0", "0"), ("0", "2")])
+@pytest.mark.parametrize("tile,xcd", [(2, robe.ROWS_MEMORY), (2, robe.ROWS_BY_TABLE_ALWAYS), (1, robe.ROWS_MEMORY),
+                                      (1, robe.ROWS_BY_TABLE_ALWAYS)])
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,d,Z,B,F", [(1_000_003, 128, 32, 700, 26), (100_003, 16, 4, 2048, 26), (37, 16, 8, 300, 5),
                                        (70_001, 64, 64, 129, 3), (4099, 8, 1, 1000, 7), (9973, 256, 32, 65, 2),
                                        (999_983, 2, 2, 5000, 26), (500, 1, 1, 200, 1)])
-def test_direct_single_hot_backward_with_and_without_tile_combining(m, d, Z, B, F, sign, tile, xcd, monkeypatch):
+def test_direct_single_hot_backward_with_and_without_tile_combining(m, d, Z, B, F, sign, tile, xcd):
     # the direct scatter: tiles of 64 lookups with their duplicates combined (in memory order and
     # walked table by table), and the plain one-atomic-per-element kernel; tables of 3 to 10^6 tokens
-    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", "direct")
-    monkeypatch.setenv("ROBE_TUNE_BWD_TILE", tile)
-    monkeypatch.setenv("ROBE_TUNE_XCD", xcd)
+    opt = robe.options(backward_route=robe.ROUTE_DIRECT, tile_combine=tile, row_order=xcd)
     h, H = both_hashes(29 * m + Z + sign, m, d, Z, sign)
     rng = np.random.default_rng(m + B)
     card = np.array([3, 10, 1000, 10**6] * 7)[:F]
     ids = (rng.integers(0, 2**40, size=(B, F)) % card).astype(np.int64)
     G = rng.standard_normal((B, F, d)).astype(np.float32)
-    check_backward(h, H, G, ids, None, B, F)
+    check_backward(h, H, G, ids, None, B, F, opt)
     Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
-    got, want = check_backward(h, H, Gi, ids, None, B, F)
+    got, want = check_backward(h, H, Gi, ids, None, B, F, opt)
     assert np.array_equal(got, want)
 
 
 @pytest.mark.parametrize("mode", ["direct", "dedup", "regions"])
-def test_backward_accumulates_onto_existing_values(mode, monkeypatch):
-    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
+def test_backward_accumulates_onto_existing_values(mode):
+    opt = robe.options(backward_route=ROUTES[mode])
     h, H = both_hashes(2, 50_021, 16, 4, 0)
     B, F = 8, 26
     rng = np.random.default_rng(0)
     ids = rng.integers(0, 1000, size=(B, F), dtype=np.int64)
     G = rng.integers(-2, 3, size=(B, F, 16)).astype(np.float32)
     ga = torch.full((H.m,), 5.0, dtype=torch.float32, device=DEV)
-    robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga)
-    robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga)
+    robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga, options=opt)
+    robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga, options=opt)
     want, _ = oracle.backward(H, G, ids, None, B, F)
     assert np.array_equal(ga.cpu().numpy().astype(np.float64), 5.0 + 2 * want)
 
@@ -221,14 +224,11 @@ def test_backward_accumulates_onto_existing_values(mode, monkeypatch):
 @pytest.mark.parametrize("mode,rshift", [("dedup", 0), ("regions", 0), ("regions", 10), ("regions", 15)])
 @pytest.mark.parametrize("key_bits", [31, 16, 8])
 @pytest.mark.parametrize("sign", [0, 1])
-def test_dedup_backward_hot_tokens_and_key_collisions(key_bits, sign, mode, rshift, monkeypatch):
+def test_dedup_backward_hot_tokens_and_key_collisions(key_bits, sign, mode, rshift):
     # one token repeated thousands of times (runs far longer than a lane group's stretch), a coarse
     # sort key so that distinct tokens share keys and interleave, blocks that wrap or leave their
     # region, unaligned grad_array; with float atomics and with the region-sorted scatter
-    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
-    if rshift:
-        monkeypatch.setenv("ROBE_TUNE_RSHIFT", str(rshift))
-    monkeypatch.setenv("ROBE_TUNE_KEY_BITS", str(key_bits))
+    opt = robe.options(backward_route=ROUTES[mode], region_shift=rshift, key_bits=key_bits)
     m, d, Z, B, F = 100_003, 64, 32, 301, 7
     h, H = both_hashes(31 + key_bits, m, d, Z, sign)
     rng = np.random.default_rng(key_bits)
@@ -238,13 +238,13 @@ def test_dedup_backward_hot_tokens_and_key_collisions(key_bits, sign, mode, rshi
     for shift in (0, 1):
         buf = torch.zeros(m + shift, dtype=torch.float32, device=DEV)
         ga = buf[shift:]
-        assert robe.robe_workspace_bytes(h, B, F, ids.size) > 0
-        robe.robe_backward(h, to_dev(Gi), to_dev(ids), None, B, F, ga)
+        assert robe.robe_workspace_bytes(h, B, F, ids.size, opt) > 0
+        robe.robe_backward(h, to_dev(Gi), to_dev(ids), None, B, F, ga, options=opt)
         want, _ = oracle.backward(H, Gi, ids, None, B, F)
         assert np.array_equal(ga.cpu().numpy().astype(np.float64), want)
     idsb, off = random_bags(rng, B * F, 30, 9.0, long_bag=5000)
     G = rng.standard_normal((B, F, d)).astype(np.float32)
-    check_backward(h, H, G, idsb, off, B, F)
+    check_backward(h, H, G, idsb, off, B, F, opt)
 
 
 def test_dedup_backward_needs_its_workspace():
@@ -258,10 +258,10 @@ def test_dedup_backward_needs_its_workspace():
     ga = torch.zeros(w.m, dtype=torch.float32, device=DEV)
     small = torch.empty(need // 2, dtype=torch.uint8, device=DEV)
     rc = robe.lib().robe_backward(ctypes.byref(h), G.data_ptr(), ids.data_ptr(), None, n, w.batch, w.n_features,
-                                  ga.data_ptr(), small.data_ptr(), need // 2, None)
+                                  ga.data_ptr(), small.data_ptr(), need // 2, None, None)
     assert rc == robe.ROBE_EINVAL and b"workspace" in robe.lib().robe_last_error()
     rc = robe.lib().robe_backward(ctypes.byref(h), G.data_ptr(), ids.data_ptr(), None, n, w.batch, w.n_features,
-                                  ga.data_ptr(), None, 0, None)
+                                  ga.data_ptr(), None, 0, None, None)
     assert rc == robe.ROBE_EINVAL
 
 
@@ -316,7 +316,7 @@ def test_sgd_matches_oracle_and_leaves_untouched_slots_alone(m, shift):
     assert bits_equal(Mg, Mo)
 
 
-def _check_fused(h, H, Gi, ids, off, B, F, m, shift=0):
+def _check_fused(h, H, Gi, ids, off, B, F, m, shift=0, options=None):
     """Fused backward + Adagrad against oracle.backward -> oracle.adagrad.  Small-integer gradients
     make every slot's sum exact, so both sides feed the same gradient to the update."""
     rng = np.random.default_rng(m + B)
@@ -328,7 +328,7 @@ def _check_fused(h, H, Gi, ids, off, B, F, m, shift=0):
         view.copy_(torch.from_numpy(a))
         return view
     Md, sd = dev_view(M0), dev_view(s0)
-    robe.robe_backward_adagrad(h, to_dev(Gi), to_dev(ids), to_dev(off), B, F, Md, sd, 0.01, 1e-8)
+    robe.robe_backward_adagrad(h, to_dev(Gi), to_dev(ids), to_dev(off), B, F, Md, sd, 0.01, 1e-8, options=options)
     g, _ = oracle.backward(H, Gi, ids, off, B, F)
     assert np.array_equal(g, np.round(g))
     Mo, so, go = M0.copy(), s0.copy(), g.astype(np.float32)
@@ -345,12 +345,10 @@ def _check_fused(h, H, Gi, ids, off, B, F, m, shift=0):
 @pytest.mark.parametrize("rshift", [0, 10, 15])
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,d,Z", [(1_000_003, 128, 32), (100_003, 64, 8), (1000, 64, 32), (300_007, 128, 128), (70_001, 16, 1)])
-def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift, monkeypatch):
-    # enough tokens (n * d >= 2^22) for the region-sorted path: hot tokens, long bags, blocks that
-    # leave their region or wrap, one region only (m = 1000), unaligned array and state
-    monkeypatch.setenv("ROBE_TUNE_FUSED", "regions")
-    if rshift:
-        monkeypatch.setenv("ROBE_TUNE_RSHIFT", str(rshift))
+def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift):
+    # the region-sorted path: hot tokens, long bags, blocks that leave their region or wrap, one
+    # region only (m = 1000), unaligned array and state
+    opt = robe.options(fused_route=robe.ROUTE_REGIONS, region_shift=rshift)
     h, H = both_hashes(23 * m + Z + sign, m, d, Z, sign)
     F = 26
     B = max(8, (1 << 22) // (d * F) + 3)
@@ -358,12 +356,12 @@ def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift, monkeypatch):
     ids = rng.integers(0, 4000, size=(B, F), dtype=np.int64)
     ids[rng.random((B, F)) < 0.3] = 11
     Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
-    assert robe.robe_fused_workspace_bytes(h, B, F, ids.size) > 8 * ids.size
-    _check_fused(h, H, Gi, ids, None, B, F, m)
-    _check_fused(h, H, Gi, ids, None, B, F, m, shift=1)
+    assert robe.robe_fused_workspace_bytes(h, B, F, ids.size, opt) > 8 * ids.size
+    _check_fused(h, H, Gi, ids, None, B, F, m, options=opt)
+    _check_fused(h, H, Gi, ids, None, B, F, m, shift=1, options=opt)
     Bb = max(4, B // 8)
     idsb, off = random_bags(rng, Bb * F, 3000, 8.0, long_bag=2500)
-    _check_fused(h, H, Gi[:Bb], idsb, off, Bb, F, m)
+    _check_fused(h, H, Gi[:Bb], idsb, off, Bb, F, m, options=opt)
 
 
 @pytest.mark.parametrize("sign", [0, 1])
@@ -373,19 +371,10 @@ def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift, monkeypatch):
     (1000, 64, 32, 4000, 0),             # one region, every block overlaps hundreds of others
     (300_007, 128, 128, 3000, 13),       # blocks as long as a slice
 ])
-def test_reproducible_mode_gives_the_same_bits_every_run(m, d, Z, card, rshift, sign, monkeypatch):
+def test_reproducible_mode_gives_the_same_bits_every_run(m, d, Z, card, rshift, sign):
     # No float atomics on this route and a canonical order of additions: the same call on the same
     # inputs gives the same bits, whatever order the integer atomics hand out record slots in.
-    if rshift:
-        monkeypatch.setenv("ROBE_TUNE_RSHIFT", str(rshift))
-    assert robe.robe_set_reproducible(True) is False
-    try:
-        _reproducible_case(m, d, Z, card, sign)
-    finally:
-        assert robe.robe_set_reproducible(False) is True
-
-
-def _reproducible_case(m, d, Z, card, sign):
+    opt = robe.options(reproducible=1, region_shift=rshift)
     h, H = both_hashes(5 * m + Z + sign, m, d, Z, sign)
     F = 26
     B = max(8, (1 << 22) // (d * F) + 3)
@@ -395,14 +384,14 @@ def _reproducible_case(m, d, Z, card, sign):
     G = rng.standard_normal((B, F, d)).astype(np.float32)
     M0 = rng.standard_normal(m).astype(np.float32)
     Gd, idd = to_dev(G), to_dev(ids)
-    assert robe.robe_fused_workspace_bytes(h, B, F, ids.size) > 8 * ids.size      # the sorted route is taken
-    assert robe.robe_workspace_bytes(h, B, F, ids.size) > 8 * ids.size
+    assert robe.robe_fused_workspace_bytes(h, B, F, ids.size, opt) > 8 * ids.size      # the sorted route is taken
+    assert robe.robe_workspace_bytes(h, B, F, ids.size, opt) > 8 * ids.size
     runs = []
     for _ in range(4):
         Md, sd = to_dev(M0), torch.zeros(m, dtype=torch.float32, device=DEV)
-        robe.robe_backward_adagrad(h, Gd, idd, None, B, F, Md, sd, 0.01, 1e-8)
+        robe.robe_backward_adagrad(h, Gd, idd, None, B, F, Md, sd, 0.01, 1e-8, options=opt)
         ga = torch.zeros(m, dtype=torch.float32, device=DEV)
-        robe.robe_backward(h, Gd, idd, None, B, F, ga)
+        robe.robe_backward(h, Gd, idd, None, B, F, ga, options=opt)
         runs.append((Md.cpu().numpy(), sd.cpu().numpy(), ga.cpu().numpy()))
     for Mk, sk, gk in runs[1:]:
         assert bits_equal(Mk, runs[0][0]) and bits_equal(sk, runs[0][1]) and bits_equal(gk, runs[0][2])
@@ -415,46 +404,82 @@ def _reproducible_case(m, d, Z, card, sign):
 
 
 def test_reproducible_mode_covers_small_problems_and_refuses_what_it_cannot_do():
-    robe.robe_set_reproducible(True)
-    try:
-        # a handful of tokens: still the sorted route, still the right answer, bags included
-        h, H = both_hashes(3, 5003, 16, 4, 1)
-        rng = np.random.default_rng(0)
-        B, F = 7, 5
-        ids = rng.integers(0, 50, size=(B, F), dtype=np.int64)
-        G = rng.standard_normal((B, F, 16)).astype(np.float32)
-        assert robe.robe_workspace_bytes(h, B, F, ids.size) > 0
-        outs = []
-        for _ in range(3):
-            ga = torch.zeros(5003, dtype=torch.float32, device=DEV)
-            robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga)
-            outs.append(ga.cpu().numpy())
-        assert bits_equal(outs[0], outs[1]) and bits_equal(outs[0], outs[2])
-        ref, S = oracle.backward(H, G, ids, None, B, F)
-        assert np.all(np.abs(outs[0].astype(np.float64) - ref) <= 1e-5 * S + TINY)
-        flat, off = random_bags(rng, B * F, 50, 3.0)
+    opt = robe.options(reproducible=1)
+    # a handful of tokens: still the sorted route, still the right answer, bags included
+    h, H = both_hashes(3, 5003, 16, 4, 1)
+    rng = np.random.default_rng(0)
+    B, F = 7, 5
+    ids = rng.integers(0, 50, size=(B, F), dtype=np.int64)
+    G = rng.standard_normal((B, F, 16)).astype(np.float32)
+    assert robe.robe_workspace_bytes(h, B, F, ids.size, opt) > 0
+    outs = []
+    for _ in range(3):
         ga = torch.zeros(5003, dtype=torch.float32, device=DEV)
-        robe.robe_backward(h, to_dev(G), to_dev(flat), to_dev(off), B, F, ga)
-        ref, S = oracle.backward(H, G, flat, off, B, F)
-        assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * S + TINY)
-        Md, sd = to_dev(rng.standard_normal(5003).astype(np.float32)), torch.zeros(5003, dtype=torch.float32, device=DEV)
-        robe.robe_backward_adagrad(h, to_dev(G), to_dev(flat), to_dev(off), B, F, Md, sd, 0.01, 1e-8)
-        g32 = ga.cpu().numpy()
-        assert bits_equal(sd.cpu().numpy(), g32 * g32)
-        # a block longer than the embedding has no atomic-free route: a loud error, not a silent fallback
-        h2, _ = both_hashes(4, 1000, 4, 16, 0)
-        ids2 = rng.integers(0, 99, size=(6, 3), dtype=np.int64)
-        G2 = rng.standard_normal((6, 3, 4)).astype(np.float32)
-        with pytest.raises(robe.RobeError) as ei:
-            robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV))
-        assert ei.value.code == robe.ROBE_EINVAL and "reproducible" in str(ei.value)
-        with pytest.raises(robe.RobeError):
-            robe.robe_backward_adagrad(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV),
-                                       torch.zeros(1000, dtype=torch.float32, device=DEV), 0.01, 1e-8)
-    finally:
-        robe.robe_set_reproducible(False)
-    # with the switch off the same shape runs (float atomics)
+        robe.robe_backward(h, to_dev(G), to_dev(ids), None, B, F, ga, options=opt)
+        outs.append(ga.cpu().numpy())
+    assert bits_equal(outs[0], outs[1]) and bits_equal(outs[0], outs[2])
+    ref, S = oracle.backward(H, G, ids, None, B, F)
+    assert np.all(np.abs(outs[0].astype(np.float64) - ref) <= 1e-5 * S + TINY)
+    flat, off = random_bags(rng, B * F, 50, 3.0)
+    ga = torch.zeros(5003, dtype=torch.float32, device=DEV)
+    robe.robe_backward(h, to_dev(G), to_dev(flat), to_dev(off), B, F, ga, options=opt)
+    ref, S = oracle.backward(H, G, flat, off, B, F)
+    assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * S + TINY)
+    Md, sd = to_dev(rng.standard_normal(5003).astype(np.float32)), torch.zeros(5003, dtype=torch.float32, device=DEV)
+    robe.robe_backward_adagrad(h, to_dev(G), to_dev(flat), to_dev(off), B, F, Md, sd, 0.01, 1e-8, options=opt)
+    g32 = ga.cpu().numpy()
+    assert bits_equal(sd.cpu().numpy(), g32 * g32)
+    # a block longer than the embedding has no atomic-free route: a loud error, not a silent fallback
+    h2, _ = both_hashes(4, 1000, 4, 16, 0)
+    ids2 = rng.integers(0, 99, size=(6, 3), dtype=np.int64)
+    G2 = rng.standard_normal((6, 3, 4)).astype(np.float32)
+    with pytest.raises(robe.RobeError) as ei:
+        robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV),
+                           options=opt)
+    assert ei.value.code == robe.ROBE_EINVAL and "reproducible" in str(ei.value)
+    with pytest.raises(robe.RobeError):
+        robe.robe_backward_adagrad(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV),
+                                   torch.zeros(1000, dtype=torch.float32, device=DEV), 0.01, 1e-8, options=opt)
+    # without the option the same shape runs (float atomics)
     robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV))
+
+
+@pytest.mark.parametrize("m,Z", [(8192 + 5, 32), (3 * 4096 + 20, 32), (2 * 32768 + 100, 64), (1024 * 5 + 31, 32)])
+def test_region_route_never_leaves_a_last_region_shorter_than_a_block(m, Z):
+    # With regions of 2^13 floats these arrays would end in a region of a few floats, and a block that
+    # starts in the region before it would pass through it and wrap to the start of the array.  The
+    # library must pick a region size without such a tail (or one region); small-integer gradients
+    # make the check exact.  Many tokens, so that blocks do start in the last full region's tail.
+    d, B, F = 2 * Z, 400, 26
+    for sign in (0, 1):
+        h, H = both_hashes(m + sign, m, d, Z, sign)
+        rng = np.random.default_rng(m)
+        ids = rng.integers(0, 10**6, size=(B, F), dtype=np.int64)
+        Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+        for opt in (robe.options(backward_route=robe.ROUTE_REGIONS), robe.options(reproducible=1)):
+            assert robe.robe_workspace_bytes(h, B, F, ids.size, opt) > 16 * ids.size
+            got, want = check_backward(h, H, Gi, ids, None, B, F, opt)
+            assert np.array_equal(got, want)
+        _check_fused(h, H, Gi, ids, None, B, F, m, options=robe.options(fused_route=robe.ROUTE_REGIONS))
+
+
+def test_reproducible_option_refuses_arrays_too_small_for_the_token_count():
+    # 170,000 distinct tokens on an array of one region: far more blocks per region than the
+    # canonical order handles; the call must fail, not fall back to an order that changes between runs
+    m, d, Z, B, F = 8192, 32, 8, 6600, 26
+    h, _ = both_hashes(5, m, d, Z, 0)
+    ids = to_dev(np.arange(B * F, dtype=np.int64).reshape(B, F))
+    G = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    opt = robe.options(reproducible=1)
+    with pytest.raises(robe.RobeError):
+        robe.robe_workspace_bytes(h, B, F, B * F, opt)
+    with pytest.raises(robe.RobeError) as ei:
+        robe.robe_backward(h, G, ids, None, B, F, torch.zeros(m, dtype=torch.float32, device=DEV), options=opt,
+                           workspace=torch.empty(1 << 24, dtype=torch.uint8, device=DEV))
+    assert ei.value.code == robe.ROBE_EINVAL and "reproducible" in str(ei.value)
+    # the same problem without the option, and a smaller one with it, run
+    robe.robe_backward(h, G, ids, None, B, F, torch.zeros(m, dtype=torch.float32, device=DEV))
+    robe.robe_backward(h, G[:500], ids[:500], None, 500, F, torch.zeros(m, dtype=torch.float32, device=DEV), options=opt)
 
 
 @pytest.mark.parametrize("m,d,Z,B,F", [(50_021, 16, 4, 9, 26), (4099, 12, 3, 5, 7), (1000, 4, 16, 6, 3), (100_003, 128, 32, 40, 26)])
@@ -505,54 +530,73 @@ def test_two_step_route_twice_on_one_workspace(m, d, Z, B, F, bags):
         assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(Mo) + 0.02) + TINY), step
 
 
-@pytest.mark.parametrize("env,val", [("ROBE_TUNE_FWD", "4,1"), ("ROBE_TUNE_FWD", "2,1"), ("ROBE_TUNE_FWD", "1,1"),
-                                     ("ROBE_TUNE_FWD", "4,0"), ("ROBE_TUNE_FWD", "2,0"), ("ROBE_TUNE_FWD", "0,0"),
-                                     ("ROBE_TUNE_BWD", "4,1"), ("ROBE_TUNE_BWD", "2,1"), ("ROBE_TUNE_BWD", "4,0"),
-                                     ("ROBE_TUNE_BWD", "2,0"), ("ROBE_TUNE_BWD", "0,0"), ("ROBE_TUNE_TL", "64"),
-                                     ("ROBE_TUNE_TL", "8"), ("ROBE_TUNE_XCD", "2"), ("ROBE_TUNE_XCD", "0")])
-def test_every_lane_layout_gives_the_same_result(env, val, monkeypatch):
-    # the library reads the override at call time; d = 64 makes every (V, layout) legal
-    monkeypatch.setenv(env, val)
+def _bag_forward_ok(h, H, M, idsb, off, B, F, options):
+    outb = robe.robe_forward(h, to_dev(M), to_dev(idsb), to_dev(off), B, F, options=options).cpu().numpy()
+    want = oracle.forward(H, M, idsb, off, B, F, threads=THREADS)
+    H_abs = oracle.Hash(H.m, H.d, H.Z, 0, H.P, H.coef)
+    S = oracle.forward(H_abs, np.abs(M), idsb, off, B, F, threads=THREADS).astype(np.float64)
+    err = np.abs(outb.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= 1e-5 * S + TINY), float((err / (S + TINY)).max())
+
+
+@pytest.mark.parametrize("fields", [dict(fwd_elems=4), dict(fwd_elems=2), dict(fwd_elems=1),
+                                    dict(fwd_elems=4, fwd_strided=1), dict(fwd_elems=2, fwd_strided=1), dict(fwd_elems=-1),
+                                    dict(bwd_elems=4), dict(bwd_elems=2), dict(bwd_elems=4, bwd_strided=1),
+                                    dict(bwd_elems=2, bwd_strided=1), dict(bwd_elems=-1), dict(tile_lookups=64),
+                                    dict(tile_lookups=8), dict(row_order=robe.ROWS_BY_TABLE_ALWAYS),
+                                    dict(row_order=robe.ROWS_MEMORY)])
+def test_every_lane_layout_gives_the_same_result(fields):
+    # d = 64 makes every (elements per lane, layout) legal
+    opt = robe.options(**fields)
     m, d, Z, B, F = 60_013, 64, 16, 41, 26
     for sign in (0, 1):
         h, H = both_hashes(99, m, d, Z, sign)
         rng = np.random.default_rng(5)
         ids = rng.integers(0, 3000, size=(B, F), dtype=np.int64)
         M = workloads.make_array(m, 9)
-        out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F)
+        out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F, options=opt)
         assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F, threads=THREADS))
         idsb, off = random_bags(rng, B * F, 3000, 7.0, long_bag=100)
-        outb = robe.robe_forward(h, to_dev(M), to_dev(idsb), to_dev(off), B, F).cpu().numpy()
-        np.testing.assert_allclose(outb, oracle.forward(H, M, idsb, off, B, F, threads=THREADS), rtol=0, atol=2e-6)
+        _bag_forward_ok(h, H, M, idsb, off, B, F, opt)
         Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
         for (i_, o_) in ((ids, None), (idsb, off)):
             ga = torch.zeros(m, dtype=torch.float32, device=DEV)
-            robe.robe_backward(h, to_dev(Gi), to_dev(i_), to_dev(o_), B, F, ga)
+            robe.robe_backward(h, to_dev(Gi), to_dev(i_), to_dev(o_), B, F, ga, options=opt)
             want, _ = oracle.backward(H, Gi, i_, o_, B, F)
             assert np.array_equal(ga.cpu().numpy().astype(np.float64), want)
 
 
+def test_options_that_do_not_fit_are_errors_not_silent_defaults():
+    h, _ = both_hashes(1, 10_007, 48, 16, 0)
+    M = torch.zeros(10_007, dtype=torch.float32, device=DEV)
+    ids = torch.zeros((4, 3), dtype=torch.int64, device=DEV)
+    for fields in (dict(fwd_elems=5), dict(fwd_elems=4), dict(fwd_elems=3), dict(tile_lookups=3), dict(row_order=9),
+                   dict(region_shift=9), dict(key_bits=40), dict(backward_route=7), dict(reproducible=2)):
+        with pytest.raises(robe.RobeError) as ei:      # 48 / 4 = 12 lanes, 3 consecutive: neither exists
+            robe.robe_forward(h, M, ids, None, 4, 3, options=robe.options(**fields))
+        assert ei.value.code == robe.ROBE_EINVAL, fields
+    robe.robe_forward(h, M, ids, None, 4, 3, options=robe.options(fwd_elems=3, fwd_strided=1))
+
+
 @pytest.mark.parametrize("B,F", [(1, 2), (3, 26), (37, 26), (64, 5), (1000, 3), (5, 64), (129, 1)])
-@pytest.mark.parametrize("xcd", ["0", "2"])
-def test_row_walk_orders_cover_every_row_once(B, F, xcd, monkeypatch):
+@pytest.mark.parametrize("xcd", [robe.ROWS_MEMORY, robe.ROWS_BY_TABLE_ALWAYS])
+def test_row_walk_orders_cover_every_row_once(B, F, xcd):
     # rows walked in memory order or table by table (an eighth of that order per XCD): same results,
     # for batches smaller than a tile, tables that end inside a tile, and grids padded to 8 XCDs
-    monkeypatch.setenv("ROBE_TUNE_XCD", xcd)
-    monkeypatch.setenv("ROBE_TUNE_BWD_MODE", "direct")
+    opt = robe.options(row_order=xcd, backward_route=robe.ROUTE_DIRECT)
     for (m, d, Z) in [(50_021, 128, 32), (9_973, 16, 4), (30_011, 128, 1)]:
         h, H = both_hashes(B * 131 + F, m, d, Z, 1)
         rng = np.random.default_rng(B + F)
         ids = rng.integers(0, 2000, size=(B, F), dtype=np.int64)
         M = workloads.make_array(m, 2)
-        out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F)
+        out = robe.robe_forward(h, to_dev(M), to_dev(ids), None, B, F, options=opt)
         assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F, threads=THREADS))
         idsb, off = random_bags(rng, B * F, 2000, 4.0, long_bag=70)
-        outb = robe.robe_forward(h, to_dev(M), to_dev(idsb), to_dev(off), B, F).cpu().numpy()
-        np.testing.assert_allclose(outb, oracle.forward(H, M, idsb, off, B, F, threads=THREADS), rtol=0, atol=2e-6)
+        _bag_forward_ok(h, H, M, idsb, off, B, F, opt)
         Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
         for (i_, o_) in ((ids, None), (idsb, off)):
             ga = torch.zeros(m, dtype=torch.float32, device=DEV)
-            robe.robe_backward(h, to_dev(Gi), to_dev(i_), to_dev(o_), B, F, ga)
+            robe.robe_backward(h, to_dev(Gi), to_dev(i_), to_dev(o_), B, F, ga, options=opt)
             want, _ = oracle.backward(H, Gi, i_, o_, B, F)
             assert np.array_equal(ga.cpu().numpy().astype(np.float64), want)
 
@@ -576,7 +620,7 @@ def test_empty_problems_and_all_empty_bags():
     assert not out.cpu().numpy().any() and not np.signbit(out.cpu().numpy()).any()
     robe.robe_backward(h, torch.ones((B, F, 16), device=DEV), none, off, B, F, ga)
     assert bool((ga == 2.0).all())
-    rc = robe.lib().robe_forward(ctypes.byref(h), M.data_ptr(), None, off.data_ptr(), 0, B, F, out.data_ptr(), None)
+    rc = robe.lib().robe_forward(ctypes.byref(h), M.data_ptr(), None, off.data_ptr(), 0, B, F, out.data_ptr(), None, None)
     assert rc == robe.ROBE_OK
 
 
@@ -607,12 +651,12 @@ def test_runs_on_a_side_stream_and_reports_bad_sizes():
     s.synchronize()
     assert bits_equal(out.cpu().numpy(), oracle.forward(H, M, ids, None, B, F))
     rc = robe.lib().robe_forward(ctypes.byref(h), Md.data_ptr(), idd.data_ptr(), None,
-                                 B * F + 1, B, F, out.data_ptr(), None)
+                                 B * F + 1, B, F, out.data_ptr(), None, None)
     assert rc == robe.ROBE_EINVAL and b"n_indices" in robe.lib().robe_last_error()
 
 
 @pytest.mark.parametrize("m,modes", [(2**30, ("direct", "dedup", "regions")), (2**31 - 1, ("direct", "dedup"))])
-def test_backward_on_the_largest_arrays(m, modes, monkeypatch):
+def test_backward_on_the_largest_arrays(m, modes):
     # 2^30 slots is the largest array the region-sorted route takes (32768 regions of 2^15 floats),
     # 2^31 - 1 the largest array at all; small-integer gradients make every route exact
     d, Z, B, F = 128, 32, 2048, 26
@@ -628,17 +672,16 @@ def test_backward_on_the_largest_arrays(m, modes, monkeypatch):
     nz = np.flatnonzero(ref)
     Gd, idd, offd = to_dev(G), to_dev(ids), to_dev(off)
     for mode in modes:
-        monkeypatch.setenv("ROBE_TUNE_BWD_MODE", mode)
+        opt = robe.options(backward_route=ROUTES[mode], fused_route=robe.ROUTE_REGIONS)
         ga = torch.zeros(m, dtype=torch.float32, device=DEV)
-        robe.robe_backward(h, Gd, idd, offd, B, F, ga)
+        robe.robe_backward(h, Gd, idd, offd, B, F, ga, options=opt)
         assert int(torch.count_nonzero(ga).item()) == nz.size, mode
         assert np.array_equal(ga[torch.from_numpy(nz).to(DEV)].cpu().numpy().astype(np.float64), ref[nz]), mode
         del ga
         if mode == "regions":
-            monkeypatch.setenv("ROBE_TUNE_FUSED", "regions")
             Md = torch.zeros(m, dtype=torch.float32, device=DEV)
             sd = torch.zeros(m, dtype=torch.float32, device=DEV)
-            robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Md, sd, 0.01, 1e-8)
+            robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Md, sd, 0.01, 1e-8, options=opt)
             assert int(torch.count_nonzero(sd).item()) == nz.size
             got_s = sd[torch.from_numpy(nz).to(DEV)].cpu().numpy()
             assert np.array_equal(got_s, ref[nz].astype(np.float32) ** 2)

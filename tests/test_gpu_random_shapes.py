@@ -58,13 +58,14 @@ def draw_ids(rng, n):
 
 
 @pytest.mark.parametrize("chunk", range(8))
-def test_random_problems_match_the_oracle(chunk, monkeypatch):
+def test_random_problems_match_the_oracle(chunk):
     rng = np.random.default_rng(1000 + chunk)
     for case in range(12):
         m, d, Z, B, F, sign = draw_case(rng)
-        monkeypatch.setenv("ROBE_TUNE_XCD", str(int(rng.choice([0, 2]))))
-        monkeypatch.setenv("ROBE_TUNE_BWD_MODE", str(rng.choice(["direct", "dedup", "regions"])))
-        monkeypatch.setenv("ROBE_TUNE_BWD_TILE", str(rng.choice(["0", "2"])))
+        opt = robe.options(row_order=int(rng.choice([robe.ROWS_MEMORY, robe.ROWS_BY_TABLE_ALWAYS])),
+                           backward_route=int(rng.choice([robe.ROUTE_DIRECT, robe.ROUTE_COMBINE, robe.ROUTE_REGIONS])),
+                           tile_combine=int(rng.choice([1, 2])))
+        repro = robe.options(reproducible=1)
         tag = f"chunk {chunk} case {case}: m={m} d={d} Z={Z} B={B} F={F} sign={sign}"
         print(tag, flush=True)
         seed = int(rng.integers(0, 2**63))
@@ -75,7 +76,7 @@ def test_random_problems_match_the_oracle(chunk, monkeypatch):
         rows = B * F
         # single-hot
         ids = draw_ids(rng, rows).reshape(B, F)
-        out = robe.robe_forward(h, dev(M), dev(ids), None, B, F).cpu().numpy()
+        out = robe.robe_forward(h, dev(M), dev(ids), None, B, F, options=opt).cpu().numpy()
         want = oracle.forward(H, M, ids, None, B, F, threads=THREADS)
         assert np.array_equal(out.view(np.int32), want.view(np.int32)), tag
         # bags
@@ -85,7 +86,7 @@ def test_random_problems_match_the_oracle(chunk, monkeypatch):
         off = np.zeros(rows + 1, dtype=np.int64)
         np.cumsum(sizes, out=off[1:])
         idsb = draw_ids(rng, int(off[-1]))
-        outb = robe.robe_forward(h, dev(M), dev(idsb), dev(off), B, F).cpu().numpy()
+        outb = robe.robe_forward(h, dev(M), dev(idsb), dev(off), B, F, options=opt).cpu().numpy()
         wantb = oracle.forward(H, M, idsb, off, B, F, threads=THREADS)
         H_abs = oracle.Hash(H.m, H.d, H.Z, 0, H.P, H.coef)
         S = oracle.forward(H_abs, np.abs(M), idsb, off, B, F, threads=THREADS).astype(np.float64)
@@ -94,22 +95,18 @@ def test_random_problems_match_the_oracle(chunk, monkeypatch):
         Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
         for (i_, o_) in ((ids, None), (idsb, off)):
             ga = torch.zeros(m, dtype=torch.float32, device=DEV)
-            robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, ga)
+            robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, ga, options=opt)
             ref, _ = oracle.backward(H, Gi, i_, o_, B, F, threads=1)
             assert np.array_equal(ga.cpu().numpy().astype(np.float64), ref), tag
-            # the same call in reproducible mode gives the same sums (exact here) when it has a route
+            # the same call with the reproducible option gives the same sums (exact here) when it has a route
             if Z <= d:
-                robe.robe_set_reproducible(True)
+                gr = torch.zeros(m, dtype=torch.float32, device=DEV)
                 try:
-                    gr = torch.zeros(m, dtype=torch.float32, device=DEV)
-                    try:
-                        robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, gr)
-                    except robe.RobeError as e:
-                        assert "reproducible" in str(e), tag      # shapes without an atomic-free route
-                    else:
-                        assert np.array_equal(gr.cpu().numpy().astype(np.float64), ref), tag
-                finally:
-                    robe.robe_set_reproducible(False)
+                    robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, gr, options=repro)
+                except robe.RobeError as e:
+                    assert "reproducible" in str(e), tag      # shapes without an atomic-free route
+                else:
+                    assert np.array_equal(gr.cpu().numpy().astype(np.float64), ref), tag
         # bfloat16 array: single-hot bit-exact
         Mb = oracle.to_bf16(M)
         outq = robe.robe_forward_bf16(h, dev(Mb.view(np.int16)), dev(ids), None, B, F).cpu().numpy()
@@ -120,11 +117,11 @@ def test_random_problems_match_the_oracle(chunk, monkeypatch):
             dims = [int(Z * rng.integers(1, 5)) for _ in range(F)]
             if F > 2:
                 dims[1] = dims[0]                                     # a run of equal dimensions
-            outm = robe.robe_forward_mixed(h, dims, dev(M), dev(ids), None, B).cpu().numpy()
+            outm = robe.robe_forward_mixed(h, dims, dev(M), dev(ids), None, B, options=opt).cpu().numpy()
             wantm = oracle.forward_mixed(H, dims, M, ids, None, B)
             assert np.array_equal(outm.view(np.int32), wantm.view(np.int32)), tag
             Gm = rng.integers(-3, 4, size=(B, sum(dims))).astype(np.float32)
             gm = torch.zeros(m, dtype=torch.float32, device=DEV)
-            robe.robe_backward_mixed(h, dims, dev(Gm), dev(idsb), dev(off), B, gm)
+            robe.robe_backward_mixed(h, dims, dev(Gm), dev(idsb), dev(off), B, gm, options=opt)
             refm, _ = oracle.backward_mixed(H, dims, Gm, idsb, off, B)
             assert np.array_equal(gm.cpu().numpy().astype(np.float64), refm), tag

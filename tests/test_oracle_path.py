@@ -201,6 +201,26 @@ def test_backward_threads_do_not_change_the_result_beyond_rounding():
     np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-12)
 
 
+def test_forward_threads_give_the_same_bits_as_the_sequential_loop():
+    # the full-size GPU comparisons use the threaded oracle: rows are independent, so the split over
+    # threads must not change a single bit (single-hot and bags, sign on and off, a ragged row count)
+    rng = np.random.default_rng(3)
+    for sign in (0, 1):
+        H = oracle.init_hash(7 + sign, 5003, 16, 4, sign)
+        M = rng.standard_normal(5003).astype(np.float32)
+        M[::5] = -0.0
+        ids = rng.integers(0, 300, size=(67, 5))
+        a = oracle.forward(H, M, ids, None, 67, 5, threads=1)
+        for t in (2, 4, 7):
+            b = oracle.forward(H, M, ids, None, 67, 5, threads=t)
+            assert np.array_equal(a.view(np.int32), b.view(np.int32)), (sign, t)
+        idsb, off = _random_bags(rng, 67 * 5, 300)
+        a = oracle.forward(H, M, idsb, off, 67, 5, threads=1)
+        for t in (2, 4, 7):
+            b = oracle.forward(H, M, idsb, off, 67, 5, threads=t)
+            assert np.array_equal(a.view(np.int32), b.view(np.int32)), (sign, t)
+
+
 def test_adagrad_matches_torch_cpu_and_touches_only_nonzero_gradients():
     rng = np.random.default_rng(0)
     n = 4096
