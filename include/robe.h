@@ -236,6 +236,26 @@ int robe_backward(const robe_hash_t *hash, const float *grad_out,
                   const robe_options_t *options, void *stream);
 
 /*
+ * robe_backward for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, result
+ * and routes as robe_backward, but the workspace is a buffer built into the library: a fixed
+ * robe_noalloc_max_workspace_bytes() = 32 MiB of device memory per GPU, present from the moment the
+ * library is loaded until the process ends.  The call allocates and frees nothing (no hipMalloc, no
+ * library routine that allocates); its first use on a device looks the buffer's address up once.
+ * A problem whose workspace (robe_workspace_bytes with the same options) exceeds the buffer fails with
+ * ROBE_EINVAL and launches nothing; problems that scatter directly need no workspace and have no
+ * size limit.  The buffer holds nothing between calls that a call relies on.  All calls on one GPU
+ * share it: two such calls that overlap in time on one GPU (different streams, or different threads)
+ * race and give wrong results - order them on one stream or with events.
+ * Errors: as robe_backward, plus ROBE_EHIP if the buffer's address cannot be obtained.
+ */
+size_t robe_noalloc_max_workspace_bytes(void);
+int robe_backward_noalloc(const robe_hash_t *hash, const float *grad_out,
+                          const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                          int64_t batch, int32_t n_features, float *grad_array,
+                          const robe_options_t *options, void *stream);
+
+/*
  * Sparse Adagrad step on the touched slots (Duchi, Hazan, Singer 2011; the
  * optimizer is named by the workload, not by the paper).  For every j with
  * grad_array[j] != 0, in float32 with each operation rounded on its own:

@@ -60,7 +60,7 @@ ROWS_AUTO, ROWS_MEMORY, ROWS_BY_TABLE, ROWS_BY_TABLE_ALWAYS = 0, 1, 2, 3
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
            "robe_forward_mixed", "robe_backward_mixed", "robe_array_to_bf16", "robe_forward_bf16",
-           "robe_sort_workspace_bytes", "robe_sort_pairs",
+           "robe_sort_workspace_bytes", "robe_sort_pairs", "robe_noalloc_max_workspace_bytes", "robe_backward_noalloc",
            "robe_last_error")
 
 _lib = None
@@ -88,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.robe_workspace_bytes.argtypes = [HP, i64, i32, i64, OP, szp]
         L.robe_backward.restype = ctypes.c_int
         L.robe_backward.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_size_t, OP, vp]
+        L.robe_noalloc_max_workspace_bytes.restype = ctypes.c_size_t
+        L.robe_noalloc_max_workspace_bytes.argtypes = []
+        L.robe_backward_noalloc.restype = ctypes.c_int
+        L.robe_backward_noalloc.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, OP, vp]
         L.robe_adagrad_update.restype = ctypes.c_int
         L.robe_adagrad_update.argtypes = [HP, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp]
         L.robe_sgd_update.restype = ctypes.c_int
@@ -210,6 +214,23 @@ def robe_backward(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, of
                                _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                indices.numel(), batch, n_features, _dev(grad_array, torch.float32, "grad_array"),
                                ws_ptr, ws_len, _opt(options), _stream()))
+    return grad_array
+
+
+def robe_backward_noalloc(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                          batch: int, n_features: int, grad_array: torch.Tensor,
+                          options: Optional[RobeOptions] = None) -> torch.Tensor:
+    """robe_backward on the library's built-in workspace: nothing is allocated, here or in the library."""
+    if grad_array.numel() != h.m:
+        raise ValueError("grad_array length differs from hash.m")
+    if grad_out.numel() != batch * n_features * h.d:
+        raise ValueError("grad_out has the wrong size")
+    if offsets is not None and offsets.numel() != batch * n_features + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    _check(lib().robe_backward_noalloc(ctypes.byref(h), _dev(grad_out, torch.float32, "grad_out"),
+                                       _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                                       indices.numel(), batch, n_features, _dev(grad_array, torch.float32, "grad_array"),
+                                       _opt(options), _stream()))
     return grad_array
 
 

@@ -13,12 +13,18 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/robe.h"
 #include "robe_kernels.h"
 #include "robe_backward_dedup.h"
 #include "robe_backward_regions.h"
 #include "robe_radix_sort.h"
+
+// Workspace of robe_backward_noalloc: device memory that exists from the moment the library is
+// loaded, one copy per GPU, so that the call itself allocates nothing.
+#define ROBE_STATIC_SCRATCH_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char scratch[ROBE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -908,6 +914,49 @@ int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const flo
     if (opt.reproducible) return fail_not_reproducible();
     return launch_mixed<true>(hash, opt, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
                               grad_out, stream);
+}
+
+// The address of `scratch` on the current device.  In host code the array's name is only a handle
+// for the symbol: the device address comes from hipGetSymbolAddress, once per device, and every
+// later use goes through the pointer kept here.
+static int static_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void *ptr_of_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t st = hipGetDevice(&dev);
+    if (st != hipSuccess) return fail(ROBE_EHIP, "hipGetDevice: %s", hipGetErrorString(st));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ROBE_EINVAL, "device %d: at most %d devices are supported", dev, kMaxDevices);
+    std::lock_guard<std::mutex> hold(lock);
+    if (ptr_of_device[dev] == nullptr) {
+        void *ptr = nullptr;
+        st = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (st != hipSuccess || ptr == nullptr)
+            return fail(ROBE_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(st));
+        ptr_of_device[dev] = ptr;
+    }
+    *out = ptr_of_device[dev];
+    return ROBE_OK;
+}
+
+size_t robe_noalloc_max_workspace_bytes(void) { return (size_t)ROBE_STATIC_SCRATCH_BYTES; }
+
+int robe_backward_noalloc(const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
+                          int64_t n_indices, int64_t batch, int32_t n_features, float *grad_array,
+                          const robe_options_t *options, void *stream)
+{
+    size_t need = 0;
+    if (int rc = robe_workspace_bytes(hash, batch, n_features, n_indices, options, &need)) return rc;
+    if (need > (size_t)ROBE_STATIC_SCRATCH_BYTES)
+        return fail(ROBE_EINVAL, "robe_backward_noalloc: this problem needs a workspace of %zu bytes, the built-in one holds %zu; "
+                                 "use robe_backward with a workspace of your own, or ROBE_ROUTE_DIRECT",
+                    need, (size_t)ROBE_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (need > 0)
+        if (int rc = static_scratch(&ws)) return rc;
+    return robe_backward(hash, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
+                         ws, need > 0 ? (size_t)ROBE_STATIC_SCRATCH_BYTES : 0, options, stream);
 }
 
 size_t robe_sort_workspace_bytes(uint64_t n)
