@@ -393,12 +393,13 @@ struct BwdPlan {
     bool dedup;          // sort the tokens and combine identical ones
     bool regions;        // ... and then sort the blocks by destination region instead of using float atomics
     bool spill_rows;     // ... with room in LDS for a row of Z floats per lane group of the reduce kernel
+    bool gather;         // ... and the reduce kernel finds its blocks in the sorted token list (no record kernels)
     Layout lay;
     uint32_t key_bits;   // most significant key bits the sort looks at
     size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_tok_bag, off_temp, temp_bytes, bytes;
     // regions only
     robe::RegionPlan rp;
-    size_t off_head, off_src_row, off_run_tg, off_P, off_counts, off_starts, off_wg_first, off_rec, off_rec_tg;
+    size_t off_head, off_src_row, off_run_tg, off_P, off_counts, off_starts, off_wg_first, off_rec, off_rec_tg, off_dir;
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -418,22 +419,21 @@ int fail_not_reproducible()
                              "32-bit record counts and a region size that leaves no short last region)");
 }
 
-// Region size for the region-sorted scatter: 2^shift floats.  A region must hold two blocks, the
-// array at most kMaxRegions regions, and the last region must be full or at least Z floats long (a
-// block that starts in the region before it must end inside it).  0: no size fits.
+// Region size for the region-sorted scatter with record kernels: 2^shift floats.  A region must hold
+// two blocks and the array at most kMaxRegions regions.  0: no size fits.
 uint32_t pick_region_shift(const robe_hash_t *h, int requested)
 {
     auto fits = [&](uint32_t shift) {
-        const uint64_t R = 1ull << shift, NR = (h->m + R - 1) >> shift, last = h->m - ((NR - 1) << shift);
-        return NR <= robe::kMaxRegions && R >= 2ull * h->Z && (NR == 1 || last == R || last >= h->Z);
+        const uint64_t R = 1ull << shift, NR = (h->m + R - 1) >> shift;
+        return NR <= robe::kMaxRegions && R >= 2ull * h->Z;
     };
     if (requested) return fits((uint32_t)requested) ? (uint32_t)requested : 0u;
     for (uint32_t shift = 13; shift <= 15; ++shift)
         if (fits(shift)) return shift;
-    for (uint32_t shift = 12; shift >= 10; --shift)
-        if (fits(shift)) return shift;
     return 0;
 }
+
+uint32_t ceil_log2(uint64_t v) { uint32_t s = 0; while ((1ull << s) < v) ++s; return s; }
 
 // Decide between the direct scatter, the combine-duplicates one and the region-sorted one, and lay
 // out the workspace.  Host arithmetic only, so that the workspace queries and the calls agree.
@@ -464,8 +464,8 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
     const size_t temp = radix_sort_temp_bytes(n);
     pl.dedup = true;
     size_t off = 0;
-    pl.off_keys_in = off;  off = align_up(off + n * 4, 256);
-    pl.off_keys_out = off; off = align_up(off + n * 4, 256);
+    pl.off_keys_in = off;  off = align_up(off + (n + 8) * 4, 256);
+    pl.off_keys_out = off; off = align_up(off + (n + 8) * 4, 256);
     pl.off_vals_in = off;  off = align_up(off + n * 4, 256);
     pl.off_vals_out = off; off = align_up(off + n * 4, 256);
     pl.off_tok_bag = off;  if (bags && h->use_sign) off = align_up(off + n * 4, 256);   // sign off: the sorted value is the row
@@ -477,23 +477,55 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
     const bool want_regions = need_regions || (route == ROBE_ROUTE_AUTO ? regions_by_default(h, n_indices) : route == ROBE_ROUTE_REGIONS);
     if (!want_regions) return pl;
     const uint64_t C = h->d / h->Z;                       // Z <= d here (lay.V != 0)
-    const uint32_t shift = pick_region_shift(h, opt.region_shift);
-    if (shift == 0) return pl;
-    const uint64_t NR = (h->m + (1ull << shift) - 1) >> shift;
     uint32_t lg = 8;  // lanes per record in the reduce kernel: at most 64 groups per workgroup, a group inside one wavefront
     while (lg < robe::kMaxRecordLanes && lg < h->Z) lg <<= 1;
     static_assert(robe::kMaxRecordLanes <= 64 && (robe::kMaxRecordLanes & (robe::kMaxRecordLanes - 1)) == 0,
                   "a lane group of the reduce kernel is a power of two and never spans two wavefronts");
     const uint32_t grp_shift = 9 - log2u(lg);
-    const uint64_t p_rows = (n + 1) / 2;
-    if (shift < grp_shift || (1u << (shift - grp_shift)) < h->Z ||               // a slice of the region must hold one block
-        ((uint64_t)rows + p_rows) * C >= 0x7FFFFFFFull || 2ull * n * C >= 0xFFFFFFFFull)
-        return pl;
-    // The reproducible order splits an overfull region into at most 2^kMaxClassShift classes of at most
-    // one round's records each.  Refuse what could come near that: one and a half times the average
-    // region (hashed offsets spread evenly; a block in Z / R leaves a second record), plus every run of
-    // the most frequent token (one per kStretch * G copies) in one region, against six tenths of the room.
-    if (opt.reproducible) {
+    // rows of P: an eighth of the positions a lane group of the combine kernel walks, for every group
+    // (a group that meets more runs of repeated tokens than that leaves the rest uncombined; on the
+    // Zipf-distributed bags of the benchmark a walk of 512 positions holds 26 such runs on average
+    // and 60 at most)
+    const uint64_t walk = (uint64_t)robe::kStretch * pl.lay.G;
+    const uint32_t p_quota = walk / 8 ? (uint32_t)(walk / 8) : 1u;
+    const uint64_t combine_blocks = (n + (uint64_t)robe::kBlock * robe::kStretch - 1) / ((uint64_t)robe::kBlock * robe::kStretch);
+    const uint64_t p_rows = combine_blocks * (robe::kBlock / pl.lay.G) * p_quota;
+    if (((uint64_t)rows + p_rows) * C >= 0x7FFFFFFFull) return pl;       // 31-bit source block numbers
+
+    // Gather variant: the reduce kernel reads the sorted token list through a range table of
+    // C * ((P - 1) / m + 3) entries, which must fit its LDS: large arrays, few chunks per embedding.
+    // No record kernels, no record storage, any number of regions.  Taken by default where the region
+    // route is (arrays of 2^26 slots or more); options->region_records forces either variant.
+    uint32_t shift = 0;
+    {
+        const uint32_t gshift = opt.region_shift ? (uint32_t)opt.region_shift : 13u;
+        const uint64_t R = 1ull << gshift, kmax = ((uint64_t)ROBE_PRIME - 1) / h->m, NE = C * (kmax + 3);
+        const uint32_t cap = h->use_sign ? robe::gather_entries_max<true>() : robe::gather_entries_max<false>();
+        const bool can = R >= 2ull * h->Z && h->m >= R + h->Z && NE <= cap && gshift >= grp_shift &&
+                         (1u << (gshift - grp_shift)) >= h->Z && ((h->m + R - 1) >> gshift) <= 0x7FFFFFFFull;
+        const bool want = opt.region_records == 2 || (opt.region_records == 0 && h->m >= (1ull << 26));
+        if (can && want) {
+            pl.gather = true;
+            shift = gshift;
+        }
+    }
+    if (!pl.gather) {
+        shift = pick_region_shift(h, opt.region_shift);
+        if (shift == 0 || shift < grp_shift || (1u << (shift - grp_shift)) < h->Z) return pl;   // a slice of the region must hold one block
+    }
+    const uint64_t NR = (h->m + (1ull << shift) - 1) >> shift;
+    // record kernels: a block leaves at most one more record, two when the array ends in a region
+    // shorter than a block (a block can pass through it and go on at slot 0)
+    const uint64_t last_len = h->m - ((NR - 1) << shift);
+    const uint64_t rec_per_block = (NR > 1 && last_len < h->Z) ? 3 : 2;
+    if (!pl.gather && rec_per_block * n * C >= 0xFFFFFFFFull) return pl;
+    // The reproducible order of the record kernels splits an overfull region into at most
+    // 2^kMaxClassShift classes of at most one round's records each.  Refuse what could come near that:
+    // one and a half times the average region (hashed offsets spread evenly; a block in Z / R leaves a
+    // second record), plus every run of the most frequent token (one per kStretch * G copies) in one
+    // region, against six tenths of the room.  (The gather variant stages its records in an order
+    // that is fixed by the sorted list and needs no such split.)
+    if (opt.reproducible && !pl.gather) {
         const uint64_t batch = h->use_sign ? robe::rec_batch<true>() : robe::rec_batch<false>();
         const uint64_t room = ((batch << robe::kMaxClassShift) * 6) / 10;
         const uint64_t R = 1ull << shift, span = R < h->m ? R : h->m;
@@ -508,6 +540,7 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
     r.n = (uint32_t)n;
     r.rows = (uint32_t)rows;
     r.src_blocks = (uint32_t)(((uint64_t)rows + p_rows) * C);
+    r.p_quota = p_quota;
     r.bin_blocks = NR * 4 > 80 * 1024 ? 256u : 512u;      // one or two workgroups per CU by LDS
     if (n < (size_t)r.bin_blocks * 1024) r.bin_blocks = (uint32_t)((n + 1023) / 1024);
     r.pos_per_block = (uint32_t)((n + r.bin_blocks - 1) / r.bin_blocks);
@@ -517,16 +550,31 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
     r.fullest_first = (NR <= 8192 || opt.reproducible) ? 1u : 0u;
     r.keep_rows = bags ? 1u : 0u;
     pl.spill_rows = (uint64_t)(512u / lg) * h->Z <= robe::kSpillFloats;
-    pl.off_head = off;    off = align_up(off + n, 256);
-    pl.off_src_row = off; off = align_up(off + n * 4, 256);
-    pl.off_run_tg = off;  if (h->use_sign) off = align_up(off + n * 4, 256);
+    // (the reduce kernel of the gather variant reads keys, src_row and run_tg eight positions at a
+    // time: every such array is padded to whole chunks)
+    pl.off_head = off;    if (!pl.gather) off = align_up(off + n, 256);
+    pl.off_src_row = off; off = align_up(off + (n + 8) * 4, 256);
+    pl.off_run_tg = off;  if (h->use_sign) off = align_up(off + (n + 8) * 4, 256);
     pl.off_P = off;       off = align_up(off + p_rows * h->d * 4, 256);
-    pl.off_counts = off;  off = align_up(off + NR * 4, 256);
-    pl.off_starts = off;  off = align_up(off + (NR + 1) * 4, 256);
-    pl.off_wg_first = off; off = align_up(off + (size_t)r.bin_blocks * NR * 4, 256);
-    pl.off_rec = off;     off = align_up(off + 2 * n * C * 8, 256);
-    pl.off_rec_tg = off;  if (h->use_sign) off = align_up(off + 2 * n * C * 4, 256);
-    pl.bytes = off;
+    if (pl.gather) {
+        // directory buckets: about two sorted positions each, never finer than what the sort looked at
+        uint32_t bits = ceil_log2(n) > 1 ? ceil_log2(n) - 1 : 1;
+        if (bits > 22) bits = 22;
+        if (bits > pl.key_bits) bits = pl.key_bits;
+        r.dir_shift = 31 - bits;
+        r.dir_buckets = 1u << bits;
+        r.epc = (uint32_t)(((uint64_t)ROBE_PRIME - 1) / h->m + 3);
+        r.NE = (uint32_t)(C * r.epc);
+        r.epc_recip = (65536u + r.epc - 1) / r.epc;
+        pl.off_dir = off;  off = align_up(off + ((size_t)r.dir_buckets + 1) * 4, 256);
+    } else {
+        pl.off_counts = off;  off = align_up(off + NR * 4, 256);
+        pl.off_starts = off;  off = align_up(off + (NR + 1) * 4, 256);
+        pl.off_wg_first = off; off = align_up(off + (size_t)r.bin_blocks * NR * 4, 256);
+        pl.off_rec = off;     off = align_up(off + rec_per_block * n * C * 8, 256);
+        pl.off_rec_tg = off;  if (h->use_sign) off = align_up(off + rec_per_block * n * C * 4, 256);
+    }
+    pl.bytes = off + 256;      // (slack: the padded reads above never leave the workspace)
     return pl;
 }
 
@@ -600,15 +648,22 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         robe::RegionPlan r = pl.rp;
         r.keys = keys_out;
         r.keep_array = (rule == 1 && h->m <= kKeepArrayMax) ? 1u : 0u;
-        r.head = reinterpret_cast<uint8_t *>(ws + pl.off_head);
+        r.head = pl.gather ? nullptr : reinterpret_cast<uint8_t *>(ws + pl.off_head);
         r.src_row = reinterpret_cast<uint32_t *>(ws + pl.off_src_row);
         r.run_tg = reinterpret_cast<uint32_t *>(ws + pl.off_run_tg);
         r.P = reinterpret_cast<float *>(ws + pl.off_P);
-        r.counts = reinterpret_cast<uint32_t *>(ws + pl.off_counts);
-        r.starts = reinterpret_cast<uint32_t *>(ws + pl.off_starts);
-        r.wg_first = reinterpret_cast<uint32_t *>(ws + pl.off_wg_first);
-        r.rec = reinterpret_cast<uint2 *>(ws + pl.off_rec);
-        r.rec_tg = reinterpret_cast<uint32_t *>(ws + pl.off_rec_tg);
+        if (pl.gather) {
+            r.dir = reinterpret_cast<uint32_t *>(ws + pl.off_dir);
+            r.counts = r.starts = r.wg_first = r.rec_tg = nullptr;
+            r.rec = nullptr;
+        } else {
+            r.dir = nullptr;
+            r.counts = reinterpret_cast<uint32_t *>(ws + pl.off_counts);
+            r.starts = reinterpret_cast<uint32_t *>(ws + pl.off_starts);
+            r.wg_first = reinterpret_cast<uint32_t *>(ws + pl.off_wg_first);
+            r.rec = reinterpret_cast<uint2 *>(ws + pl.off_rec);
+            r.rec_tg = reinterpret_cast<uint32_t *>(ws + pl.off_rec_tg);
+        }
 
         // R1: combine runs into P, leave one record per run (a lane group walks kStretch * G positions)
         const dim3 rgrid1((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * robe::kStretch - 1) / ((uint64_t)robe::kBlock * robe::kStretch)));
@@ -630,32 +685,38 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
 #undef ROBE_COMBINE_ROWS
         if (int rc = check_launch("backward (combine rows)")) return rc;
 
-        // R2..R4: records sorted by region
-        const size_t lds_bin = (size_t)r.NR * 4;
-        if (int rc = allow_lds(robe::region_bin_kernel<false, false>, lds_bin, "backward (count)")) return rc;
-        robe::region_bin_kernel<false, false><<<dim3(r.bin_blocks), dim3(robe::kBinBlock), lds_bin, stream>>>(p, r);
-        if (int rc = check_launch("backward (count)")) return rc;
-        robe::region_scan_kernel<<<dim3(1), dim3(1024), 0, stream>>>(r);
-        if (int rc = check_launch("backward (scan)")) return rc;
-        if (sign) {
-            if (int rc = allow_lds(robe::region_bin_kernel<true, true>, lds_bin, "backward (records)")) return rc;
-            robe::region_bin_kernel<true, true><<<dim3(r.bin_blocks), dim3(robe::kBinBlock), lds_bin, stream>>>(p, r);
-        } else {
-            if (int rc = allow_lds(robe::region_bin_kernel<false, true>, lds_bin, "backward (records)")) return rc;
-            robe::region_bin_kernel<false, true><<<dim3(r.bin_blocks), dim3(robe::kBinBlock), lds_bin, stream>>>(p, r);
+        // R2..R4: records sorted by region (the gather variant of R5 does without)
+        if (!pl.gather) {
+            const size_t lds_bin = (size_t)r.NR * 4;
+            if (int rc = allow_lds(robe::region_bin_kernel<false, false>, lds_bin, "backward (count)")) return rc;
+            robe::region_bin_kernel<false, false><<<dim3(r.bin_blocks), dim3(robe::kBinBlock), lds_bin, stream>>>(p, r);
+            if (int rc = check_launch("backward (count)")) return rc;
+            robe::region_scan_kernel<<<dim3(1), dim3(1024), 0, stream>>>(r);
+            if (int rc = check_launch("backward (scan)")) return rc;
+            if (sign) {
+                if (int rc = allow_lds(robe::region_bin_kernel<true, true>, lds_bin, "backward (records)")) return rc;
+                robe::region_bin_kernel<true, true><<<dim3(r.bin_blocks), dim3(robe::kBinBlock), lds_bin, stream>>>(p, r);
+            } else {
+                if (int rc = allow_lds(robe::region_bin_kernel<false, true>, lds_bin, "backward (records)")) return rc;
+                robe::region_bin_kernel<false, true><<<dim3(r.bin_blocks), dim3(robe::kBinBlock), lds_bin, stream>>>(p, r);
+            }
+            if (int rc = check_launch("backward (records)")) return rc;
         }
-        if (int rc = check_launch("backward (records)")) return rc;
 
         // R5: one workgroup per region
-        const size_t lds_red = ((size_t)1 << r.r_shift) * 4 + (sign ? (size_t)robe::rec_batch<true>() * 12 : (size_t)robe::rec_batch<false>() * 8) + (64 + 65 + 1) * 4   // region + batch + slice counters
-                               + (pl.spill_rows ? (size_t)robe::kSpillFloats * 4 : 0);
+        const size_t lds_red = robe::reduce_lds_bytes(r.r_shift, sign, pl.gather, pl.spill_rows);
         const int vec_ok = aligned(grad_array, 16) && (rule == 0 || aligned(state, 16)) ? 1 : 0;
         const dim3 rgrid(r.NR), rblock(robe::kReduceBlock);
         const bool canon = opt.reproducible;
+#define ROBE_REDUCE_G(S_, R_, C_, P_, G_)                                                                             \
+    do {                                                                                                              \
+        if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_, C_, P_, G_>, lds_red, "backward (reduce)")) return rc;  \
+        robe::region_reduce_kernel<S_, R_, C_, P_, G_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, lr, eps, vec_ok); \
+    } while (0)
 #define ROBE_REDUCE_C(S_, R_, C_, P_)                                                                                 \
     do {                                                                                                              \
-        if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_, C_, P_>, lds_red, "backward (reduce)")) return rc;  \
-        robe::region_reduce_kernel<S_, R_, C_, P_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, lr, eps, vec_ok); \
+        if (pl.gather) ROBE_REDUCE_G(S_, R_, C_, P_, true);                                                           \
+        else ROBE_REDUCE_G(S_, R_, C_, P_, false);                                                                    \
     } while (0)
 #define ROBE_REDUCE(S_, R_)                                                                                           \
     do {                                                                                                              \
@@ -668,6 +729,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         else      { if (rule) ROBE_REDUCE(false, 1); else ROBE_REDUCE(false, 0); }
 #undef ROBE_REDUCE
 #undef ROBE_REDUCE_C
+#undef ROBE_REDUCE_G
         return check_launch("backward (reduce)");
     }
     if (rule != 0) return fail(ROBE_EINVAL, "internal: fused update needs the region-sorted scatter");

@@ -48,6 +48,7 @@ constexpr uint32_t kMaxRegions = 32768;
 constexpr uint32_t kMaxClassShift = 10;  // R5 splits an overfull region into at most 2^10 classes (the table lives in the batch area)
 constexpr uint32_t kPartBit = 0x80000000u;   // record flag: the elements past the end of the block's own region
 constexpr uint32_t kDeadRecord = 0xFFFFFFFFu;
+constexpr uint32_t kNoRun = 0xFFFFFFFFu;     // src_row of a sorted position where no run starts
 
 struct RegionPlan {
     uint32_t r_shift;        // log2 of the region size in floats
@@ -61,11 +62,17 @@ struct RegionPlan {
     uint32_t fullest_first;  // 1: R5 takes the regions by descending size class instead of by address
     uint32_t keep_rows;      // 1: gradient rows are read more than once (bags): R5 loads them with the default cache policy
     uint32_t keep_array;     // 1: R5 with the Adagrad rule leaves the array in the caches for the next forward pass (small arrays)
+    // gather variant of R5 (no R2..R4): the range table has NE = C * epc entries, epc = kmax + 3 with
+    // kmax = (P - 1) / m; dir[b] is the first sorted position whose key >> dir_shift is >= b
+    // (dir[buckets] = n), written by R1; NULL when R2..R4 run instead
+    uint32_t NE, epc, epc_recip, dir_shift, dir_buckets;   // epc_recip = ceil(2^16 / epc)
+    uint32_t *dir;
     const uint32_t *keys;    // sorted keys
     uint8_t *head;           // [n]  1: a run starts here
     uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
     uint32_t *run_tg;        // [n]  at run starts: token part of the sign hash (sign on only)
-    float *P;                // [(n + 1) / 2][d] summed rows of the runs longer than one
+    uint32_t p_quota;        // rows of P per lane group of R1
+    float *P;                // [lane groups of R1 * p_quota][d] summed rows of the runs longer than one
     uint32_t *counts, *starts;   // [NR], [NR + 1]; after R3 counts holds the order of the regions for R5
     uint32_t *wg_first;      // [bin_blocks][NR]: R2 -> R4, see region_bin_kernel
     uint2 *rec;              // [<= 2 * n * C] (offset, source block | part flag)
@@ -123,7 +130,8 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
     const uint32_t n = s.n;
     const uint64_t thread_id = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     // the record counts of R2 start at zero (this kernel is the last one before it)
-    for (uint64_t i = thread_id; i < s.NR; i += (uint64_t)gridDim.x * kBlock) s.counts[i] = 0;
+    if (s.counts != nullptr)
+        for (uint64_t i = thread_id; i < s.NR; i += (uint64_t)gridDim.x * kBlock) s.counts[i] = 0;
     if ((thread_id - lane) * kStretch >= n) return;     // the whole wavefront is past the end
     const uint64_t i_first = (thread_id - grp) * kStretch;   // first sorted position of this group's walk
 
@@ -135,10 +143,10 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
         if (pos < n) {
             const uint32_t v = vals[pos];                  // sign off: the row itself (see robe_backward_dedup.h)
             const uint32_t row = !SIGN ? v : (v < n ? (BAGS ? tok_bag[v] : v) : s.rows);
-            if (row < s.rows) {
+            t.th = s.keys[pos];                            // also for a token that is not ok: the directory covers every position
+            if (row < s.rows && t.th < kP) {               // (a key that is no residue: a position no bag of a malformed CSR wrote)
                 t.ok = true;
                 t.row = row;
-                t.th = s.keys[pos];
                 if constexpr (SIGN) {
                     const int64_t x = indices[v];
                     t.e = row % q.F;
@@ -155,11 +163,19 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
 #pragma unroll
     for (int k = 0; k < V; ++k) acc[k] = 0.0f;
     uint32_t head_pos = 0;
+    // Rows of P: every lane group owns p_quota of them, at row (group number) * p_quota, and hands
+    // them to the runs longer than one that start in its walk, in order.  A group that meets more
+    // such runs leaves the rest uncombined: each of their tokens becomes a run of its own.
+    const uint32_t p_first = (uint32_t)((thread_id - grp) >> q.g_shift) * s.p_quota;
+    uint32_t n_multi = 0, run_slot = 0;        // multi-token runs started so far; slot of the run being summed
+    uint32_t open_slot = 0;                    // slot of the run that the stretch before left open, if it has one
+    bool open_over = false;                    // ... or whether that run found the quota used up
 
     SortedToken cur = fetch(i_first + grp);
     SortedToken carry;          // the last token of the stretch before; none before the first
     carry.th = carry.row = carry.e = carry.xlo = carry.xhi = carry.tg = 0;
     carry.ok = false;
+    if (s.dir != nullptr && i_first > 0 && i_first <= n) carry.th = s.keys[i_first - 1];   // its key only: the directory needs it
     for (uint32_t st = 0; st < (uint32_t)kStretch; ++st) {
         const uint64_t i0 = i_first + (uint64_t)st * q.G;
         if (__all(i0 >= n)) break;                          // every group of the wavefront is past the end
@@ -179,28 +195,83 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
         const SortedToken first_of_next = shfl_token<SIGN>(nxt, (int)base_lane);
         if (grp + 1u >= q.G) after = first_of_next;
         const bool my_end = cur.ok && (!after.ok || !same_token<SIGN>(after, cur));
-        const bool my_single = my_head && my_end;
+        bool my_single = my_head && my_end;
+        // the slot of the run every position belongs to: the run of the last head at or before it (none:
+        // the run left open by the stretch before), counted among this walk's multi-token runs
+        uint32_t my_slot = open_slot;
+        bool my_over = open_over;
+        {
+            const uint64_t gmask = q.G >= 64u ? ~0ull : ((1ull << q.G) - 1ull);
+            const uint64_t heads = (__ballot(my_head) >> base_lane) & gmask;
+            const uint64_t multi = (__ballot(my_head && !my_end) >> base_lane) & gmask;
+            const uint64_t upto = heads & ((2ull << grp) - 1ull);
+            if (upto) {
+                const uint32_t hl = 63u - (uint32_t)__builtin_clzll(upto);
+                my_slot = n_multi + (uint32_t)__popcll(multi & ((1ull << hl) - 1ull));
+                my_over = my_slot >= s.p_quota;
+            }
+            n_multi += (uint32_t)__popcll(multi);
+        }
+        if (cur.ok && !my_single && my_over) my_single = true;     // no row of P left: this token alone
+        const bool my_lead = my_head || (cur.ok && my_over);      // a record starts at this position
+
+        // Directory for the gather variant of R5: the first sorted position of every key bucket.  The
+        // position whose bucket differs from the one before it writes the entries in between (a long gap
+        // is shared out over the wavefront), the last position writes the rest.
+        if (s.dir != nullptr) {
+            const uint64_t pos = i0 + grp;
+            uint32_t blo = 1, bhi = 0;                           // empty
+            if (pos < n) {
+                // (bit 31 is no key bit: the sort ignores it, so it is masked to keep the buckets in order)
+                blo = pos == 0 ? 0u : ((before.th & kP) >> s.dir_shift) + 1u;
+                bhi = (cur.th & kP) >> s.dir_shift;
+            }
+            const bool any = blo <= bhi, wide = any && bhi - blo >= 16u;
+            if (any && !wide)
+                for (uint32_t b = blo; b <= bhi; ++b) s.dir[b] = (uint32_t)pos;
+            uint32_t clo = bhi + 1u;                            // what the last position closes: (its bucket, buckets]
+            uint64_t todo = __ballot(wide), closer = __ballot(pos + 1u == n);
+            while (todo) {
+                const int l = __builtin_ctzll(todo);
+                todo &= todo - 1ull;
+                const uint32_t lo = __shfl(blo, l), hi = __shfl(bhi, l), v = __shfl((uint32_t)pos, l);
+                for (uint32_t b = lo + lane; b <= hi; b += 64u) s.dir[b] = v;
+            }
+            if (closer) {
+                const uint32_t lo = __shfl(clo, __builtin_ctzll(closer));
+                for (uint32_t b = lo + lane; b <= s.dir_buckets; b += 64u) s.dir[b] = n;
+            }
+        }
 
         if (i0 + grp < n) {
-            s.head[i0 + grp] = my_head ? 1 : 0;
-            if (my_single) s.src_row[i0 + grp] = cur.row;            // a run of one: read grad_out in place
+            if (s.head != nullptr) s.head[i0 + grp] = my_lead ? 1 : 0;
+            // a run of one reads grad_out in place; the head of a longer run gets its row of P when the run
+            // ends; every other position says that no run starts there (the gather variant of R5 reads
+            // this array alone to find the runs)
+            if (my_single) s.src_row[i0 + grp] = cur.row;
+            else if (!my_head) s.src_row[i0 + grp] = kNoRun;
             if constexpr (SIGN) {
-                if (my_head) s.run_tg[i0 + grp] = cur.tg;
+                if (my_lead) s.run_tg[i0 + grp] = cur.tg;
             }
         }
 
         // runs longer than one: sum their rows into P (a run may have begun in an earlier stretch)
         for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsAhead) {     // same trip count for every lane of the wavefront
-            uint32_t row[kRowsAhead];
+            uint32_t row[kRowsAhead], slot[kRowsAhead];
             bool use[kRowsAhead], head[kRowsAhead], end[kRowsAhead];
+            // what the loop below needs of a position, in one word: its run's slot, whether the position
+            // takes part, starts a run, ends one
+            const uint32_t mine = (my_slot << 3) | ((cur.ok && !my_single) ? 4u : 0u) | (my_head ? 2u : 0u) | (my_end ? 1u : 0u);
 #pragma unroll
             for (int u = 0; u < kRowsAhead; ++u) {
                 const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
                 const bool in = k0 + u < q.G;
-                use[u] = in && __shfl((int)(cur.ok && !my_single), from) != 0;
+                const uint32_t theirs = __shfl(mine, from);
                 row[u] = __shfl(cur.row, from);
-                head[u] = __shfl((int)my_head, from) != 0;
-                end[u] = __shfl((int)my_end, from) != 0;
+                use[u] = in && (theirs & 4u) != 0;
+                head[u] = (theirs & 2u) != 0;
+                end[u] = (theirs & 1u) != 0;
+                slot[u] = theirs >> 3;
             }
             float v[kRowsAhead][V];
 #pragma unroll
@@ -212,20 +283,22 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
                 if (!use[u]) continue;
                 if (head[u]) {
                     head_pos = (uint32_t)i0 + k0 + u;
+                    run_slot = slot[u];
 #pragma unroll
                     for (int k = 0; k < V; ++k) acc[k] = 0.0f;
                 }
 #pragma unroll
                 for (int k = 0; k < V; ++k) acc[k] += v[u][k];
                 if (end[u]) {
-                    // two runs longer than one start at least two positions apart: head_pos / 2 is unique
-                    const uint32_t prow = head_pos >> 1;
+                    const uint32_t prow = p_first + run_slot;
                     store_row<V, false>(s.P + (uint64_t)prow * p.d, q, grp, acc);
                     if (grp == 0) s.src_row[head_pos] = s.rows + prow;
                 }
             }
         }
         carry = shfl_token<SIGN>(cur, (int)(base_lane + q.G - 1u));
+        open_slot = __shfl(my_slot, (int)(base_lane + q.G - 1u));
+        open_over = __shfl((int)my_over, (int)(base_lane + q.G - 1u)) != 0;
         cur = nxt;
     }
 }
@@ -263,10 +336,19 @@ __device__ __forceinline__ void for_each_block(const Params &p, const RegionPlan
             uint32_t cc = 0;  // (Ch * c) mod P, built up by addition
             for (uint32_t c = 0; c < p.C; ++c) {
                 const uint32_t o = offset_of(p, th[u], cc);
-                const uint32_t r = o >> s.r_shift;
+                uint32_t r = o >> s.r_shift;
                 f(o, src0 + c, r, 0u, tgv[u]);
-                const uint64_t r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
-                if ((uint64_t)o + p.Z > r_end) f(o, src0 + c, r_end == p.m ? 0u : r + 1u, kPartBit, tgv[u]);
+                // the regions the block enters after its own: normally at most one; two when the array
+                // ends in a region shorter than the block and the block passes through it to slot 0
+                uint64_t r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
+                uint64_t left = (uint64_t)o + p.Z > r_end ? (uint64_t)o + p.Z - r_end : 0u;
+                for (int hop = 0; hop < 2 && left > 0; ++hop) {
+                    r = r_end == p.m ? 0u : r + 1u;
+                    f(o, src0 + c, r, kPartBit, tgv[u]);
+                    const uint64_t r_begin = (uint64_t)r << s.r_shift;
+                    r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
+                    left = left > r_end - r_begin ? left - (r_end - r_begin) : 0u;
+                }
                 cc = add_p(cc, p.Ch);
             }
         }
@@ -413,6 +495,18 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
 
 // ---------------------------------------------------------------------------------------------
 // R5.  RULE 0: grad_array += region.  RULE 1: Adagrad on array / state with the region as gradient.
+//
+// Where a region's records come from:
+//   GATHER = false   from the region-sorted copy that R2..R4 wrote (s.rec).
+//   GATHER = true    straight from the sorted token list, with no R2..R4 at all.  Block c of a token
+//                    with key th starts at ((th + (Ch c mod P)) mod P) mod m, so the tokens whose
+//                    block c meets a given region are those with th in a few contiguous ranges - one
+//                    per multiple of m below P - and a range of keys is a stretch of the sorted list.
+//                    The workgroup works those ranges out (R5-a), finds the stretches through a
+//                    directory that R1 left (first sorted position of every key bucket), and walks
+//                    them eight positions per thread, picking up the runs that start there.  The
+//                    order in which records are staged is a function of the sorted list alone, so
+//                    the reproducible variant needs no class split here.
 // ---------------------------------------------------------------------------------------------
 template <bool SIGN>
 __device__ __forceinline__ float signed_block_value(const Params &p, float v, uint32_t tg, uint32_t src, uint32_t j)
@@ -432,19 +526,144 @@ __device__ __forceinline__ uint32_t record_class(uint2 rec, uint32_t shift)
     return ((rec.y * 0x9E3779B1u) ^ (rec.x * 0x85EBCA6Bu + 0xC2B2AE35u) * 0x27D4EB2Fu) >> (32u - shift);
 }
 
-template <bool SIGN, int RULE, bool CANON, bool SPILL>
+// Which elements of a record a region holds.  Element j of a block at offset o sits at array position
+// (o + j) mod m.  A record without the part flag starts inside the region (r0 <= o < r0 + len) and
+// keeps the elements before the region's end; one with the flag belongs to a block that starts before
+// the region and enters it at its first slot, with element js = (r0 - o) mod m, 0 < js < Z.  Element j
+// lands in region slot abase + j (unsigned wrap-around arithmetic) for jlo <= j < jhi.
+struct RecordSpan {
+    uint32_t abase, jlo, jhi;
+    bool ok;
+};
+
+__device__ __forceinline__ RecordSpan span_of(uint32_t o, bool part, uint32_t r0, uint32_t region_len, uint32_t m, uint32_t Z)
+{
+    RecordSpan sp;
+    if (!part) {
+        sp.ok = o >= r0 && o - r0 < region_len;
+        const uint32_t keep = r0 + region_len - o;
+        sp.abase = o - r0;
+        sp.jlo = 0;
+        sp.jhi = keep < Z ? keep : Z;
+    } else {
+        const uint32_t js = r0 >= o ? r0 - o : r0 + (m - o);
+        sp.ok = js > 0 && js < Z;
+        sp.abase = 0u - js;
+        sp.jlo = js;
+        sp.jhi = js + region_len < Z ? js + region_len : Z;
+    }
+    return sp;
+}
+
+// Inclusive prefix sums of one value per thread over the first WAVES wavefronts of the workgroup
+// (the values of the other threads are not looked at and their result is meaningless); `total` is
+// valid in every thread.  One barrier; wave_tot is LDS for one word per wavefront, free again after
+// the workgroup's next barrier.
+template <uint32_t WAVES>
+__device__ __forceinline__ uint32_t reduce_block_scan(uint32_t v, uint32_t *wave_tot, uint32_t &total)
+{
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+    if (wave < WAVES) {                       // uniform over a wavefront
+#pragma unroll
+        for (uint32_t off = 1; off < 64u; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        if (lane == 63u) wave_tot[wave] = incl;
+    }
+    __syncthreads();
+    uint32_t before = 0;
+    total = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < WAVES; ++w) {
+        const uint32_t x = wave_tot[w];
+        before += w < wave ? x : 0u;
+        total += x;
+    }
+    return before + incl;
+}
+
+// R5-a.  Entry e of a region's range table: chunk c = e / epc of the embedding, and within the chunk
+// either the k-th multiple of m (k = e % epc <= kmax + 1) or, for the last entry, the lower part of
+// the one range that the wrap-around of (th + cc) mod P cuts in two.  Gives the keys [ta, tb) (empty
+// when ta >= tb) whose block c meets [r0 - Z + 1, r0 + len) modulo m.
+struct KeyRange {
+    uint32_t ta, tb, cc, c;
+};
+
+__device__ __forceinline__ KeyRange key_range(const Params &p, const RegionPlan &s, uint32_t e, uint32_t r0, uint32_t region_len)
+{
+    KeyRange kr;
+    kr.c = (e * s.epc_recip) >> 16;              // e / epc for e < 2^8 (the host checks the reciprocal)
+    const uint32_t j = e - kr.c * s.epc;
+    kr.cc = mod_p((uint64_t)p.Ch * kr.c);
+    kr.ta = kr.tb = 0;
+    const int64_t lo = (int64_t)r0 - (int64_t)p.Z + 1, hi = (int64_t)r0 + region_len, cc = kr.cc, P = kP;
+    int64_t k = j;
+    if (j + 1u == s.epc) {                       // the split entry: which multiple of m holds cc?
+        if (cc < lo) return kr;
+        const uint32_t x = (uint32_t)(cc - lo);  // <= P + Z: 32 bits; x / m by the reciprocal, low by at most one
+        uint32_t q = __umulhi(x, p.m_recip);
+        if (x - q * p.m >= p.m) ++q;
+        k = q;
+        if (k > (int64_t)s.epc - 2) return kr;
+    }
+    int64_t a = k * p.m + lo, b = k * p.m + hi;
+    if (a < 0) a = 0;
+    if (b > P) b = P;
+    if (a >= b) return kr;
+    if (j + 1u == s.epc) {
+        if (a < cc && cc < b) { kr.ta = (uint32_t)(a + P - cc); kr.tb = (uint32_t)P; }
+    } else if (a >= cc) {
+        kr.ta = (uint32_t)(a - cc); kr.tb = (uint32_t)(b - cc);
+    } else if (b <= cc) {
+        kr.ta = (uint32_t)(a + P - cc); kr.tb = (uint32_t)(b + P - cc);
+    } else {
+        kr.ta = 0; kr.tb = (uint32_t)(b - cc);
+    }
+    return kr;
+}
+
+// Records staged and applied per round.  32 KB region + batch (8 bytes a record, 12 with the sign
+// term) + counters + spill-over rows (+ the range table) stay under 40 KB: four workgroups per CU.
+template <bool SIGN, bool GATHER>
+constexpr int reduce_batch() { return GATHER ? (SIGN ? 384 : 512) : rec_batch<SIGN>(); }
+// Range-table entries that fit beside that (8 bytes each).
+template <bool SIGN>
+constexpr uint32_t gather_entries_max() { return SIGN ? 56u : 120u; }
+constexpr uint32_t kGatherChunk = 4;     // sorted positions a thread of the gather variant looks at per round
+static_assert(kGatherChunk == 4, "one uint4 of keys per thread");
+constexpr uint32_t kReduceWords = 64 + 65 + 1 + 8 + 2;   // slice counters, slice starts, stage counter, scan totals, round totals
+
+__host__ __device__ constexpr size_t reduce_lds_bytes(uint32_t r_shift, bool sign, bool gather, bool spill)
+{
+    const size_t batch = gather ? (sign ? 384u : 512u) : (sign ? 448u : 640u);
+    return ((size_t)1 << r_shift) * 4 + batch * (sign ? 12u : 8u) + kReduceWords * 4 + (spill ? (size_t)kSpillFloats * 4 : 0)
+           + (gather ? ((size_t)(sign ? 56u : 120u) * 2 + 1) * 4 + 512u : 0);   // range table, and the entry of each of the first 512 chunks
+}
+static_assert(reduce_lds_bytes(13, false, false, true) <= 40960 && reduce_lds_bytes(13, true, false, true) <= 40960 &&
+              reduce_lds_bytes(13, false, true, true) <= 40960 && reduce_lds_bytes(13, true, true, true) <= 40960,
+              "R5 with 32 KB regions: four workgroups per CU");
+
+template <bool SIGN, int RULE, bool CANON, bool SPILL, bool GATHER>
 __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void region_reduce_kernel(Params p, RegionPlan s,
                                                                      const float *__restrict__ grad_out,
                                                                      float *__restrict__ dst,      // RULE 0: grad_array; RULE 1: array
                                                                      float *__restrict__ state,    // RULE 1 only
                                                                      float lr, float eps, int vec_ok)
 {
-    constexpr int kRecBatch = rec_batch<SIGN>();
+    constexpr int kRecBatch = reduce_batch<SIGN, GATHER>();
+    constexpr int kPer = (kRecBatch + kReduceBlock - 1) / kReduceBlock;     // records per thread and round
     extern __shared__ float acc[];  // 2^r_shift floats, then the batch staging area
-    const uint32_t r = s.counts[blockIdx.x];     // after R3: the regions, fullest first
+    const uint32_t r = GATHER ? blockIdx.x : s.counts[blockIdx.x];     // records path, after R3: the regions, fullest first
     if (r >= s.NR) return;
-    const uint32_t rb = s.starts[r], re = s.starts[r + 1];
-    if (rb >= re) return;           // nothing lands in this region: it is not touched at all
+    uint32_t rb = 0, re = 0;
+    if constexpr (!GATHER) {
+        rb = s.starts[r];
+        re = s.starts[r + 1];
+        if (rb >= re) return;           // nothing lands in this region: it is not touched at all
+    }
 
     const uint32_t R = 1u << s.r_shift;
     const uint32_t r0 = r << s.r_shift;
@@ -456,10 +675,46 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
     uint32_t *cnt = srt_tg + (SIGN ? kRecBatch : 0);   // 64 slice counters
     uint32_t *pre = cnt + 64;                          // 65 slice starts
     uint32_t *sel = pre + 65;                          // records staged for this round
+    uint32_t *wave_tot = sel + 1;                      // 8 words for the block scans
+    uint32_t *round_tot = wave_tot + 8;                // 2 words: chunks taken, records staged (gather)
+    float *spill_base = reinterpret_cast<float *>(round_tot + 2);
     // this group's spill-over row, as an index into acc
-    const uint32_t spill_at = (uint32_t)(reinterpret_cast<float *>(sel + 1) - acc) + (threadIdx.x >> s.lg_shift) * p.Z;
+    const uint32_t spill_at = (uint32_t)(spill_base - acc) + (threadIdx.x >> s.lg_shift) * p.Z;
+    uint32_t *tab_pa = reinterpret_cast<uint32_t *>(spill_base + (SPILL ? kSpillFloats : 0u));   // gather: first position (a multiple of 8) of every range
+    uint32_t *tab_cum = tab_pa + gather_entries_max<SIGN>();                                    // gather: chunks before every range, total last
+    uint8_t *chunk_entry = reinterpret_cast<uint8_t *>(tab_cum + gather_entries_max<SIGN>() + 1);   // gather: the range of each of the first kReduceBlock chunks
 
-    for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = 0.0f;
+    // R5-a: the ranges of this region and where they sit in the sorted list
+    uint32_t total_chunks = 0;
+    if constexpr (GATHER) {
+        uint32_t pa = 0, pb = 0;
+        if (threadIdx.x < s.NE) {
+            const KeyRange kr = key_range(p, s, threadIdx.x, r0, region_len);
+            if (kr.ta < kr.tb) {
+                pa = s.dir[kr.ta >> s.dir_shift];
+                pb = s.dir[((kr.tb - 1u) >> s.dir_shift) + 1u];
+            }
+        }
+        // (the region is cleared while the directory entries are on their way)
+        for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = 0.0f;
+        uint32_t my_chunks = 0, my_pa = 0;
+        pb = pb < s.n ? pb : s.n;                            // (whatever the directory holds, nothing past the list is read)
+        if (pb > pa) {
+            my_pa = pa & ~(kGatherChunk - 1u);
+            my_chunks = (pb - my_pa + kGatherChunk - 1u) / kGatherChunk;
+        }
+        static_assert(gather_entries_max<SIGN>() <= 128u, "the range table is scanned by the first two wavefronts");
+        const uint32_t incl = reduce_block_scan<2>(my_chunks, wave_tot, total_chunks);
+        if (total_chunks == 0) return;  // no token's block comes near this region: it is not touched at all
+        if (threadIdx.x < s.NE) {
+            tab_pa[threadIdx.x] = my_pa;
+            tab_cum[threadIdx.x] = incl - my_chunks;
+            for (uint32_t g = incl - my_chunks; g < incl && g < (uint32_t)kReduceBlock; ++g) chunk_entry[g] = (uint8_t)threadIdx.x;
+        }
+        if (threadIdx.x == 0) tab_cum[s.NE] = total_chunks;
+    } else {
+        for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = 0.0f;
+    }
 
     typedef Vec<4>::A V4;
     const uint32_t nvec = vec_ok ? region_len / 4u : 0u;
@@ -472,25 +727,17 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
     const uint32_t slice_shift = s.r_shift - grp_shift;       // the host guarantees 2^slice_shift >= Z
     const uint32_t slice_end = (grp + 1u) << slice_shift;
 
-    // Elements of a record that this region (and this record's part) holds: element j sits at array
-    // position (o + j) mod m; part 0 keeps the elements before the end of o's own region, part 1 the
-    // rest, which continue at the start of the next region (or of the array).
-    auto own_end = [&](uint32_t o) -> uint32_t {              // end of the region that holds offset o
-        const uint64_t e = ((uint64_t)((o >> s.r_shift) + 1u)) << s.r_shift;
-        return e < p.m ? (uint32_t)e : p.m;
-    };
-
-    // Which records go into which round must not depend on the order in which the records were
-    // written (that order comes from integer atomics and changes from run to run): a region with more
-    // than one round's worth of records is split into classes by a hash of the record, with as many
-    // classes as it takes for every class to fit one round.  The host refuses reproducible calls whose
-    // regions could need more than 2^kMaxClassShift classes; should one turn up all the same (ids
-    // chosen against the hash), its slots receive NaN instead of a sum whose bits could change from
-    // run to run.
+    // Records path: which records go into which round must not depend on the order in which the
+    // records were written (that order comes from integer atomics and changes from run to run): a
+    // region with more than one round's worth of records is split into classes by a hash of the
+    // record, with as many classes as it takes for every class to fit one round.  The host refuses
+    // reproducible calls whose regions could need more than 2^kMaxClassShift classes; should one turn
+    // up all the same (ids chosen against the hash), its slots receive NaN instead of a sum whose bits
+    // could change from run to run.
     const uint32_t count = re - rb;
     uint32_t cls_shift = 0;
     bool by_class = false;
-    if (CANON && count > (uint32_t)kRecBatch) {
+    if (!GATHER && CANON && count > (uint32_t)kRecBatch) {
         uint32_t *hist = reinterpret_cast<uint32_t *>(srt);
         cls_shift = 1;
         while (((count + (1u << cls_shift) - 1u) >> cls_shift) > (uint32_t)kRecBatch / 2u) ++cls_shift;
@@ -512,20 +759,85 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             }
         }
     }
-    const bool poison = CANON && count > (uint32_t)kRecBatch && !by_class;
-    const uint32_t rounds = poison ? 0u : (by_class ? (1u << cls_shift) : (count + kRecBatch - 1u) / kRecBatch);
+    const bool poison = !GATHER && CANON && count > (uint32_t)kRecBatch && !by_class;
+    const uint32_t rounds = GATHER ? 0u : (poison ? 0u : (by_class ? (1u << cls_shift) : (count + kRecBatch - 1u) / kRecBatch));
     if (poison) {
         __syncthreads();
         for (uint32_t i = threadIdx.x; i < region_len; i += kReduceBlock) acc[i] = __uint_as_float(0x7FC00000u);
     }
 
-    for (uint32_t round = 0; round < rounds; ++round) {
+    uint32_t chunk_base = 0, window = kReduceBlock;           // gather: chunks taken by the rounds before; chunks this round tries
+    for (uint32_t round = 0; GATHER ? chunk_base < total_chunks : round < rounds; ++round) {
         if (threadIdx.x < groups) cnt[threadIdx.x] = 0;
         if (threadIdx.x == 0) *sel = 0;
         __syncthreads();   // also orders the previous round's last pass before this round's writes
         uint32_t bb = rb + round * kRecBatch;
         uint32_t nb = re - bb < (uint32_t)kRecBatch ? re - bb : (uint32_t)kRecBatch;
-        if (CANON && by_class) {
+        if constexpr (GATHER) {
+            // R5-b: thread t looks at the t-th of the next `window` chunks of four sorted positions: their
+            // keys and source rows in one vector load each (the arrays are padded to whole chunks).  A run
+            // starts where the source row says so; it belongs to this range when its key does (a bucket
+            // of the directory is wider than the range's ends).  Every run found is staged at once, its
+            // slot taken from a counter; should the window hold more runs than the batch has room for,
+            // the round is done again with half the window (a window of a quarter of the batch always
+            // fits).  Which runs a round takes is thus a function of the sorted list alone; the order of
+            // the slots is not, and does not matter.
+            const uint32_t g = chunk_base + threadIdx.x;
+            if (threadIdx.x < window && g < total_chunks) {
+                uint32_t lo_e = 0;                             // the range of chunk g: tab_cum[lo_e] <= g < tab_cum[lo_e + 1]
+                if (g < (uint32_t)kReduceBlock) {
+                    lo_e = chunk_entry[g];
+                } else {
+                    uint32_t hi_e = s.NE;
+                    while (hi_e - lo_e > 1u) {
+                        const uint32_t mid = (lo_e + hi_e) >> 1;
+                        if (tab_cum[mid] <= g) lo_e = mid; else hi_e = mid;
+                    }
+                }
+                const uint32_t q = tab_pa[lo_e] + kGatherChunk * (g - tab_cum[lo_e]);
+                if (q < s.n) {
+                    const uint4 k4 = *reinterpret_cast<const uint4 *>(s.keys + q);
+                    const uint4 s4 = *reinterpret_cast<const uint4 *>(s.src_row + q);
+                    const KeyRange kr = key_range(p, s, lo_e, r0, region_len);
+                    const uint32_t th4[4] = {k4.x, k4.y, k4.z, k4.w}, sr4[4] = {s4.x, s4.y, s4.z, s4.w};
+                    const uint32_t live = s.n - q < 4u ? s.n - q : 4u;          // positions past the end hold nothing
+                    uint32_t hits = 0;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if ((uint32_t)k < live && sr4[k] != kNoRun && th4[k] >= kr.ta && th4[k] < kr.tb) hits |= 1u << k;
+                    if (hits) {
+                        uint32_t tg4[4] = {0, 0, 0, 0};
+                        if constexpr (SIGN) {
+                            const uint4 g4 = *reinterpret_cast<const uint4 *>(s.run_tg + q);
+                            tg4[0] = g4.x; tg4[1] = g4.y; tg4[2] = g4.z; tg4[3] = g4.w;
+                        }
+                        uint32_t slot = atomicAdd(sel, (uint32_t)__popc(hits));
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            if (!((hits >> k) & 1u)) continue;
+                            if (slot < (uint32_t)kRecBatch) {
+                                const uint32_t o = offset_of(p, th4[k], kr.cc);
+                                const bool inside = o >= r0 && o - r0 < region_len;
+                                srt[slot] = make_uint2(o, (sr4[k] * p.C + kr.c) | (inside ? 0u : kPartBit));
+                                if constexpr (SIGN) srt_tg[slot] = tg4[k];
+                            }
+                            ++slot;
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            nb = *sel;
+            if (nb > (uint32_t)kRecBatch) {     // too many runs in this window (uniform over the workgroup)
+                __syncthreads();                // everyone has read the counter before the next attempt clears it
+                window >>= 1;
+                --round;
+                continue;
+            }
+            chunk_base += window;
+            window = kReduceBlock;
+        }
+        if (!GATHER && CANON && by_class) {
             // stage this round's class in the batch area, in any order
             for (uint32_t k = threadIdx.x; k < count; k += kReduceBlock) {
                 const uint2 x = s.rec[rb + k];
@@ -540,14 +852,14 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             nb = *sel < (uint32_t)kRecBatch ? *sel : (uint32_t)kRecBatch;
         }
 
-        // 1. each thread takes two records, finds their slice and their rank inside it
-        uint2 rc[2];
-        uint32_t tgv[2], sl[2], rk[2];
-        if (CANON && by_class) {   // two branches: one reads LDS, the other global memory
+        // 1. each thread takes its records, finds their slice and their rank inside it
+        uint2 rc[kPer];
+        uint32_t tgv[kPer], sl[kPer], rk[kPer];
+        if (GATHER || (CANON && by_class)) {   // two branches: one reads LDS, the other global memory
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < kPer; ++t) {
                 const uint32_t k = threadIdx.x + (uint32_t)t * kReduceBlock;
-                rc[t] = make_uint2(kDeadRecord, 0u);
+                rc[t] = make_uint2(0u, kDeadRecord);
                 tgv[t] = 0;
                 if (k < nb) {
                     rc[t] = srt[k];
@@ -556,9 +868,9 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             }
         } else {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < kPer; ++t) {
                 const uint32_t k = threadIdx.x + (uint32_t)t * kReduceBlock;
-                rc[t] = make_uint2(kDeadRecord, 0u);
+                rc[t] = make_uint2(0u, kDeadRecord);
                 tgv[t] = 0;
                 if (k < nb) {
                     rc[t] = s.rec[bb + k];
@@ -567,20 +879,23 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             }
         }
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < kPer; ++t) {
             sl[t] = 0;
             rk[t] = 0;
-            if (rc[t].x != kDeadRecord) {
+            if (rc[t].y != kDeadRecord) {
                 const uint32_t o = rc[t].x, src = rc[t].y & ~kPartBit;
                 const bool part1 = (rc[t].y & kPartBit) != 0;
-                // where the record's first element of this part lands; anything else cannot occur
-                // with consistent inputs and is dropped
-                const uint32_t first = part1 ? own_end(o) % p.m : o;
-                if (o < p.m && src < s.src_blocks && (first >> s.r_shift) == r) {
-                    sl[t] = (first - r0) >> slice_shift;
+                // anything that does not belong here cannot occur with consistent inputs and is dropped
+                const RecordSpan sp = span_of(o, part1, r0, region_len, p.m, p.Z);
+                if (o < p.m && src < s.src_blocks && sp.ok) {
+                    // From here on the record carries, instead of its offset, the region slot of its
+                    // element 0 (negative when the block enters the region at slot 0 with a later
+                    // element): element j then lands in slot x + j whenever that is a slot of the region.
+                    rc[t].x = sp.abase;
+                    sl[t] = part1 ? 0u : sp.abase >> slice_shift;
                     rk[t] = atomicAdd(&cnt[sl[t]], 1u);
                 } else {
-                    rc[t].x = kDeadRecord;
+                    rc[t].y = kDeadRecord;
                 }
             }
         }
@@ -595,8 +910,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
         }
         __syncthreads();
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (rc[t].x != kDeadRecord) {
+        for (int t = 0; t < kPer; ++t) {
+            if (rc[t].y != kDeadRecord) {
                 const uint32_t at = pre[sl[t]] + rk[t];
                 srt[at] = rc[t];
                 if constexpr (SIGN) srt_tg[at] = tgv[t];
@@ -616,8 +931,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                 return tk < mine_tg || (tk == mine_tg && k < mine_at);
             };
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                if (rc[t].x != kDeadRecord) {
+            for (int t = 0; t < kPer; ++t) {
+                if (rc[t].y != kDeadRecord) {
                     const uint32_t a = pre[sl[t]], b = pre[sl[t] + 1u], me = a + rk[t];
                     uint32_t c = 0;
                     for (uint32_t k0 = a; k0 < b; k0 += kCanonAhead) {     // kCanonAhead independent LDS reads per step
@@ -640,8 +955,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             }
             __syncthreads();
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                if (rc[t].x != kDeadRecord) {
+            for (int t = 0; t < kPer; ++t) {
+                if (rc[t].y != kDeadRecord) {
                     const uint32_t at = pre[sl[t]] + rk[t];
                     srt[at] = rc[t];
                     if constexpr (SIGN) srt_tg[at] = tgv[t];
@@ -664,24 +979,15 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             for (uint32_t j = j0; j < p.Z; j += LG) acc[spill_at + j] = 0.0f;
         }
         for (uint32_t k0 = lb; k0 < le; k0 += kRecAhead) {
-            // per record: element j lands at region slot abase + j, for j in [jlo, jhi) (packed; Z <= 2^15)
-            uint32_t abase[kRecAhead], win[kRecAhead], src[kRecAhead], tg[kRecAhead];
+            // per record: element j lands at region slot abase + j if that is one (unsigned compare)
+            uint32_t abase[kRecAhead], src[kRecAhead], tg[kRecAhead];
 #pragma unroll
             for (int u = 0; u < kRecAhead; ++u) {
                 const bool live = k0 + u < le;
                 const uint2 x = srt[live ? k0 + u : lb];
                 src[u] = x.y & ~kPartBit;
                 tg[u] = SIGN ? srt_tg[live ? k0 + u : lb] : 0u;
-                const uint32_t keep = own_end(x.x) - x.x;                 // elements before the end of o's own region
-                const uint32_t cut = keep < p.Z ? keep : p.Z;
-                if (x.y & kPartBit) {
-                    abase[u] = 0u - cut;                                  // element `cut` is the first of this region
-                    win[u] = cut | (p.Z << 16);
-                } else {
-                    abase[u] = x.x - r0;
-                    win[u] = cut << 16;
-                }
-                if (!live) win[u] = 0;
+                abase[u] = live ? x.x : region_len;            // (a record past the end lands nowhere)
             }
             for (uint32_t j = j0; j < p.Z; j += LG) {
                 float v[kRecAhead];
@@ -694,7 +1000,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
 #pragma unroll
                 for (int u = 0; u < kRecAhead; ++u) {
                     const uint32_t a = abase[u] + j;
-                    if (j >= (win[u] & 0xFFFFu) && j < (win[u] >> 16) && a < region_len) {
+                    if (a < region_len) {
                         const float val = signed_block_value<SIGN>(p, v[u], tg[u], src[u], j);
                         if constexpr (SPILL) {
                             // one read-modify-write, in the slice or in the group's spill-over row
@@ -719,15 +1025,14 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
         } else {
             for (uint32_t k = lb; k < le; ++k) {
                 const uint2 x = srt[k];
-                if (x.y & kPartBit) continue;                       // a part-1 record starts its slice: never past its end
-                const uint32_t o = x.x, src = x.y;
-                if (o - r0 + p.Z <= slice_end) continue;
-                const uint32_t oend = own_end(o);
+                if (x.y & kPartBit) continue;                       // such a record starts slice 0 at its first slot: never past a slice end
+                const uint32_t abase = x.x, src = x.y;
+                if (abase + p.Z <= slice_end) continue;
                 const uint32_t tgk = SIGN ? srt_tg[k] : 0u;
                 const float *base = src < src_own ? grad_out + (uint64_t)src * p.Z : s.P + (uint64_t)(src - src_own) * p.Z;
                 for (uint32_t j = j0; j < p.Z; j += LG) {
-                    const uint32_t a = o + j - r0;
-                    if (o + j < oend && a >= slice_end && a < region_len)
+                    const uint32_t a = abase + j;
+                    if (a >= slice_end && a < region_len)
                         acc[a] += signed_block_value<SIGN>(p, base[j], tgk, src, j);
                 }
             }

@@ -463,6 +463,28 @@ def test_region_route_never_leaves_a_last_region_shorter_than_a_block(m, Z):
         _check_fused(h, H, Gi, ids, None, B, F, m, options=robe.options(fused_route=robe.ROUTE_REGIONS))
 
 
+@pytest.mark.parametrize("m,d,Z,records", [(1_000_003, 128, 32, 1), (45_000_007, 64, 64, 2), (300_007, 16, 4, 1)])
+def test_region_route_when_repeated_tokens_outnumber_the_rows_of_their_sums(m, d, Z, records):
+    # Every token two or three times: far more runs of repeated tokens than a lane group of the combine
+    # kernel has rows for their sums (an eighth of the positions it walks).  The runs it has no row
+    # for go uncombined, token by token; sums stay exact with small-integer gradients.
+    B, F = 700, 26
+    for sign in (0, 1):
+        h, H = both_hashes(m + sign + d, m, d, Z, sign)
+        rng = np.random.default_rng(d)
+        ids = rng.integers(0, B * F // 3, size=(B, F), dtype=np.int64) * 1000 + np.arange(F)
+        Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+        opt = robe.options(backward_route=robe.ROUTE_REGIONS, region_records=records)
+        assert robe.robe_workspace_bytes(h, B, F, ids.size, opt) > 16 * ids.size
+        ref, _ = oracle.backward(H, Gi, ids, None, B, F, threads=THREADS, want_abs=False)
+        for o in (opt, robe.options(reproducible=1, region_records=records)):
+            ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+            robe.robe_backward(h, to_dev(Gi), to_dev(ids), None, B, F, ga, options=o)
+            nz = torch.from_numpy(np.flatnonzero(ref)).to(DEV)
+            assert int(torch.count_nonzero(ga).item()) == nz.numel()
+            assert np.array_equal(ga[nz].cpu().numpy().astype(np.float64), ref[nz.cpu().numpy()])
+
+
 def test_reproducible_option_refuses_arrays_too_small_for_the_token_count():
     # 170,000 distinct tokens on an array of one region: far more blocks per region than the
     # canonical order handles; the call must fail, not fall back to an order that changes between runs

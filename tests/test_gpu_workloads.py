@@ -125,9 +125,18 @@ def run_workload(name, **scale):
     assert int(bad.sum()) <= 2 + w.m // 10**5, int(bad.sum())
     del Mg, sg, Mo, so, go
 
-    # The single call that scatters and updates at once, from the same start, to the same bar.
+    # The single call that scatters and updates at once, from the same start, to the same bar.  It runs
+    # on exactly the workspace the library asks for: the bytes after it, in the same allocation, hold a
+    # pattern that must still be there afterwards.
     Mf, sf = dev(M), torch.zeros(w.m, dtype=torch.float32, device=DEV)
-    robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Mf, sf, w.lr, w.eps)
+    need = robe.robe_fused_workspace_bytes(h, B, F, ids.size)
+    tail = 1 << 20
+    buf = torch.full((need + tail,), 0xA5, dtype=torch.uint8, device=DEV)
+    robe.robe_backward_adagrad(h, Gd, idd, offd, B, F, Mf, sf, w.lr, w.eps, workspace=buf[:need])
+    assert bool((buf[need:] == 0xA5).all()), "the fused step wrote past the workspace it asked for"
+    if name == "multihot":
+        assert need <= 10**9, need          # sort buffers, one source row per token, the rows of P, the directory
+    del buf
     Mf, sf = Mf.cpu().numpy(), sf.cpu().numpy()
     assert bits_equal(Mf[untouched], M[untouched]) and not sf[untouched].any()
     # accumulator: s = g^2 from zero, g within 1e-5 * S of the oracle's
