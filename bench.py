@@ -77,21 +77,57 @@ def algorithmic_bytes(w, rows, tokens, touched):
     return {"fwd": fwd, "bwd": bwd, "adagrad": ada, "sgd": sgd, "bwd_adagrad": bwd + ada}
 
 
-def measured_traffic(workload, kernel):
-    """HBM-side bytes per launch from the committed rocprofv3 counter summary, if there is one.
+def kernel_sources_hash():
+    """Identifies the kernels a profile was taken with: a hash over the HIP sources and the header."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2108_02191_amd", "csrc")
+    for path in sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "robe.h")]:
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profile_traffic(workload, unfused):
+    """HBM-side bytes per launch from the committed rocprofv3 counter summary of this workload.
 
     profiles/<workload>_step.md (the default step) and profiles/<workload>_step_separate_calls.md
-    (--unfused) carry lines `traffic <kernel> <bytes>` (FETCH_SIZE and WRITE_SIZE of separate --pmc
-    runs of this same script, scaled by the calibration copy)."""
-    for suffix in ("_step.md", "_step_separate_calls.md"):
-        try:
-            for line in open(os.path.join(ROOT, "profiles", workload + suffix)):
-                parts = line.split()
-                if len(parts) == 3 and parts[0] == "traffic" and parts[1] == kernel:
-                    return int(parts[2])
-        except OSError:
-            pass
-    return None
+    (--unfused) carry a line `sources <hash>` (the kernel sources the profile was taken with), lines
+    `traffic <phase> <bytes>` per entry-point call and `traffic_kernel <kernel> <bytes>` per launch
+    (FETCH_SIZE and WRITE_SIZE of separate --pmc runs of this same script, scaled by the calibration
+    copy).  A profile taken with other sources says nothing about these kernels: then nothing is returned."""
+    name = workload + ("_step_separate_calls.md" if unfused else "_step.md")
+    out = {"phase": {}, "kernel": {}, "kernel_us": {}}
+    try:
+        lines = open(os.path.join(ROOT, "profiles", name)).read().splitlines()
+    except OSError:
+        return None
+    stamp = [l.split()[1] for l in lines if l.startswith("sources ") and len(l.split()) == 2]
+    if not stamp or stamp[0] != kernel_sources_hash():
+        return None
+    for line in lines:
+        parts = line.split()
+        if len(parts) == 3 and parts[0] == "traffic":
+            out["phase"][parts[1]] = int(parts[2])
+        elif len(parts) == 3 and parts[0] == "traffic_kernel":
+            out["kernel"][parts[1]] = int(parts[2])
+        elif len(parts) == 3 and parts[0] == "duration_us":
+            out["kernel_us"][parts[1]] = float(parts[2])
+    return out
+
+
+def token_statistics(w, ids, off):
+    """Distinct tokens of a batch, and how many of them occur once (host arithmetic on the inputs)."""
+    import numpy as np
+    F = w.n_features
+    if off is None:
+        feat = np.tile(np.arange(F, dtype=np.int64), w.batch)
+        flat = ids.ravel()
+    else:
+        feat = np.repeat(np.arange(w.rows, dtype=np.int64) % F, np.diff(off))
+        flat = ids
+    key = flat.astype(np.uint64) * np.uint64(64) + feat.astype(np.uint64)
+    _, counts = np.unique(key, return_counts=True)
+    return int(counts.size), int((counts == 1).sum())
 
 
 def cpu_baseline(w, M, ids, off, G, target_s):
@@ -216,7 +252,7 @@ def main():
 
     stream = torch.cuda.current_stream()
 
-    def step(k, ev=None):
+    def step(k, ev=None, opt=opt):
         idd, offd = dev_batches[k % len(dev_batches)]
         if ev:
             ev[0].record(stream)
@@ -272,6 +308,28 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # Which kernel inside the backward call to time on its own: the library records two events of ours
+    # around one kernel of the sorted routes (options probe_*).  The per-region reduce kernel if the
+    # call launches it, else the kernel that combines repeated tokens, else none (direct scatter).
+    def probe_options(kernel):
+        pb, pe = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pb.record(stream)
+        pe.record(stream)            # (recording creates the handles)
+        o = robe.options(**fields, probe_kernel=kernel, probe_begin=pb.cuda_event, probe_end=pe.cuda_event)
+        return o, pb, pe
+
+    probe_kernel = robe.PROBE_NONE
+    if do_bwd and not mixed:
+        for cand in (robe.PROBE_REDUCE, robe.PROBE_COMBINE):
+            o, pb, pe = probe_options(cand)
+            mark = torch.cuda.Event(enable_timing=True)
+            mark.record(stream)
+            step(0, opt=o)
+            torch.cuda.synchronize()
+            if mark.elapsed_time(pb) > 0 and pb.elapsed_time(pe) > 0:     # recorded inside that step
+                probe_kernel = cand
+                break
+
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize()
@@ -297,12 +355,14 @@ def main():
         graph_ms = 1e3 * (time.perf_counter() - t1) / (n_rep * per_replay)
 
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    probes = [probe_options(probe_kernel) if probe_kernel else (opt, None, None) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(k, events[k])
+        step(k, events[k], opt=probes[k][0])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    probe_ms = [pb.elapsed_time(pe) for _, pb, pe in probes if pb is not None]
 
     ms_per_step = 1e3 * elapsed / args.steps
     k_ms = {"fwd": [], "bwd": [], "adagrad": [], "sgd": [], "bwd_adagrad": []}
@@ -419,7 +479,6 @@ def main():
                              "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
                              "frac_of_device_copy": round(gbs / copy_gbs, 4)}
     in_step = [n for n in kernels if not (fused and n in ("bwd", "adagrad"))]
-    dominant = max(in_step, key=lambda n: kernels[n]["ms"])
     phases = {"fwd": {"ms": round(avg["fwd"], 4), "lookups_per_s": rate(avg["fwd"])}}
     if do_bwd and avg["bwd"] > 0:
         phases["fwd_bwd"] = {"ms": round(avg["fwd"] + avg["bwd"], 4), "lookups_per_s": rate(avg["fwd"] + avg["bwd"])}
@@ -431,22 +490,77 @@ def main():
             t_sep = avg["fwd"] + avg["bwd"] + avg["adagrad"]
             phases["fwd_bwd_adagrad_separate_calls"] = {"ms": round(t_sep, 4), "lookups_per_s": rate(t_sep)}
     elif do_ada or do_sgd:
-        opt = "adagrad" if do_ada else "sgd"
-        t_all = avg["fwd"] + avg["bwd"] + avg[opt]
-        phases["fwd_bwd_" + opt] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all)}
+        rule = "adagrad" if do_ada else "sgd"
+        t_all = avg["fwd"] + avg["bwd"] + avg[rule]
+        phases["fwd_bwd_" + rule] = {"ms": round(t_all, 4), "lookups_per_s": rate(t_all)}
     total_alg = sum(alg[n] for n in in_step)
-    # the timed unit of each phase is one entry-point call; backward is several kernels when it sorts
-    entry_names = {"fwd": "robe_forward", "adagrad": "robe_adagrad_update", "sgd": "robe_sgd_update",
-                   "bwd_adagrad": "robe_backward_adagrad (every kernel of the call: token keys, radix sort, then "
-                                  "combine_rows + region count/scan/records + region_reduce with the Adagrad "
-                                  "write-back on large arrays, scatter + update_kernel on small ones)",
-                   "bwd": "robe_backward (every kernel of the call: "
-                          + ("token keys, radix sort, then combine + scatter" if ws_bytes else "direct scatter kernel") + ")"}
-    if bf16:
-        entry_names["fwd"] = "robe_forward_bf16"
-    if mixed:
-        entry_names["fwd"] = "robe_forward_mixed (one launch per run of equal dimensions)"
-        entry_names["bwd"] = "robe_backward_mixed (direct scatter, one launch per run of equal dimensions)"
+
+    # ---- what was measured, per entry-point call and for the single kernel that takes the most time ----
+    # Per call, three byte counts: `algorithmic` prices every token at the per-unit figures of the
+    # workload statement (forward: a read of its d slots; backward: a read and a write of them; 24 bytes
+    # per touched slot for Adagrad), whether or not the implementation moves them; `compulsory` is what
+    # any implementation of the fused call must move (every gradient row, id and offset once; array and
+    # state of the touched slots read and written once); `traffic` is what rocprofv3 counted at the
+    # L2 <-> fabric boundary (committed profile of these same kernel sources; absent otherwise).
+    prof = profile_traffic(w.name, args.unfused) if not (args.batch or args.m or fields) else None
+    distinct, singles = token_statistics(w, *batches[0])
+    vec = 4 * w.d
+    id_bytes_dev = tok * 8 + ((rows + 1) * 8 if w.bag_mean is not None else 0)
+    compulsory = {"fwd": alg["fwd"],
+                  "bwd": rows * vec + id_bytes_dev + touched * 8,
+                  "adagrad": touched * 24, "sgd": touched * 16,
+                  "bwd_adagrad": rows * vec + id_bytes_dev + touched * 16}
+    for name, kk in kernels.items():
+        if not mixed and not bf16:
+            kk["compulsory_GB"] = round(compulsory[name] / 1e9, 4)
+        t = prof["phase"].get(name) if prof else None
+        kk["traffic_GB"] = None if t is None else round(t / 1e9, 4)
+        kk["frac_physical"] = None if t is None else round(t / (kk["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+
+    # Single kernels timed live with events on the launch stream: the forward kernel (the whole
+    # robe_forward call), the optimizer kernel (the whole update call), and the kernel the library
+    # bracketed with the probe events inside the backward call.  Algorithmic bytes per launch, from the
+    # units that launch processes: the reduce kernel reads one summed gradient row per distinct token
+    # and reads and writes array and state (fused) or the gradient array (robe_backward) of every
+    # touched slot; the combine kernel reads the gradient row of every token that occurs more than once
+    # and writes one row per such distinct token (region route), or reads every token's row and reads
+    # and writes the slots of every distinct token (atomic route).
+    single = {}
+    if not mixed:
+        single["bag_kernel / single_hot_kernel (robe_forward%s)" % ("_bf16" if bf16 else "")] = (avg["fwd"], alg["fwd"], "fwd_kernel")
+    for rule in ("adagrad", "sgd"):
+        if avg[rule] > 0 and not fused:      # (beside a fused step the update call is timed for comparison only)
+            single["update_kernel (robe_%s_update)" % rule] = (avg[rule], alg[rule], "update_kernel")
+    if probe_ms:
+        pms = sum(probe_ms) / len(probe_ms)
+        multi = distinct - singles
+        if probe_kernel == robe.PROBE_REDUCE:
+            per_slot = 16 if fused else 8
+            single["region_reduce_kernel (inside robe_backward%s)" % ("_adagrad" if fused else "")] = (
+                pms, distinct * vec + touched * per_slot, "region_reduce_kernel")
+        elif fws_bytes or ws_bytes:
+            single["combine_scatter_kernel (inside robe_backward)"] = (pms, tok * vec + distinct * 2 * vec, "combine_scatter_kernel")
+    roof = None
+    if single:
+        dom = max(single, key=lambda k: single[k][0])
+        ms_k, bytes_k, tag = single[dom]
+        t = prof["kernel"].get(tag) if prof else None
+        roof = {"kernel": dom, "bound": "hbm", "achieved": round(bytes_k / (ms_k * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(bytes_k / (ms_k * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "traffic": t, "frac_physical": None if t is None else round(t / (ms_k * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "ms": round(ms_k, 4), "algorithmic_bytes": int(bytes_k),
+                "ms_rocprofv3": None if not prof or tag not in prof["kernel_us"] else round(prof["kernel_us"][tag] / 1e3, 4),
+                "units": {"tokens": tok, "distinct_tokens": distinct, "tokens_occurring_once": singles, "rows": rows,
+                          "touched_slots": touched},
+                "all_single_kernels_ms": {k: round(v[0], 4) for k, v in single.items()},
+                "profile": "profiles/%s_step%s.md" % (w.name, "_separate_calls" if args.unfused else "") if prof else None,
+                "kernel_sources": kernel_sources_hash()}
+    else:       # tables of mixed dimensions: several launches per call, the call is the unit
+        dom = max(in_step, key=lambda n: kernels[n]["ms"])
+        roof = {"kernel": "robe_%s_mixed (one launch per run of equal dimensions)" % ("backward" if dom == "bwd" else "forward"),
+                "bound": "hbm", "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": prof["phase"].get(dom) if prof else None,
+                "ms": kernels[dom]["ms"], "kernel_sources": kernel_sources_hash()}
     result = {
         "metric": "ROBE lookups/sec, whole step (fwd%s%s), d=%d, Z=%d" % (
             "+bwd" if do_bwd else "", "+Adagrad" if do_ada else ("+SGD" if do_sgd else ""), w.d, w.Z)
@@ -468,9 +582,7 @@ def main():
         "effective_frac_of_device_copy": total_alg / (ms_per_step * 1e-3) / 1e9 / copy_gbs,
         "phases": phases,
         "kernels": kernels,
-        "roofline": {"kernel": entry_names[dominant], "bound": "hbm", "achieved": kernels[dominant]["achieved_GBps"],
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"],
-                     "traffic": measured_traffic(w.name, dominant)},
+        "roofline": roof,
         "pcie_inclusive": None if not n_h2d else {
                            "ms_per_step": round(h2d_ms, 4), "lookups_per_s": tok / (h2d_ms * 1e-3),
                            "host_to_device_bytes_per_step": int(id_bytes), "steps": n_h2d,

@@ -123,6 +123,12 @@ typedef struct robe_hash_t {
  *   key_bits       most significant bits of the 31-bit token key that the sort looks at, 8..31
  *   region_records 0 by size, 1: ROBE_ROUTE_REGIONS writes a region-sorted copy of the block records,
  *                  2: the region workgroups look their blocks up in the sorted token list instead
+ *   probe_kernel, probe_begin, probe_end
+ *                  a measurement aid.  With probe_kernel = ROBE_PROBE_* and two hipEvent_t handles,
+ *                  a backward call records probe_begin on the stream just before the named kernel of
+ *                  the sorted routes and probe_end just after it, so that a benchmark can time that one
+ *                  kernel inside the call (calls that do not launch it record neither).
+ *                  ROBE_PROBE_NONE (0) or NULL events: nothing is recorded.
  */
 typedef struct robe_options_t {
     int32_t reproducible;
@@ -136,8 +142,15 @@ typedef struct robe_options_t {
     int32_t region_shift;
     int32_t key_bits;
     int32_t region_records;
-    int32_t reserved[3];      /* must be zero */
+    int32_t probe_kernel;
+    int32_t reserved[2];      /* must be zero */
+    void *probe_begin, *probe_end;
 } robe_options_t;
+
+#define ROBE_PROBE_NONE     0
+#define ROBE_PROBE_COMBINE  1   /* the kernel that sums the rows of repeated tokens (both sorted routes) */
+#define ROBE_PROBE_REDUCE   2   /* the per-region reduce kernel of ROBE_ROUTE_REGIONS                    */
+#define ROBE_PROBE_SORT     3   /* the radix sort passes, first count kernel to last scatter kernel      */
 
 #define ROBE_ROUTE_AUTO      0
 #define ROBE_ROUTE_DIRECT    1

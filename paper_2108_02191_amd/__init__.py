@@ -51,11 +51,13 @@ class RobeOptions(ctypes.Structure):
                 ("bwd_elems", ctypes.c_int32), ("bwd_strided", ctypes.c_int32),
                 ("tile_lookups", ctypes.c_int32), ("row_order", ctypes.c_int32), ("tile_combine", ctypes.c_int32),
                 ("region_shift", ctypes.c_int32), ("key_bits", ctypes.c_int32), ("region_records", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 3)]
+                ("probe_kernel", ctypes.c_int32), ("reserved", ctypes.c_int32 * 2),
+                ("probe_begin", ctypes.c_void_p), ("probe_end", ctypes.c_void_p)]
 
 
 ROUTE_AUTO, ROUTE_DIRECT, ROUTE_COMBINE, ROUTE_REGIONS, ROUTE_TWO_STEP = 0, 1, 2, 3, 4
 ROWS_AUTO, ROWS_MEMORY, ROWS_BY_TABLE, ROWS_BY_TABLE_ALWAYS = 0, 1, 2, 3
+PROBE_NONE, PROBE_COMBINE, PROBE_REDUCE, PROBE_SORT = 0, 1, 2, 3
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
@@ -162,7 +164,7 @@ def options(**fields) -> RobeOptions:
     for k, v in fields.items():
         if k not in {f[0] for f in RobeOptions._fields_} or k == "reserved":
             raise TypeError(f"robe_options_t has no field {k!r}")
-        setattr(o, k, int(v))
+        setattr(o, k, v if k in ("probe_begin", "probe_end") else int(v))
     return o
 
 

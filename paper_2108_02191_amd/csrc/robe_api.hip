@@ -104,7 +104,18 @@ struct Opt {
     int fwd_elems = 0, fwd_strided = 0, bwd_elems = 0, bwd_strided = 0;
     int tile_lookups = 0, row_order = ROBE_ROWS_AUTO, tile_combine = 0, region_shift = 0, key_bits = 0;
     int region_records = 0;
+    int probe_kernel = ROBE_PROBE_NONE;
+    hipEvent_t probe_begin = nullptr, probe_end = nullptr;
 };
+
+// Record the caller's probe events around kernel `which` (see robe_options_t).
+int probe(const Opt &opt, int which, bool end, hipStream_t stream)
+{
+    if (opt.probe_kernel != which || opt.probe_begin == nullptr || opt.probe_end == nullptr) return ROBE_OK;
+    hipError_t st = hipEventRecord(end ? opt.probe_end : opt.probe_begin, stream);
+    if (st != hipSuccess) return fail(ROBE_EHIP, "probe event: %s", hipGetErrorString(st));
+    return ROBE_OK;
+}
 
 bool elems_ok(int v, int strided)
 {
@@ -132,7 +143,8 @@ int read_options(const robe_options_t *o, Opt *out)
         return fail(ROBE_EINVAL, "options: region_shift = %d outside 10..15", o->region_shift);
     if (o->key_bits != 0 && (o->key_bits < 8 || o->key_bits > 31)) return fail(ROBE_EINVAL, "options: key_bits = %d outside 8..31", o->key_bits);
     if (o->region_records < 0 || o->region_records > 2) return fail(ROBE_EINVAL, "options: region_records = %d outside 0..2", o->region_records);
-    if (o->reserved[0] | o->reserved[1] | o->reserved[2]) return fail(ROBE_EINVAL, "options: reserved fields must be zero");
+    if (o->probe_kernel < ROBE_PROBE_NONE || o->probe_kernel > ROBE_PROBE_SORT) return fail(ROBE_EINVAL, "options: probe_kernel = %d", o->probe_kernel);
+    if (o->reserved[0] | o->reserved[1]) return fail(ROBE_EINVAL, "options: reserved fields must be zero");
     out->reproducible = o->reproducible != 0;
     out->bwd_route = o->backward_route;
     out->fused_route = o->fused_route;
@@ -144,6 +156,9 @@ int read_options(const robe_options_t *o, Opt *out)
     out->region_shift = o->region_shift;
     out->key_bits = o->key_bits;
     out->region_records = o->region_records;
+    out->probe_kernel = o->probe_kernel;
+    out->probe_begin = (hipEvent_t)o->probe_begin;
+    out->probe_end = (hipEvent_t)o->probe_end;
     return ROBE_OK;
 }
 
@@ -626,9 +641,11 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
     // S2: sort (key, value) pairs by the top key_bits bits of the 31-bit key
     {
         bool in_b = false;
+        if (int rc = probe(opt, ROBE_PROBE_SORT, false, stream)) return rc;
         if (int rc = launch_radix_sort(keys_in, vals_in, keys_out, vals_out, n, 31 - pl.key_bits, 31, ws + pl.off_temp,
                                        stream, &in_b))
             return rc;
+        if (int rc = probe(opt, ROBE_PROBE_SORT, true, stream)) return rc;
         if (!in_b) {        // an even number of passes leaves the result in the first pair of buffers
             keys_out = keys_in;
             vals_out = vals_in;
@@ -665,6 +682,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
             r.rec_tg = reinterpret_cast<uint32_t *>(ws + pl.off_rec_tg);
         }
 
+        if (int rc = probe(opt, ROBE_PROBE_COMBINE, false, stream)) return rc;
         // R1: combine runs into P, leave one record per run (a lane group walks kStretch * G positions)
         const dim3 rgrid1((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * robe::kStretch - 1) / ((uint64_t)robe::kBlock * robe::kStretch)));
 #define ROBE_COMBINE_ROWS(V_)                                                                                         \
@@ -684,6 +702,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         }
 #undef ROBE_COMBINE_ROWS
         if (int rc = check_launch("backward (combine rows)")) return rc;
+        if (int rc = probe(opt, ROBE_PROBE_COMBINE, true, stream)) return rc;
 
         // R2..R4: records sorted by region (the gather variant of R5 does without)
         if (!pl.gather) {
@@ -725,15 +744,18 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         else if (pl.spill_rows) ROBE_REDUCE_C(S_, R_, false, true);                                                   \
         else ROBE_REDUCE_C(S_, R_, false, false);                                                                     \
     } while (0)
+        if (int rc = probe(opt, ROBE_PROBE_REDUCE, false, stream)) return rc;
         if (sign) { if (rule) ROBE_REDUCE(true, 1); else ROBE_REDUCE(true, 0); }
         else      { if (rule) ROBE_REDUCE(false, 1); else ROBE_REDUCE(false, 0); }
 #undef ROBE_REDUCE
 #undef ROBE_REDUCE_C
 #undef ROBE_REDUCE_G
-        return check_launch("backward (reduce)");
+        if (int rc = check_launch("backward (reduce)")) return rc;
+        return probe(opt, ROBE_PROBE_REDUCE, true, stream);
     }
     if (rule != 0) return fail(ROBE_EINVAL, "internal: fused update needs the region-sorted scatter");
 
+    if (int rc = probe(opt, ROBE_PROBE_COMBINE, false, stream)) return rc;
     // S3: combine runs and scatter with float atomics (a lane group walks kWalk * G positions)
     const dim3 sgrid((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * robe::kWalk - 1) / ((uint64_t)robe::kBlock * robe::kWalk)));
 #define ROBE_COMBINE(V_)                                                                                              \
@@ -752,7 +774,8 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         default: ROBE_COMBINE(4); break;
     }
 #undef ROBE_COMBINE
-    return check_launch("backward (combine and scatter)");
+    if (int rc = check_launch("backward (combine and scatter)")) return rc;
+    return probe(opt, ROBE_PROBE_COMBINE, true, stream);
 }
 
 int check_rows(const robe_hash_t *h, const int64_t *indices, const int64_t *offsets, int64_t n_indices,

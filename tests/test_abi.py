@@ -44,9 +44,9 @@ def test_struct_layout_matches_header():
     body = re.search(r"typedef struct robe_options_t \{(.*?)\} robe_options_t;", text, flags=re.S).group(1)
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     names = [n.strip().split("[")[0] for decl in body.split(";") if decl.strip()
-             for n in decl.replace("int32_t", "").split(",")]
+             for n in decl.replace("int32_t", "").replace("void", "").replace("*", "").split(",")]
     assert names == [f[0] for f in robe.RobeOptions._fields_]
-    assert ctypes.sizeof(robe.RobeOptions) == 16 * 4
+    assert ctypes.sizeof(robe.RobeOptions) == 16 * 4 + 2 * ctypes.sizeof(ctypes.c_void_p)
 
 
 @pytest.mark.parametrize("seed", [0, 1, 7, 2**40 + 3, 2**64 - 1])
