@@ -245,7 +245,10 @@ def main():
     if args.reproducible:
         fields["reproducible"] = 1
     opt = robe.options(**fields) if fields else None
-    ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n, opt) for n in tokens) if (do_bwd and w.dims is None) else 0
+    if do_bwd and w.dims is not None:
+        ws_bytes = max(robe.robe_mixed_workspace_bytes(h, w.dims, B, n, opt) for n in tokens)
+    else:
+        ws_bytes = max(robe.robe_workspace_bytes(h, B, F, n, opt) for n in tokens) if do_bwd else 0
     fused = do_ada and not args.unfused
     fws_bytes = max(robe.robe_fused_workspace_bytes(h, B, F, n, opt) for n in tokens) if fused else 0
     ws = torch.empty(max(ws_bytes, fws_bytes, 1), dtype=torch.uint8, device=dev) if max(ws_bytes, fws_bytes) else None
@@ -265,7 +268,7 @@ def main():
         if ev:
             ev[1].record(stream)
         if mixed:
-            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga, options=opt)
+            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga, workspace=ws, options=opt)
             if ev:
                 ev[2].record(stream)
             ga.zero_()
@@ -293,7 +296,7 @@ def main():
     if do_bwd:
         idd, offd = dev_batches[0]
         if mixed:
-            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga, options=opt)
+            robe.robe_backward_mixed(h, w.dims, Gd, idd, offd, B, ga, workspace=ws, options=opt)
         else:
             robe.robe_backward(h, Gd, idd, offd, B, F, ga, workspace=ws, options=opt)
         touched = int((ga != 0).sum().item())

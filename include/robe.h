@@ -321,24 +321,35 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
 /*
  * Tables of different embedding dimensions sharing the one array (Section 3.2, "Multiple embedding
  * tables": all tables, even with varying dimensions, share the array; the table id is an argument of
- * h and g).  Table f has dimension dims[f], a positive multiple of Z; its embedding is Eq. 4 / Eq. 5
- * with d = dims[f] (hash->d is not used).  A sample's row is the concatenation of its tables'
- * embeddings: out and grad_out are device float[batch][D], D = dims[0] + ... + dims[n_features-1],
- * table f at column dims[0] + ... + dims[f-1].  indices / offsets / n_indices / batch are as in
- * robe_forward; dims is a HOST array of n_features entries, read during the call only.
- * One launch is made per run of consecutive tables of equal dimension.  robe_backward_mixed
- * accumulates onto grad_array like robe_backward, always with float atomics (no workspace; it fails
- * with ROBE_EINVAL when options->reproducible is set); follow it with robe_adagrad_update /
- * robe_sgd_update.
- * Errors: ROBE_EINVAL (also: a dims entry that is zero or not a multiple of Z), ROBE_EHIP.
+ * h and g).  Table f has dimension dims[f], a positive multiple of Z or a divisor of it; its
+ * embedding is Eq. 4 / Eq. 5 with d = dims[f] (for a divisor: Section 3.3, Z / dims[f] consecutive
+ * tokens of the table share a block; hash->d is not used).  A sample's row is the concatenation of
+ * its tables' embeddings: out and grad_out are device float[batch][D], D = dims[0] + ... +
+ * dims[n_features-1], table f at column dims[0] + ... + dims[f-1].  indices / offsets / n_indices /
+ * batch are as in robe_forward; dims is a HOST array of n_features entries, read during the call only.
+ * robe_forward_mixed makes one launch per run of consecutive tables of equal dimension.
+ * robe_backward_mixed accumulates onto grad_array like robe_backward.  Large scatters (the size rule
+ * of robe_backward on the average dimension; every dimension a multiple of Z, the largest at most
+ * 512, batch * D below 2^32) sort the tokens of all tables once and combine repeated tokens before
+ * the atomics (ROBE_ROUTE_COMBINE; two tokens are the same when key and table agree); anything else
+ * is one direct scatter per run of equal dimensions.  There is no route without float atomics here:
+ * options->reproducible makes both calls fail with ROBE_EINVAL, and ROBE_ROUTE_REGIONS is taken as
+ * ROBE_ROUTE_COMBINE.  Follow it with robe_adagrad_update / robe_sgd_update.
+ *   workspace  device buffer of at least robe_mixed_workspace_bytes(...) bytes (same dims and
+ *              options), 256-byte aligned; may be NULL when that size is 0
+ * Errors: ROBE_EINVAL (also: a dims entry that is zero or neither a multiple nor a divisor of Z;
+ * workspace too small), ROBE_EHIP.
  */
 int robe_forward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *array,
                        const int64_t *indices, const int64_t *offsets, int64_t n_indices,
                        int64_t batch, int32_t n_features, float *out,
                        const robe_options_t *options, void *stream);
+int robe_mixed_workspace_bytes(const robe_hash_t *hash, const uint32_t *dims, int64_t batch, int32_t n_features,
+                               int64_t n_indices, const robe_options_t *options, size_t *bytes);
 int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out,
                         const int64_t *indices, const int64_t *offsets, int64_t n_indices,
                         int64_t batch, int32_t n_features, float *grad_array,
+                        void *workspace, size_t workspace_bytes,
                         const robe_options_t *options, void *stream);
 
 /*

@@ -607,7 +607,8 @@ int allow_lds(K kernel, size_t bytes, const char *what)
 int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &pl, const float *grad_out, const int64_t *indices,
                           const int64_t *offsets, int64_t n_indices, int64_t rows, uint32_t F,
                           float *grad_array, void *workspace, hipStream_t stream,
-                          int rule = 0, float *state = nullptr, float lr = 0.0f, float eps = 0.0f)
+                          int rule = 0, float *state = nullptr, float lr = 0.0f, float eps = 0.0f,
+                          const uint2 *tables = nullptr, int64_t sample_floats = 0)
 {
     const robe::Params p = to_params(h);
     char *ws = static_cast<char *>(workspace);
@@ -658,6 +659,8 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
     q.d = h->d;
     q.G = pl.lay.G;
     q.g_shift = log2u(pl.lay.G);
+    q.tables = tables;              // tables of mixed dimensions (atomic route only)
+    q.row_floats = sample_floats;
     const uint64_t blocks = ((uint64_t)n + robe::kBlock - 1) / robe::kBlock;   // one lane per sorted position
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
 
@@ -807,8 +810,8 @@ int launch_mixed(const robe_hash_t *hash, const Opt &opt, const uint32_t *dims, 
     if (dims == nullptr) return fail(ROBE_EINVAL, "dims is NULL");
     int64_t D = 0;
     for (int32_t f = 0; f < n_features; ++f) {
-        if (dims[f] < 1 || dims[f] % hash->Z != 0)
-            return fail(ROBE_EINVAL, "dims[%d] = %u is not a positive multiple of Z = %u", f, dims[f], hash->Z);
+        if (dims[f] < 1 || (dims[f] % hash->Z != 0 && hash->Z % dims[f] != 0))
+            return fail(ROBE_EINVAL, "dims[%d] = %u is neither a multiple nor a divisor of Z = %u", f, dims[f], hash->Z);
         D += dims[f];
         if (D > 0x7FFFFFFFll) return fail(ROBE_EINVAL, "sum of dims exceeds 2^31 - 1");
     }
@@ -990,15 +993,102 @@ int robe_forward_mixed(const robe_hash_t *hash, const uint32_t *dims, const floa
     return launch_mixed<false>(hash, opt, dims, array, indices, offsets, n_indices, batch, n_features, out, out, stream);
 }
 
+// Backward over tables of mixed dimensions: one token sort and one combine kernel for all tables
+// (duplicates combined, atomics once per distinct token) when the scatter is large enough, every
+// dimension is a multiple of Z and the largest has a lane layout; else one direct scatter per run of
+// equal dimensions.  The plan is host arithmetic shared by the query and the call.
+struct MixedPlan {
+    bool sorted;
+    BwdPlan pl;
+    robe_hash_t widest;     // the hash with d = the largest dimension: lane constants and the sort's plan
+    size_t off_tables, bytes;
+    int64_t D;
+};
+
+static int plan_mixed(const robe_hash_t *hash, const Opt &opt, const uint32_t *dims, int64_t batch, int32_t n_features,
+                      int64_t n_indices, bool bags, const void *grad_out, MixedPlan *mp)
+{
+    memset(mp, 0, sizeof(*mp));
+    if (dims == nullptr) return fail(ROBE_EINVAL, "dims is NULL");
+    uint32_t dmax = 0;
+    bool narrow = false;
+    int64_t D = 0;
+    for (int32_t f = 0; f < n_features; ++f) {
+        if (dims[f] < 1 || (dims[f] % hash->Z != 0 && hash->Z % dims[f] != 0))
+            return fail(ROBE_EINVAL, "dims[%d] = %u is neither a multiple nor a divisor of Z = %u", f, dims[f], hash->Z);
+        narrow = narrow || dims[f] < hash->Z;
+        dmax = dims[f] > dmax ? dims[f] : dmax;
+        D += dims[f];
+        if (D > 0x7FFFFFFFll) return fail(ROBE_EINVAL, "sum of dims exceeds 2^31 - 1");
+    }
+    mp->D = D;
+    mp->widest = *hash;
+    mp->widest.d = dmax;
+    if (opt.reproducible) return ROBE_OK;                   // (the caller refuses: no route without float atomics here)
+    if (opt.bwd_route == ROBE_ROUTE_DIRECT || narrow || batch < 1 || n_indices < 1) return ROBE_OK;
+    if ((uint64_t)batch * (uint64_t)D >= 0xFFFFFFFFull) return ROBE_OK;           // 32-bit row starts in the combine kernel
+    const bool forced = opt.bwd_route == ROBE_ROUTE_COMBINE || opt.bwd_route == ROBE_ROUTE_REGIONS;
+    // the same size rule as robe_backward, on the average dimension
+    if (!forced && (uint64_t)n_indices * (uint64_t)(D / n_features) < (1ull << 25)) return ROBE_OK;
+    Opt sorted = opt;
+    sorted.bwd_route = ROBE_ROUTE_COMBINE;
+    mp->pl = plan_backward(&mp->widest, sorted, batch * (int64_t)n_features, n_indices, bags, grad_out);
+    if (!mp->pl.dedup || mp->pl.regions) return ROBE_OK;
+    mp->sorted = true;
+    mp->off_tables = mp->pl.bytes;
+    mp->bytes = align_up(mp->pl.bytes + (size_t)n_features * sizeof(uint2), 256);
+    return ROBE_OK;
+}
+
+int robe_mixed_workspace_bytes(const robe_hash_t *hash, const uint32_t *dims, int64_t batch, int32_t n_features,
+                               int64_t n_indices, const robe_options_t *options, size_t *bytes)
+{
+    Opt opt;
+    if (int rc = check_query(hash, batch, n_features, n_indices, options, bytes, &opt)) return rc;
+    if (opt.reproducible) return fail_not_reproducible();
+    MixedPlan mp;
+    if (int rc = plan_mixed(hash, opt, dims, batch, n_features, n_indices, true, nullptr, &mp)) return rc;
+    *bytes = mp.sorted ? mp.bytes : 0;
+    return ROBE_OK;
+}
+
 int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out, const int64_t *indices,
                         const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features,
-                        float *grad_array, const robe_options_t *options, void *stream)
+                        float *grad_array, void *workspace, size_t workspace_bytes,
+                        const robe_options_t *options, void *stream)
 {
     Opt opt;
     if (int rc = read_options(options, &opt)) return rc;
     if (opt.reproducible) return fail_not_reproducible();
-    return launch_mixed<true>(hash, opt, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
-                              grad_out, stream);
+    int64_t rows = 0;
+    if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
+    MixedPlan mp;
+    if (int rc = plan_mixed(hash, opt, dims, batch, n_features, n_indices, offsets != nullptr, grad_out, &mp)) return rc;
+    if (!mp.sorted)
+        return launch_mixed<true>(hash, opt, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
+                                  grad_out, stream);
+    if (workspace == nullptr || workspace_bytes < mp.bytes)
+        return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", mp.bytes, workspace_bytes);
+    if (!aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
+    if (grad_out == nullptr || grad_array == nullptr) return fail(ROBE_EINVAL, "grad_out or grad_array is NULL");
+    if (!aligned(grad_out, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    uint2 *tables = reinterpret_cast<uint2 *>(static_cast<char *>(workspace) + mp.off_tables);
+    uint32_t col = 0;
+    for (int32_t f0 = 0; f0 < n_features; f0 += robe::kTableArgs) {
+        robe::TableArgs a;
+        memset(&a, 0, sizeof(a));
+        const int32_t cnt = n_features - f0 < robe::kTableArgs ? n_features - f0 : robe::kTableArgs;
+        for (int32_t k = 0; k < cnt; ++k) {
+            a.col[k] = col;
+            a.dim[k] = dims[f0 + k];
+            col += dims[f0 + k];
+        }
+        robe::table_map_kernel<<<dim3(1), dim3(64), 0, s>>>(a, (uint32_t)f0, (uint32_t)cnt, tables);
+        if (int rc = check_launch("backward (table map)")) return rc;
+    }
+    return launch_dedup_backward(&mp.widest, opt, mp.pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
+                                 grad_array, workspace, s, 0, nullptr, 0.0f, 0.0f, tables, mp.D);
 }
 
 // The address of `scratch` on the current device.  In host code the array's name is only a handle

@@ -95,6 +95,18 @@ __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, u
     }
 }
 
+// Tables of mixed dimensions: the per-table map (first float inside a sample, dimension) that the
+// combine kernel looks rows up in, written from kernel arguments, kTableArgs tables per launch.
+constexpr int kTableArgs = 64;
+struct TableArgs {
+    uint32_t col[kTableArgs], dim[kTableArgs];
+};
+
+__global__ __launch_bounds__(64) void table_map_kernel(TableArgs a, uint32_t first, uint32_t count, uint2 *__restrict__ tables)
+{
+    if (threadIdx.x < count) tables[first + threadIdx.x] = make_uint2(a.col[threadIdx.x], a.dim[threadIdx.x]);
+}
+
 // S3.  Lane layout as in the direct scatter: G lanes per row, lane `grp` owns elements grp + k*G.
 template <int V, bool SIGN, bool BAGS>
 __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom q,
@@ -119,7 +131,7 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
     float acc[V];
 #pragma unroll
     for (int k = 0; k < V; ++k) acc[k] = 0.0f;
-    uint32_t run_th = 0, run_tg = 0;
+    uint32_t run_th = 0, run_tg = 0, run_d = q.d;
     bool open = false;
     // the last token of the stretch before (none before the first stretch)
     uint32_t c_th = 0, c_e = 0, c_xlo = 0, c_xhi = 0;
@@ -130,7 +142,7 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
         if (__all(i0 >= n_indices)) break;                   // every group of the wavefront is past the end
 
         // lane l of the group looks at sorted position i0 + l
-        uint32_t my_th = 0, my_tg = 0, my_row = 0, my_e = 0;
+        uint32_t my_th = 0, my_tg = 0, my_at = 0, my_d = q.d, my_e = 0;   // my_at: the token's gradient row (mixed dimensions: its first float)
         int64_t my_x = 0;
         bool my_ok = false;
         if (i0 + grp < n_indices) {
@@ -138,11 +150,16 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
             const uint32_t row = !SIGN ? t : (t < n_indices ? (BAGS ? tok_bag[t] : t) : rows);
             if (row < rows) {
                 my_ok = true;
-                my_row = row;
+                my_at = row;
                 my_th = keys[i0 + grp];
+                if (SIGN || q.tables != nullptr) my_e = row % q.F;
+                if (q.tables != nullptr) {                      // tables of mixed dimensions
+                    const uint2 tab = q.tables[my_e];
+                    my_at = (row / q.F) * (uint32_t)q.row_floats + tab.x;
+                    my_d = tab.y;
+                }
                 if constexpr (SIGN) {
                     my_x = indices[t];
-                    my_e = row % q.F;
                     my_tg = staged_g(p, my_x, my_e);
                 }
             }
@@ -156,6 +173,11 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
             p_ok = c_ok;
         }
         bool my_head = !p_ok || p_th != my_th;
+        if (!SIGN && q.tables != nullptr) {     // equal keys of two tables (a hash collision) may differ in dimension: not one run
+            uint32_t p_e = __shfl(my_e, prev);
+            if (grp == 0) p_e = c_e;
+            my_head = my_head || p_e != my_e;
+        }
         if constexpr (SIGN) {
             uint32_t p_e = __shfl(my_e, prev);
             uint32_t p_xlo = __shfl((uint32_t)my_x, prev), p_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), prev);
@@ -168,26 +190,28 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
         }
 
         for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsInFlight) {     // same trip count for every lane of the wavefront
-            uint32_t row[kRowsInFlight], th[kRowsInFlight], tg[kRowsInFlight];
+            uint32_t at[kRowsInFlight], dd[kRowsInFlight], th[kRowsInFlight], tg[kRowsInFlight];
             bool ok[kRowsInFlight], head[kRowsInFlight];
 #pragma unroll
             for (int u = 0; u < kRowsInFlight; ++u) {
                 const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
                 ok[u] = (k0 + u < q.G) && __shfl((int)my_ok, from) != 0;
-                row[u] = __shfl(my_row, from);
+                at[u] = __shfl(my_at, from);
+                dd[u] = q.tables != nullptr ? __shfl(my_d, from) : q.d;
                 th[u] = __shfl(my_th, from);
                 tg[u] = SIGN ? __shfl(my_tg, from) : 0u;
                 head[u] = __shfl((int)my_head, from) != 0;
-                if (!ok[u]) row[u] = 0;                        // any valid row: its values are discarded
+                if (!ok[u]) at[u] = 0;                         // any valid row: its values are discarded
             }
             float v[kRowsInFlight][V];
 #pragma unroll
-            for (int u = 0; u < kRowsInFlight; ++u) load_row<V, false, BAGS>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+            for (int u = 0; u < kRowsInFlight; ++u)
+                load_row_of<V, BAGS>(grad_out + (q.tables != nullptr ? (uint64_t)at[u] : (uint64_t)at[u] * p.d), q.G, dd[u], grp, v[u]);
 #pragma unroll
             for (int u = 0; u < kRowsInFlight; ++u) {
                 if (!ok[u]) continue;
                 if (head[u] && open) {
-                    L.scatter(p, grad_array, run_th, run_tg, acc);
+                    L.scatter(p, grad_array, run_th, run_tg, acc, 0, grp, q.G, run_d);
 #pragma unroll
                     for (int k = 0; k < V; ++k) acc[k] = 0.0f;
                 }
@@ -195,19 +219,21 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
                 for (int k = 0; k < V; ++k) acc[k] += v[u][k];
                 run_th = th[u];
                 run_tg = tg[u];
+                run_d = dd[u];
                 open = true;
             }
         }
         const int last = (int)(base_lane + q.G - 1u);
         c_th = __shfl(my_th, last);
         c_ok = __shfl((int)my_ok, last) != 0;
+        if (!SIGN && q.tables != nullptr) c_e = __shfl(my_e, last);
         if constexpr (SIGN) {
             c_e = __shfl(my_e, last);
             c_xlo = __shfl((uint32_t)my_x, last);
             c_xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), last);
         }
     }
-    if (open) L.scatter(p, grad_array, run_th, run_tg, acc);
+    if (open) L.scatter(p, grad_array, run_th, run_tg, acc, 0, grp, q.G, run_d);
 }
 
 }  // namespace robe

@@ -43,6 +43,10 @@ struct Geom {
     uint32_t e0;         // table id of this launch's first table = its place in a sample's input row
     int64_t row_floats;  // floats per sample in out / grad_out
     int64_t col0;        // first float of this launch's first table inside a sample
+    // Sorted backward over tables of different dimensions (one launch for all of them): per table its
+    // first float inside a sample (.x) and its dimension (.y); d above is then the largest dimension.
+    // NULL: every table has dimension d and row k starts at float k * d.
+    const uint2 *tables;
 };
 
 // One row of a launch: where its id (or bag bounds) and its d floats live, and its table id.
@@ -212,14 +216,17 @@ struct Lane {
     }
 
     // grad_array[idx] += g * v[k] for the V owned elements of one token.
+    // own: the lane's first element (grp in the strided layout); dlim: elements at or past it do not
+    // exist in this row (tables of mixed dimensions; the lane constants are those of the largest).
     __device__ __forceinline__ void scatter(const Params &p, float *__restrict__ grad_array,
-                                            uint32_t th, uint32_t tg, const float (&v)[V], uint32_t place = 0) const
+                                            uint32_t th, uint32_t tg, const float (&v)[V], uint32_t place = 0,
+                                            uint32_t own = 0, uint32_t stride = 0, uint32_t dlim = 0xFFFFFFFFu) const
     {
         const uint32_t pos0 = CONSEC ? position(p, th, 0, place) : 0u;
 #pragma unroll
         for (int k = 0; k < V; ++k) {
             // CONSEC: every element wraps on its own
-            if (!has(k)) continue;
+            if (!has(k) || own + (uint32_t)k * stride >= dlim) continue;
             const uint32_t pos = CONSEC ? wrap(pos0 + (uint32_t)k, p.m) : position(p, th, k, place);
             const float val = SIGN ? apply_sign(v[k], mask(tg, k)) : v[k];
             __hip_atomic_fetch_add(grad_array + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -245,6 +252,18 @@ __device__ __forceinline__ void store_row(float *__restrict__ row, const Geom &q
 
 // KEEP: the row will be read again soon (the tokens of a bag all read the bag's row), so it is loaded
 // with the default cache policy; otherwise it is streamed past the caches' resident lines.
+// (strided layout) the same for a row of d elements, d <= q.d
+template <int V, bool KEEP>
+__device__ __forceinline__ void load_row_of(const float *__restrict__ row, uint32_t G, uint32_t d, uint32_t grp, float (&v)[V])
+{
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const uint32_t i = grp + (uint32_t)k * G;
+        const float *at = row + (i < d ? i : 0u);           // idle slots read element 0; nobody stores their value
+        v[k] = KEEP ? *at : __builtin_nontemporal_load(at);
+    }
+}
+
 template <int V, bool CONSEC, bool KEEP = false>
 __device__ __forceinline__ void load_row(const float *__restrict__ row, const Geom &q, uint32_t grp, float (&v)[V])
 {

@@ -40,12 +40,17 @@ CASES = [
     (4099, (1, 5, 2, 7, 64, 1), 1),
     (61, (16, 8, 8, 32), 8),
     (500_009, (256, 512, 128), 128),
+    (100_003, (4, 16, 64, 8, 16, 2), 16),       # tables narrower than the block: 4, 2 and 8 tokens share one (Section 3.3)
+    (70_001, (1, 3, 6, 12), 6),
 ]
+ROUTES = [robe.ROUTE_DIRECT, robe.ROUTE_COMBINE]
 
 
+@pytest.mark.parametrize("route", ROUTES)
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,dims,Z", CASES)
-def test_mixed_single_hot_forward_is_bit_exact_and_backward_within_tolerance(m, dims, Z, sign):
+def test_mixed_single_hot_forward_is_bit_exact_and_backward_within_tolerance(m, dims, Z, sign, route):
+    opt = robe.options(backward_route=route)
     h, H = hashes(7 * m + Z + sign, m, Z, sign, max(dims))
     F, B = len(dims), 257
     rng = np.random.default_rng(m + sum(dims))
@@ -56,19 +61,29 @@ def test_mixed_single_hot_forward_is_bit_exact_and_backward_within_tolerance(m, 
     assert bits_equal(out, oracle.forward_mixed(H, dims, M, ids, None, B))
     G = rng.standard_normal((B, sum(dims))).astype(np.float32)
     ga = torch.zeros(m, dtype=torch.float32, device=DEV)
-    robe.robe_backward_mixed(h, dims, dev(G), dev(ids), None, B, ga)
+    sorted_route = route == robe.ROUTE_COMBINE and min(dims) >= Z and max(dims) <= 512
+    assert (robe.robe_mixed_workspace_bytes(h, dims, B, ids.size, opt) > 0) == sorted_route
+    robe.robe_backward_mixed(h, dims, dev(G), dev(ids), None, B, ga, options=opt)
     ref, S = oracle.backward_mixed(H, dims, G, ids, None, B)
     got = ga.cpu().numpy()
     assert np.all(np.abs(got.astype(np.float64) - ref) <= 1e-5 * S + TINY)
     assert not got[S == 0].any()
     # accumulates onto what is there
-    robe.robe_backward_mixed(h, dims, dev(G), dev(ids), None, B, ga)
+    robe.robe_backward_mixed(h, dims, dev(G), dev(ids), None, B, ga, options=opt)
     assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - 2 * ref) <= 2e-5 * S + TINY)
+    # small-integer gradients: exact in any order
+    Gi = rng.integers(-3, 4, size=(B, sum(dims))).astype(np.float32)
+    ga.zero_()
+    robe.robe_backward_mixed(h, dims, dev(Gi), dev(ids), None, B, ga, options=opt)
+    refi, _ = oracle.backward_mixed(H, dims, Gi, ids, None, B)
+    assert np.array_equal(ga.cpu().numpy().astype(np.float64), refi)
 
 
+@pytest.mark.parametrize("route", ROUTES)
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,dims,Z", CASES)
-def test_mixed_bags_within_tolerance(m, dims, Z, sign):
+def test_mixed_bags_within_tolerance(m, dims, Z, sign, route):
+    opt = robe.options(backward_route=route)
     h, H = hashes(11 * m + Z + sign, m, Z, sign, max(dims))
     F, B = len(dims), 131
     rng = np.random.default_rng(m + 1)
@@ -86,7 +101,7 @@ def test_mixed_bags_within_tolerance(m, dims, Z, sign):
     assert np.all(np.abs(out.astype(np.float64) - want) <= 1e-5 * S + TINY)
     G = rng.standard_normal((B, sum(dims))).astype(np.float32)
     ga = torch.zeros(m, dtype=torch.float32, device=DEV)
-    robe.robe_backward_mixed(h, dims, dev(G), dev(flat), dev(off), B, ga)
+    robe.robe_backward_mixed(h, dims, dev(G), dev(flat), dev(off), B, ga, options=opt)
     ref, Sb = oracle.backward_mixed(H, dims, G, flat, off, B)
     assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * Sb + TINY)
 
@@ -106,7 +121,7 @@ def test_mixed_rejects_bad_dimensions_and_the_reproducible_option():
     h, _ = hashes(1, 1000, 4, 0, 16)
     ids = dev(np.zeros((2, 3), dtype=np.int64))
     M = torch.zeros(1000, dtype=torch.float32, device=DEV)
-    for dims in ([16, 6, 4], [16, 0, 4], [2, 4, 4]):
+    for dims in ([16, 6, 4], [16, 0, 4], [3, 4, 4]):
         with pytest.raises(robe.RobeError) as ei:
             robe.robe_forward_mixed(h, dims, M, ids, None, 2)
         assert ei.value.code == robe.ROBE_EINVAL
@@ -114,3 +129,20 @@ def test_mixed_rejects_bad_dimensions_and_the_reproducible_option():
         robe.robe_backward_mixed(h, [16, 4, 4], torch.zeros((2, 24), dtype=torch.float32, device=DEV), ids, None, 2, M,
                                  options=robe.options(reproducible=1))
     assert robe.robe_forward_mixed(h, [16, 4, 4], M, dev(np.zeros((0, 3), dtype=np.int64)), None, 0).shape == (0, 24)
+
+
+def test_mixed_sorted_route_keeps_equal_keys_of_different_tables_apart():
+    # Two tables of different dimension whose tokens share a sort key: with 8 key bits nearly all
+    # neighbours in the sorted list do.  A run must end where the table changes even if the key does not.
+    m, Z, dims = 200_003, 4, (8, 32, 8, 16, 4, 64)
+    h, H = hashes(9, m, Z, 0, max(dims))
+    B = 700
+    rng = np.random.default_rng(1)
+    ids = rng.integers(0, 30, size=(B, len(dims)), dtype=np.int64)
+    Gi = rng.integers(-3, 4, size=(B, sum(dims))).astype(np.float32)
+    for kb in (8, 31):
+        opt = robe.options(backward_route=robe.ROUTE_COMBINE, key_bits=kb)
+        ga = torch.zeros(m, dtype=torch.float32, device=DEV)
+        robe.robe_backward_mixed(h, dims, dev(Gi), dev(ids), None, B, ga, options=opt)
+        ref, _ = oracle.backward_mixed(H, dims, Gi, ids, None, B)
+        assert np.array_equal(ga.cpu().numpy().astype(np.float64), ref), kb

@@ -115,6 +115,9 @@ def test_random_problems_match_the_oracle(chunk):
         # tables of mixed dimensions (multiples of Z), single-hot forward bit-exact, backward exact
         if Z <= 64:
             dims = [int(Z * rng.integers(1, 5)) for _ in range(F)]
+            if rng.random() < 0.3:                                    # some tables narrower than the block
+                divs = [z for z in range(1, Z + 1) if Z % z == 0]
+                dims[0] = int(rng.choice(divs))
             if F > 2:
                 dims[1] = dims[0]                                     # a run of equal dimensions
             outm = robe.robe_forward_mixed(h, dims, dev(M), dev(ids), None, B, options=opt).cpu().numpy()
