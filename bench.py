@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--m", type=int, default=0, help="override the array length in floats (0: as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--reproducible", action="store_true",
-                    help="time the step with robe_set_reproducible(1): region-sorted backward, canonical addition order")
+                    help="time the step with robe_options_t::reproducible set: no float atomics, canonical addition order")
     ap.add_argument("--unfused", action="store_true",
                     help="time robe_backward and robe_adagrad_update as separate calls inside the step "
                          "(default: the fused robe_backward_adagrad; the separate calls are then timed beside it)")
@@ -560,7 +560,8 @@ def main():
                 "kernel_sources": kernel_sources_hash()}
     else:       # tables of mixed dimensions: several launches per call, the call is the unit
         dom = max(in_step, key=lambda n: kernels[n]["ms"])
-        roof = {"kernel": "robe_%s_mixed (one launch per run of equal dimensions)" % ("backward" if dom == "bwd" else "forward"),
+        roof = {"kernel": ("robe_backward_mixed (whole call: token sort, then one combine kernel over all tables)" if dom == "bwd"
+                           else "robe_forward_mixed (whole call: one launch per run of equal dimensions)"),
                 "bound": "hbm", "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": prof["phase"].get(dom) if prof else None,
                 "ms": kernels[dom]["ms"], "kernel_sources": kernel_sources_hash()}
