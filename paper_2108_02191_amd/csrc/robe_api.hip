@@ -410,7 +410,9 @@ struct BwdPlan {
     bool spill_rows;     // ... with room in LDS for a row of Z floats per lane group of the reduce kernel
     bool gather;         // ... and the reduce kernel finds its blocks in the sorted token list (no record kernels)
     Layout lay;
-    uint32_t key_bits;   // most significant key bits the sort looks at
+    robe_hash_t eff;     // the instance the kernels after the key kernel run on: the caller's, or (Z > d) its one-chunk form
+    uint32_t key_top;    // keys are below 2^key_top
+    uint32_t key_bits;   // most significant key bits (below key_top) the sort looks at
     size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_tok_bag, off_temp, temp_bytes, bytes;
     // regions only
     robe::RegionPlan rp;
@@ -430,7 +432,7 @@ bool regions_by_default(const robe_hash_t *h, int64_t n_indices)
 int fail_not_reproducible()
 {
     return fail(ROBE_EINVAL, "reproducible option: this shape or size has no route without float atomics "
-                             "(it needs Z <= d <= 512, d / Z and the lane group a power of two, at most 2^30 array slots, "
+                             "(it needs d <= 512, d / Z and the lane group a power of two, at most 2^30 array slots, "
                              "32-bit record counts and a region size that leaves no short last region)");
 }
 
@@ -453,11 +455,21 @@ uint32_t ceil_log2(uint64_t v) { uint32_t s = 0; while ((1ull << s) < v) ++s; re
 // Decide between the direct scatter, the combine-duplicates one and the region-sorted one, and lay
 // out the workspace.  Host arithmetic only, so that the workspace queries and the calls agree.
 // need_regions: the caller (the fused step) wants the region-sorted scatter whatever the size.
-BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_t n_indices, bool bags,
+BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t rows, int64_t n_indices, bool bags,
                       const void *grad_out, bool need_regions = false)
 {
     BwdPlan pl;
     memset(&pl, 0, sizeof(pl));
+    // Blocks larger than embeddings (Z > d, Section 3.3): a token writes one piece of d slots, and the
+    // sort key is that piece's array offset (sort_key in robe_backward_dedup.h).  From the sort on the
+    // problem is an instance with blocks of d slots, one chunk per embedding and keys below m.
+    pl.eff = *caller_hash;
+    pl.key_top = 31;
+    if (caller_hash->Z > caller_hash->d) {
+        pl.eff.Z = caller_hash->d;
+        pl.key_top = ceil_log2(caller_hash->m) ? ceil_log2(caller_hash->m) : 1u;
+    }
+    const robe_hash_t *h = &pl.eff;
     int route = opt.bwd_route;
     if (opt.reproducible) {
         need_regions = true;   // the only route without float atomics
@@ -468,12 +480,13 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
     // 32-bit positions and row numbers
     if (rows < 1 || n_indices < 1 || rows >= 0x7FFFFFFFll || n_indices >= 0x7FFFFFFFll) return pl;
     if (pick_layout(h, true, grad_out, opt, &pl.lay) != ROBE_OK) return pl;   // the launch reports the bad layout
-    if (pl.lay.V == 0 || pl.lay.consec || h->Z > h->d) return pl;   // shapes the sorted routes do not handle
+    if (pl.lay.V == 0 || pl.lay.consec) return pl;   // shapes the sorted routes do not handle
     // sorting costs about 0.1 ms plus 45 ns per thousand tokens: not worth it for small scatters
     if (!forced && (uint64_t)n_indices * h->d < (1ull << 25)) return pl;
     // Sorting on the top 24 key bits is one radix pass cheaper; tokens that share those bits merely
     // interleave and are merged less often, which stays rare while there are far fewer tokens than 2^24.
     pl.key_bits = opt.key_bits ? (uint32_t)opt.key_bits : (n_indices <= (1ll << 24) ? 24u : 31u);
+    if (pl.key_bits > pl.key_top) pl.key_bits = pl.key_top;
 
     const size_t n = (size_t)n_indices;
     const size_t temp = radix_sort_temp_bytes(n);
@@ -491,7 +504,7 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
     // Region-sorted scatter on top of the combined runs.
     const bool want_regions = need_regions || (route == ROBE_ROUTE_AUTO ? regions_by_default(h, n_indices) : route == ROBE_ROUTE_REGIONS);
     if (!want_regions) return pl;
-    const uint64_t C = h->d / h->Z;                       // Z <= d here (lay.V != 0)
+    const uint64_t C = h->d / h->Z;                       // Z <= d here
     uint32_t lg = 8;  // lanes per record in the reduce kernel: at most 64 groups per workgroup, a group inside one wavefront
     while (lg < robe::kMaxRecordLanes && lg < h->Z) lg <<= 1;
     static_assert(robe::kMaxRecordLanes <= 64 && (robe::kMaxRecordLanes & (robe::kMaxRecordLanes - 1)) == 0,
@@ -556,6 +569,7 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
     r.rows = (uint32_t)rows;
     r.src_blocks = (uint32_t)(((uint64_t)rows + p_rows) * C);
     r.p_quota = p_quota;
+    r.key_mask = pl.key_top >= 31 ? (uint32_t)ROBE_PRIME : (1u << pl.key_top) - 1u;
     r.bin_blocks = NR * 4 > 80 * 1024 ? 256u : 512u;      // one or two workgroups per CU by LDS
     if (n < (size_t)r.bin_blocks * 1024) r.bin_blocks = (uint32_t)((n + 1023) / 1024);
     r.pos_per_block = (uint32_t)((n + r.bin_blocks - 1) / r.bin_blocks);
@@ -576,7 +590,7 @@ BwdPlan plan_backward(const robe_hash_t *h, const Opt &opt, int64_t rows, int64_
         uint32_t bits = ceil_log2(n) > 1 ? ceil_log2(n) - 1 : 1;
         if (bits > 22) bits = 22;
         if (bits > pl.key_bits) bits = pl.key_bits;
-        r.dir_shift = 31 - bits;
+        r.dir_shift = pl.key_top - bits;
         r.dir_buckets = 1u << bits;
         r.epc = (uint32_t)(((uint64_t)ROBE_PRIME - 1) / h->m + 3);
         r.NE = (uint32_t)(C * r.epc);
@@ -610,6 +624,8 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
                           int rule = 0, float *state = nullptr, float lr = 0.0f, float eps = 0.0f,
                           const uint2 *tables = nullptr, int64_t sample_floats = 0)
 {
+    const robe::Params p_keys = to_params(h);     // the caller's instance: S1 hashes the ids with it
+    h = &pl.eff;                                  // everything after S1 (see plan_backward)
     const robe::Params p = to_params(h);
     char *ws = static_cast<char *>(workspace);
     uint32_t *keys_in = reinterpret_cast<uint32_t *>(ws + pl.off_keys_in);
@@ -634,16 +650,16 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
     if (key_blocks > 65536) key_blocks = 65536;
     const dim3 kgrid((uint32_t)key_blocks), kblock(256);
     // sign off: the sorted value is the token's row of grad_out and positions are never needed again
-    if (bags && sign) robe::token_keys_kernel<true, false><<<kgrid, kblock, 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
-    else if (bags) robe::token_keys_kernel<true, true><<<kgrid, kblock, 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
-    else robe::token_keys_kernel<false, true><<<kgrid, kblock, 0, stream>>>(p, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    if (bags && sign) robe::token_keys_kernel<true, false><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    else if (bags) robe::token_keys_kernel<true, true><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    else robe::token_keys_kernel<false, true><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
     if (int rc = check_launch("backward (keys)")) return rc;
 
-    // S2: sort (key, value) pairs by the top key_bits bits of the 31-bit key
+    // S2: sort (key, value) pairs by the top key_bits bits of the key
     {
         bool in_b = false;
         if (int rc = probe(opt, ROBE_PROBE_SORT, false, stream)) return rc;
-        if (int rc = launch_radix_sort(keys_in, vals_in, keys_out, vals_out, n, 31 - pl.key_bits, 31, ws + pl.off_temp,
+        if (int rc = launch_radix_sort(keys_in, vals_in, keys_out, vals_out, n, pl.key_top - pl.key_bits, pl.key_top, ws + pl.off_temp,
                                        stream, &in_b))
             return rc;
         if (int rc = probe(opt, ROBE_PROBE_SORT, true, stream)) return rc;

@@ -9,6 +9,7 @@
 //   S1 keys     every token gets the key th = (Bh*x + Ah*e + Dh) mod P - the token
 //               part of its offset hash, equal for equal (e, x) - and a value: its
 //               row of grad_out when the sign is off, its position when it is on.
+//               (Blocks larger than embeddings: the key is the array offset itself, see sort_key.)
 //   S2 sort     stable radix sort of (key, value) pairs (robe_radix_sort.h, or the device library's).
 //   S3 combine  a group of G lanes walks G consecutive sorted tokens, adds the
 //               gradient rows of runs of identical tokens in registers, and issues
@@ -41,6 +42,18 @@ constexpr int kWalk = 1;           // stretches of G sorted positions a lane gro
 // two dependent trips to memory), grid-stride over such sets; single-hot: one lane per lookup.
 constexpr int kKeyBags = 4;        // eight measured the same, sixteen slower
 
+// The sort key of a token.  Z <= d: the token part of the offset hash.  Z > d (Section 3.3): the token
+// has one piece of d slots, at its place inside the chunk it shares with r - 1 neighbours; the array
+// offset of that piece, below m, says all there is to say about where the token writes, so it is the
+// key, and every kernel after the sort runs on the instance (Z' = d, one chunk, key = offset).
+__device__ __forceinline__ uint32_t sort_key(const Params &p, int64_t x, uint32_t e)
+{
+    if (p.r == 0) return staged_h(p, x, e);
+    uint32_t place;
+    const int64_t chunk = block_key(p, x, place);
+    return wrap(offset_of(p, staged_h(p, chunk, e), 0u) + place, p.m);
+}
+
 template <bool BAGS, bool ROWVAL>
 __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, uint32_t g_shift,
                                                          const int64_t *__restrict__ indices,
@@ -55,7 +68,7 @@ __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, u
     const uint64_t group = ((uint64_t)blockIdx.x * 256u + threadIdx.x) >> g_shift;
     if constexpr (!BAGS) {
         for (uint64_t k = group; k < rows; k += groups) {      // G = 1: one lookup per lane
-            keys[k] = staged_h(p, indices[k], (uint32_t)k % F);
+            keys[k] = sort_key(p, indices[k], (uint32_t)k % F);
             vals[k] = (uint32_t)k;
         }
     } else {
@@ -81,12 +94,12 @@ __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, u
                 const uint32_t e = bag % F;
                 int64_t t = t0[j] + lane;
                 if (t < t1[j]) {
-                    keys[t] = staged_h(p, x[j], e);
+                    keys[t] = sort_key(p, x[j], e);
                     vals[t] = ROWVAL ? bag : (uint32_t)t;
                     if constexpr (!ROWVAL) tok_bag[t] = bag;
                 }
                 for (t += G; t < t1[j]; t += G) {              // bags longer than the lane group
-                    keys[t] = staged_h(p, indices[t], e);
+                    keys[t] = sort_key(p, indices[t], e);
                     vals[t] = ROWVAL ? bag : (uint32_t)t;
                     if constexpr (!ROWVAL) tok_bag[t] = bag;
                 }

@@ -66,6 +66,7 @@ struct RegionPlan {
     // kmax = (P - 1) / m; dir[b] is the first sorted position whose key >> dir_shift is >= b
     // (dir[buckets] = n), written by R1; NULL when R2..R4 run instead
     uint32_t NE, epc, epc_recip, dir_shift, dir_buckets;   // epc_recip = ceil(2^16 / epc)
+    uint32_t key_mask;       // the key bits: 2^31 - 1, or fewer when the keys are array offsets (blocks larger than embeddings)
     uint32_t *dir;
     const uint32_t *keys;    // sorted keys
     uint8_t *head;           // [n]  1: a run starts here
@@ -222,9 +223,9 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
             const uint64_t pos = i0 + grp;
             uint32_t blo = 1, bhi = 0;                           // empty
             if (pos < n) {
-                // (bit 31 is no key bit: the sort ignores it, so it is masked to keep the buckets in order)
-                blo = pos == 0 ? 0u : ((before.th & kP) >> s.dir_shift) + 1u;
-                bhi = (cur.th & kP) >> s.dir_shift;
+                // (bits above the key bits: the sort ignores them, so they are masked to keep the buckets in order)
+                blo = pos == 0 ? 0u : ((before.th & s.key_mask) >> s.dir_shift) + 1u;
+                bhi = (cur.th & s.key_mask) >> s.dir_shift;
             }
             const bool any = blo <= bhi, wide = any && bhi - blo >= 16u;
             if (any && !wide)
@@ -690,9 +691,10 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
         uint32_t pa = 0, pb = 0;
         if (threadIdx.x < s.NE) {
             const KeyRange kr = key_range(p, s, threadIdx.x, r0, region_len);
-            if (kr.ta < kr.tb) {
+            const uint32_t tb = kr.tb <= s.key_mask ? kr.tb : s.key_mask + 1u;      // no key has a bit above the mask
+            if (kr.ta < kr.tb && kr.ta < tb) {
                 pa = s.dir[kr.ta >> s.dir_shift];
-                pb = s.dir[((kr.tb - 1u) >> s.dir_shift) + 1u];
+                pb = s.dir[((tb - 1u) >> s.dir_shift) + 1u];
             }
         }
         // (the region is cleared while the directory entries are on their way)

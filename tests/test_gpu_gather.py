@@ -54,6 +54,9 @@ CASES = [
     (2**27 + 3, 128, 64, 1, 16, 0),            # a coarse sort key: distinct tokens share keys, wide directory buckets
     (40_000_003, 32, 16, 0, 8, 14),            # 8 key bits: 256 directory buckets; regions of 2^14 floats; 112 entries
     (250_000_000, 128, 32, 1, 0, 0),           # the headline shape, sign on
+    (2**26 + 3, 16, 64, 0, 0, 0),              # blocks larger than embeddings: keys are array offsets below 2^27
+    (45_000_007, 32, 128, 1, 0, 0),            # the same with the sign, keys below 2^26
+    (70_000_001, 8, 24, 0, 12, 0),             # three embeddings per block, 12 key bits of 27
 ]
 
 

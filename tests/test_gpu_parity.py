@@ -344,7 +344,8 @@ def _check_fused(h, H, Gi, ids, off, B, F, m, shift=0, options=None):
 
 @pytest.mark.parametrize("rshift", [0, 10, 15])
 @pytest.mark.parametrize("sign", [0, 1])
-@pytest.mark.parametrize("m,d,Z", [(1_000_003, 128, 32), (100_003, 64, 8), (1000, 64, 32), (300_007, 128, 128), (70_001, 16, 1)])
+@pytest.mark.parametrize("m,d,Z", [(1_000_003, 128, 32), (100_003, 64, 8), (1000, 64, 32), (300_007, 128, 128), (70_001, 16, 1),
+                                   (100_003, 16, 64), (250_007, 128, 512), (4099, 8, 24)])      # the last three: Z > d
 def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift):
     # the region-sorted path: hot tokens, long bags, blocks that leave their region or wrap, one
     # region only (m = 1000), unaligned array and state
@@ -370,6 +371,7 @@ def test_fused_backward_adagrad_sorted_path(m, d, Z, sign, rshift):
     (20_011, 32, 8, 1_000_000, 10),      # tens of thousands of records per region: split into classes
     (1000, 64, 32, 4000, 0),             # one region, every block overlaps hundreds of others
     (300_007, 128, 128, 3000, 13),       # blocks as long as a slice
+    (300_007, 32, 128, 3000, 0),         # blocks longer than embeddings: tokens sorted by their array offset
 ])
 def test_reproducible_mode_gives_the_same_bits_every_run(m, d, Z, card, rshift, sign):
     # No float atomics on this route and a canonical order of additions: the same call on the same
@@ -429,19 +431,29 @@ def test_reproducible_mode_covers_small_problems_and_refuses_what_it_cannot_do()
     robe.robe_backward_adagrad(h, to_dev(G), to_dev(flat), to_dev(off), B, F, Md, sd, 0.01, 1e-8, options=opt)
     g32 = ga.cpu().numpy()
     assert bits_equal(sd.cpu().numpy(), g32 * g32)
-    # a block longer than the embedding has no atomic-free route: a loud error, not a silent fallback
-    h2, _ = both_hashes(4, 1000, 4, 16, 0)
+    # an embedding wider than the lane-group kernels take has no atomic-free route: a loud error, not a
+    # silent fallback
+    h2, _ = both_hashes(4, 5000, 520, 8, 0)
     ids2 = rng.integers(0, 99, size=(6, 3), dtype=np.int64)
-    G2 = rng.standard_normal((6, 3, 4)).astype(np.float32)
+    G2 = rng.standard_normal((6, 3, 520)).astype(np.float32)
     with pytest.raises(robe.RobeError) as ei:
-        robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV),
+        robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(5000, dtype=torch.float32, device=DEV),
                            options=opt)
     assert ei.value.code == robe.ROBE_EINVAL and "reproducible" in str(ei.value)
     with pytest.raises(robe.RobeError):
-        robe.robe_backward_adagrad(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV),
-                                   torch.zeros(1000, dtype=torch.float32, device=DEV), 0.01, 1e-8, options=opt)
+        robe.robe_backward_adagrad(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(5000, dtype=torch.float32, device=DEV),
+                                   torch.zeros(5000, dtype=torch.float32, device=DEV), 0.01, 1e-8, options=opt)
     # without the option the same shape runs (float atomics)
-    robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(1000, dtype=torch.float32, device=DEV))
+    robe.robe_backward(h2, to_dev(G2), to_dev(ids2), None, 6, 3, torch.zeros(5000, dtype=torch.float32, device=DEV))
+    # a block longer than the embedding is sorted by its array offset and takes the same route
+    h3, H3 = both_hashes(4, 1000, 4, 16, 1)
+    ids3 = rng.integers(0, 99, size=(6, 3), dtype=np.int64)
+    G3 = rng.standard_normal((6, 3, 4)).astype(np.float32)
+    assert robe.robe_workspace_bytes(h3, 6, 3, ids3.size, opt) > 0
+    ga = torch.zeros(1000, dtype=torch.float32, device=DEV)
+    robe.robe_backward(h3, to_dev(G3), to_dev(ids3), None, 6, 3, ga, options=opt)
+    ref, S = oracle.backward(H3, G3, ids3, None, 6, 3)
+    assert np.all(np.abs(ga.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * S + TINY)
 
 
 @pytest.mark.parametrize("m,Z", [(8192 + 5, 32), (3 * 4096 + 20, 32), (2 * 32768 + 100, 64), (1024 * 5 + 31, 32)])
