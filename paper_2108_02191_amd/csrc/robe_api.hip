@@ -514,9 +514,13 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     // (a group that meets more runs of repeated tokens than that leaves the rest uncombined; on the
     // Zipf-distributed bags of the benchmark a walk of 512 positions holds 26 such runs on average
     // and 60 at most)
-    const uint64_t walk = (uint64_t)robe::kStretch * pl.lay.G;
+    // (long walks combine more copies of a frequent token per record, but a small problem needs its
+    // wavefronts: halve the walk until the combine kernel has a couple of thousand workgroups)
+    uint32_t stretch = robe::kStretch;
+    while (stretch > 1 && n / ((uint64_t)robe::kBlock * stretch) < 2048) stretch >>= 1;
+    const uint64_t walk = (uint64_t)stretch * pl.lay.G;
     const uint32_t p_quota = walk / 8 ? (uint32_t)(walk / 8) : 1u;
-    const uint64_t combine_blocks = (n + (uint64_t)robe::kBlock * robe::kStretch - 1) / ((uint64_t)robe::kBlock * robe::kStretch);
+    const uint64_t combine_blocks = (n + (uint64_t)robe::kBlock * stretch - 1) / ((uint64_t)robe::kBlock * stretch);
     const uint64_t p_rows = combine_blocks * (robe::kBlock / pl.lay.G) * p_quota;
     if (((uint64_t)rows + p_rows) * C >= 0x7FFFFFFFull) return pl;       // 31-bit source block numbers
 
@@ -550,7 +554,7 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     // The reproducible order of the record kernels splits an overfull region into at most
     // 2^kMaxClassShift classes of at most one round's records each.  Refuse what could come near that:
     // one and a half times the average region (hashed offsets spread evenly; a block in Z / R leaves a
-    // second record), plus every run of the most frequent token (one per kStretch * G copies) in one
+    // second record), plus every run of the most frequent token (one per walk of a lane group) in one
     // region, against six tenths of the room.  (The gather variant stages its records in an order
     // that is fixed by the sorted list and needs no such split.)
     if (opt.reproducible && !pl.gather) {
@@ -558,7 +562,7 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
         const uint64_t room = ((batch << robe::kMaxClassShift) * 6) / 10;
         const uint64_t R = 1ull << shift, span = R < h->m ? R : h->m;
         const uint64_t avg = (n * C * (span + h->Z) / span + NR - 1) / NR;
-        const uint64_t worst = avg + avg / 2 + 2ull * C * (n / ((uint64_t)robe::kStretch * pl.lay.G) + 1);
+        const uint64_t worst = avg + avg / 2 + 2ull * C * (n / walk + 1);
         if (worst > room) return pl;
     }
     pl.regions = true;
@@ -569,6 +573,7 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     r.rows = (uint32_t)rows;
     r.src_blocks = (uint32_t)(((uint64_t)rows + p_rows) * C);
     r.p_quota = p_quota;
+    r.stretch = stretch;
     r.key_mask = pl.key_top >= 31 ? (uint32_t)ROBE_PRIME : (1u << pl.key_top) - 1u;
     r.bin_blocks = NR * 4 > 80 * 1024 ? 256u : 512u;      // one or two workgroups per CU by LDS
     if (n < (size_t)r.bin_blocks * 1024) r.bin_blocks = (uint32_t)((n + 1023) / 1024);
@@ -578,6 +583,8 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     // reproducible mode, whose rounds are longer
     r.fullest_first = (NR <= 8192 || opt.reproducible) ? 1u : 0u;
     r.keep_rows = bags ? 1u : 0u;
+    // the slots the tokens can reach, against the array: below a quarter, most 64-byte granules stay untouched
+    r.sparse_regions = (uint64_t)n * h->d < h->m / 4 ? 1u : 0u;
     pl.spill_rows = (uint64_t)(512u / lg) * h->Z <= robe::kSpillFloats;
     // (the reduce kernel of the gather variant reads keys, src_row and run_tg eight positions at a
     // time: every such array is padded to whole chunks)
@@ -702,8 +709,8 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         }
 
         if (int rc = probe(opt, ROBE_PROBE_COMBINE, false, stream)) return rc;
-        // R1: combine runs into P, leave one record per run (a lane group walks kStretch * G positions)
-        const dim3 rgrid1((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * robe::kStretch - 1) / ((uint64_t)robe::kBlock * robe::kStretch)));
+        // R1: combine runs into P, leave one record per run (a lane group walks r.stretch * G positions)
+        const dim3 rgrid1((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * r.stretch - 1) / ((uint64_t)robe::kBlock * r.stretch)));
 #define ROBE_COMBINE_ROWS(V_)                                                                                         \
     do {                                                                                                              \
         if (sign && bags) robe::combine_rows_kernel<V_, true, true><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);   \

@@ -31,7 +31,7 @@
 namespace robe {
 
 constexpr int kRowsAhead = 8;          // gradient rows a lane group requests before adding them (R1)
-constexpr int kStretch = 8;            // stretches of G sorted positions a lane group walks in R1
+constexpr int kStretch = 8;            // stretches of G sorted positions a lane group walks in R1, at most (RegionPlan::stretch)
 constexpr int kBinBlock = 1024;        // R2 / R4
 constexpr int kReduceBlock = 512;      // R5 (the slice arithmetic assumes 2^9)
 constexpr uint32_t kMaxRecordLanes = 64;   // lanes per record in R5: a lane group must stay inside one wavefront
@@ -42,8 +42,8 @@ template <bool SIGN>
 constexpr int rec_batch() { return SIGN ? 448 : 640; }
 constexpr uint32_t kSpillFloats = 512; // LDS floats for the spill-over rows of R5 (used when groups * Z fits)
 constexpr int kRecAhead = 8;           // gradient blocks a lane group requests before adding them (R5)
+constexpr int kWb = 1;                 // vectors per thread and pass in the dense write-back of R5 (more did not pay: registers)
 constexpr int kCanonAhead = 4;         // records of a slice compared per step when R5 puts them in canonical order
-constexpr int kWb = 1;                 // vectors per thread and pass in the write-back of R5 (more did not pay: registers)
 constexpr uint32_t kMaxRegions = 32768;
 constexpr uint32_t kMaxClassShift = 10;  // R5 splits an overfull region into at most 2^10 classes (the table lives in the batch area)
 constexpr uint32_t kPartBit = 0x80000000u;   // record flag: the elements past the end of the block's own region
@@ -61,6 +61,7 @@ struct RegionPlan {
     uint32_t lg_shift;       // log2 of the lanes per record in R5
     uint32_t fullest_first;  // 1: R5 takes the regions by descending size class instead of by address
     uint32_t keep_rows;      // 1: gradient rows are read more than once (bags): R5 loads them with the default cache policy
+    uint32_t sparse_regions; // 1: the tokens reach a small part of the array: R5 writes back by a list of touched granules
     uint32_t keep_array;     // 1: R5 with the Adagrad rule leaves the array in the caches for the next forward pass (small arrays)
     // gather variant of R5 (no R2..R4): the range table has NE = C * epc entries, epc = kmax + 3 with
     // kmax = (P - 1) / m; dir[b] is the first sorted position whose key >> dir_shift is >= b
@@ -72,6 +73,7 @@ struct RegionPlan {
     uint8_t *head;           // [n]  1: a run starts here
     uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
     uint32_t *run_tg;        // [n]  at run starts: token part of the sign hash (sign on only)
+    uint32_t stretch;        // stretches of G sorted positions a lane group of R1 walks (1 .. kStretch)
     uint32_t p_quota;        // rows of P per lane group of R1
     float *P;                // [lane groups of R1 * p_quota][d] summed rows of the runs longer than one
     uint32_t *counts, *starts;   // [NR], [NR + 1]; after R3 counts holds the order of the regions for R5
@@ -87,9 +89,9 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *dst, uint32_t n
 
 // ---------------------------------------------------------------------------------------------
 // R1.  Lane layout as in the direct scatter: G lanes per row, lane `grp` owns elements grp + k*G.
-// A group walks kStretch * G consecutive sorted positions, G at a time; a run is cut only where the
+// A group walks s.stretch * G consecutive sorted positions, G at a time; a run is cut only where the
 // group's walk begins and ends, so a token that fills whole stretches leaves one record per
-// kStretch * G copies.
+// s.stretch * G copies.
 // ---------------------------------------------------------------------------------------------
 struct SortedToken {
     uint32_t th, row, e, xlo, xhi, tg;
@@ -133,8 +135,8 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
     // the record counts of R2 start at zero (this kernel is the last one before it)
     if (s.counts != nullptr)
         for (uint64_t i = thread_id; i < s.NR; i += (uint64_t)gridDim.x * kBlock) s.counts[i] = 0;
-    if ((thread_id - lane) * kStretch >= n) return;     // the whole wavefront is past the end
-    const uint64_t i_first = (thread_id - grp) * kStretch;   // first sorted position of this group's walk
+    if ((thread_id - lane) * s.stretch >= n) return;    // the whole wavefront is past the end
+    const uint64_t i_first = (thread_id - grp) * s.stretch;  // first sorted position of this group's walk
 
     // the token at a sorted position (lane l of the group looks at position i0 + l)
     auto fetch = [&](uint64_t pos) -> SortedToken {
@@ -177,11 +179,11 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
     carry.th = carry.row = carry.e = carry.xlo = carry.xhi = carry.tg = 0;
     carry.ok = false;
     if (s.dir != nullptr && i_first > 0 && i_first <= n) carry.th = s.keys[i_first - 1];   // its key only: the directory needs it
-    for (uint32_t st = 0; st < (uint32_t)kStretch; ++st) {
+    for (uint32_t st = 0; st < s.stretch; ++st) {
         const uint64_t i0 = i_first + (uint64_t)st * q.G;
         if (__all(i0 >= n)) break;                          // every group of the wavefront is past the end
         SortedToken nxt;
-        if (st + 1u < (uint32_t)kStretch) {
+        if (st + 1u < s.stretch) {
             nxt = fetch(i0 + q.G + grp);
         } else {
             nxt = carry;
@@ -1043,51 +1045,106 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
     __syncthreads();
 
     // The region is complete and this workgroup is the only one that holds any of its slots.
-    // kWb vectors per thread and pass: all their loads are requested before the first is used.
+    // Write-back per 64-byte granule (4 vectors, 4 lanes): partially written granules cost more than
+    // they save, untouched ones are neither read nor written.
     const uint32_t lane = threadIdx.x & 63u;
-    for (uint32_t it0 = 0; it0 < nvec; it0 += kWb * kReduceBlock) {   // same trip count for the whole workgroup
-        V4 g[kWb], w[kWb], st[kWb];
-        bool touch[kWb];
+    if (!s.sparse_regions) {
+        // most granules are touched: sweep the region, one vector per thread and pass
+        for (uint32_t it0 = 0; it0 < nvec; it0 += kWb * kReduceBlock) {   // same trip count for the whole workgroup
+            V4 g[kWb], w[kWb], st[kWb];
+            bool touch[kWb];
 #pragma unroll
-        for (int u = 0; u < kWb; ++u) {
-            const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) g[u][k] = 0.0f;
-            if (it < nvec) g[u] = *reinterpret_cast<const V4 *>(&acc[4u * it]);
-            const bool any = g[u][0] != 0.0f || g[u][1] != 0.0f || g[u][2] != 0.0f || g[u][3] != 0.0f;
-            // decide per 64-byte granule (4 lanes): partially written granules cost more than they save
-            const uint64_t gran_any = (__ballot(any) >> (lane & ~3u)) & 0xFull;
-            touch[u] = it < nvec && gran_any != 0;
-        }
-#pragma unroll
-        for (int u = 0; u < kWb; ++u) {
-            if (touch[u]) {
+            for (int u = 0; u < kWb; ++u) {
                 const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
-                if (RULE == 1 && s.keep_array) w[u] = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
-                else w[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
-                if constexpr (RULE == 1) st[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(state + r0 + 4u * it));
+#pragma unroll
+                for (int k = 0; k < 4; ++k) g[u][k] = 0.0f;
+                if (it < nvec) g[u] = *reinterpret_cast<const V4 *>(&acc[4u * it]);
+                const bool any = g[u][0] != 0.0f || g[u][1] != 0.0f || g[u][2] != 0.0f || g[u][3] != 0.0f;
+                // decide per 64-byte granule (4 lanes): partially written granules cost more than they save
+                const uint64_t gran_any = (__ballot(any) >> (lane & ~3u)) & 0xFull;
+                touch[u] = it < nvec && gran_any != 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kWb; ++u) {
+                if (touch[u]) {
+                    const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
+                    if (RULE == 1 && s.keep_array) w[u] = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
+                    else w[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
+                    if constexpr (RULE == 1) st[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(state + r0 + 4u * it));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kWb; ++u) {
+                if (!touch[u]) continue;
+                const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
+                if constexpr (RULE == 0) {
+                    w[u] += g[u];
+                    __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if (g[u][k] != 0.0f) {
+                            float wk = w[u][k], sk = st[u][k];
+                            adagrad_one(wk, sk, g[u][k], lr, eps);
+                            w[u][k] = wk;
+                            st[u][k] = sk;
+                        }
+                    }
+                    if (s.keep_array) *reinterpret_cast<V4 *>(dst + r0 + 4u * it) = w[u];
+                    else __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+                    __builtin_nontemporal_store(st[u], reinterpret_cast<V4 *>(state + r0 + 4u * it));
+                }
             }
         }
-#pragma unroll
-        for (int u = 0; u < kWb; ++u) {
-            if (!touch[u]) continue;
-            const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
+    } else {
+        // few granules are touched: list them first (in the batch area, which is free now), then take
+        // 128 of them per pass - one pass of loads for the whole region instead of one per 2 KB of it
+        uint16_t *gran = reinterpret_cast<uint16_t *>(srt);
+        static_assert(kRecBatch * (SIGN ? 12 : 8) >= (1 << (15 - 3)), "the batch area holds one 16-bit entry per granule of the largest region (2^15 floats)");
+        if (threadIdx.x == 0) *sel = 0;
+        __syncthreads();
+        for (uint32_t it0 = 0; it0 < nvec; it0 += kReduceBlock) {            // same trip count for the whole workgroup
+            const uint32_t it = it0 + threadIdx.x;
+            bool any = false;
+            if (it < nvec) {
+                const V4 g = *reinterpret_cast<const V4 *>(&acc[4u * it]);
+                any = g[0] != 0.0f || g[1] != 0.0f || g[2] != 0.0f || g[3] != 0.0f;
+            }
+            const uint64_t b = __ballot(any);
+            const uint64_t touched = (b | (b >> 1) | (b >> 2) | (b >> 3)) & 0x1111111111111111ull;   // bit 4k: granule k of this wavefront
+            uint32_t at = 0;
+            if (lane == 0 && touched) at = atomicAdd(sel, (uint32_t)__popcll(touched));
+            at = __shfl(at, 0);
+            if ((touched >> lane) & 1ull) gran[at + (uint32_t)__popcll(touched & ((1ull << lane) - 1ull))] = (uint16_t)(it >> 2);
+        }
+        __syncthreads();
+        const uint32_t n_gran = *sel;
+        for (uint32_t k0 = 0; k0 < n_gran; k0 += kReduceBlock / 4u) {
+            const uint32_t k = k0 + (threadIdx.x >> 2);
+            if (k >= n_gran) continue;
+            const uint32_t it = (uint32_t)gran[k] * 4u + (threadIdx.x & 3u);
+            if (it >= nvec) continue;
+            const V4 g = *reinterpret_cast<const V4 *>(&acc[4u * it]);
+            V4 w, st;
+            if (RULE == 1 && s.keep_array) w = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
+            else w = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
             if constexpr (RULE == 0) {
-                w[u] += g[u];
-                __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+                w += g;
+                __builtin_nontemporal_store(w, reinterpret_cast<V4 *>(dst + r0 + 4u * it));
             } else {
+                st = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(state + r0 + 4u * it));
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    if (g[u][k] != 0.0f) {
-                        float wk = w[u][k], sk = st[u][k];
-                        adagrad_one(wk, sk, g[u][k], lr, eps);
-                        w[u][k] = wk;
-                        st[u][k] = sk;
+                for (int e = 0; e < 4; ++e) {
+                    if (g[e] != 0.0f) {
+                        float wk = w[e], sk = st[e];
+                        adagrad_one(wk, sk, g[e], lr, eps);
+                        w[e] = wk;
+                        st[e] = sk;
                     }
                 }
-                if (s.keep_array) *reinterpret_cast<V4 *>(dst + r0 + 4u * it) = w[u];
-                else __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
-                __builtin_nontemporal_store(st[u], reinterpret_cast<V4 *>(state + r0 + 4u * it));
+                if (s.keep_array) *reinterpret_cast<V4 *>(dst + r0 + 4u * it) = w;
+                else __builtin_nontemporal_store(w, reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+                __builtin_nontemporal_store(st, reinterpret_cast<V4 *>(state + r0 + 4u * it));
             }
         }
     }
