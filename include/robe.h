@@ -228,7 +228,8 @@ int robe_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n_featu
  * once per run (ROBE_ROUTE_COMBINE); the largest (arrays of 2^26 slots or more with 2^21 tokens or
  * more) then collect the blocks by destination region and sum each region in LDS,
  * with no float atomic at all (ROBE_ROUTE_REGIONS; the route of the reproducible option).  The
- * sorted routes need the workspace, rows and n_indices below 2^31 - 1, d <= 512 and Z <= d;
+ * sorted routes need the workspace, rows and n_indices below 2^31 - 1 and d <= 512 (with Z > d,
+ * Section 3.3, tokens are sorted by the array offset of their d slots instead of the token hash);
  * ROBE_ROUTE_REGIONS also needs d / Z and the lane group to be powers of two, at most 2^30 array
  * slots, and a region size (2^10 .. 2^15 floats, at least 2 Z) that leaves the array's last region
  * either full or at least Z floats long.
@@ -331,12 +332,18 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
  * robe_backward_mixed accumulates onto grad_array like robe_backward.  Large scatters (the size rule
  * of robe_backward on the average dimension; every dimension a multiple of Z, the largest at most
  * 512, batch * D below 2^32) sort the tokens of all tables once and combine repeated tokens before
- * the atomics (ROBE_ROUTE_COMBINE; two tokens are the same when key and table agree); anything else
- * is one direct scatter per run of equal dimensions.  There is no route without float atomics here:
- * options->reproducible makes both calls fail with ROBE_EINVAL, and ROBE_ROUTE_REGIONS is taken as
- * ROBE_ROUTE_COMBINE.  Follow it with robe_adagrad_update / robe_sgd_update.
- *   workspace  device buffer of at least robe_mixed_workspace_bytes(...) bytes (same dims and
- *              options), 256-byte aligned; may be NULL when that size is 0
+ * the atomics (ROBE_ROUTE_COMBINE; two tokens are the same when key and table agree), or, when
+ * ROBE_ROUTE_REGIONS or options->reproducible asks for it, take the region route with no float
+ * atomics (same conditions as robe_backward, on the largest dimension); anything else is one direct
+ * scatter per run of equal dimensions.  With options->reproducible a shape the region route cannot
+ * take (a table narrower than the block among them) fails with ROBE_EINVAL.
+ * robe_backward_adagrad_mixed is robe_backward_adagrad for such tables: the fused region route where
+ * the plan has one (by default on arrays of 2^26 slots or more), else the scatter into a gradient
+ * array at the front of the workspace followed by the update kernel.  Otherwise follow
+ * robe_backward_mixed with robe_adagrad_update / robe_sgd_update.
+ *   workspace  device buffer of at least robe_mixed_workspace_bytes(...) bytes
+ *              (robe_fused_mixed_workspace_bytes for the fused call; same dims and options),
+ *              256-byte aligned; may be NULL when that size is 0
  * Errors: ROBE_EINVAL (also: a dims entry that is zero or neither a multiple nor a divisor of Z;
  * workspace too small), ROBE_EHIP.
  */
@@ -351,6 +358,13 @@ int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const flo
                         int64_t batch, int32_t n_features, float *grad_array,
                         void *workspace, size_t workspace_bytes,
                         const robe_options_t *options, void *stream);
+int robe_fused_mixed_workspace_bytes(const robe_hash_t *hash, const uint32_t *dims, int64_t batch, int32_t n_features,
+                                     int64_t n_indices, const robe_options_t *options, size_t *bytes);
+int robe_backward_adagrad_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out,
+                                const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                                int64_t batch, int32_t n_features, float *array, float *state,
+                                float lr, float eps, void *workspace, size_t workspace_bytes,
+                                const robe_options_t *options, void *stream);
 
 /*
  * Low-precision array (Section 2 notes that quantisation can be applied together with the method;

@@ -61,7 +61,8 @@ PROBE_NONE, PROBE_COMBINE, PROBE_REDUCE, PROBE_SORT = 0, 1, 2, 3
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
            "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
-           "robe_forward_mixed", "robe_mixed_workspace_bytes", "robe_backward_mixed", "robe_array_to_bf16", "robe_forward_bf16",
+           "robe_forward_mixed", "robe_mixed_workspace_bytes", "robe_backward_mixed", "robe_fused_mixed_workspace_bytes",
+           "robe_backward_adagrad_mixed", "robe_array_to_bf16", "robe_forward_bf16",
            "robe_sort_workspace_bytes", "robe_sort_pairs", "robe_noalloc_max_workspace_bytes", "robe_backward_noalloc",
            "robe_last_error")
 
@@ -109,6 +110,11 @@ def lib() -> ctypes.CDLL:
         L.robe_mixed_workspace_bytes.argtypes = [HP, vp, i64, i32, i64, OP, szp]
         L.robe_backward_mixed.restype = ctypes.c_int
         L.robe_backward_mixed.argtypes = [HP, vp, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_size_t, OP, vp]
+        L.robe_fused_mixed_workspace_bytes.restype = ctypes.c_int
+        L.robe_fused_mixed_workspace_bytes.argtypes = [HP, vp, i64, i32, i64, OP, szp]
+        L.robe_backward_adagrad_mixed.restype = ctypes.c_int
+        L.robe_backward_adagrad_mixed.argtypes = [HP, vp, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_float, ctypes.c_float,
+                                                  vp, ctypes.c_size_t, OP, vp]
         L.robe_array_to_bf16.restype = ctypes.c_int
         L.robe_array_to_bf16.argtypes = [vp, vp, u64, vp]
         L.robe_forward_bf16.restype = ctypes.c_int
@@ -335,6 +341,37 @@ def robe_backward_mixed(h: RobeHash, dims, grad_out: torch.Tensor, indices: torc
                                      _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                      indices.numel(), batch, F, _dev(grad_array, torch.float32, "grad_array"),
                                      ws_ptr, ws_len, _opt(options), _stream()))
+
+
+def robe_fused_mixed_workspace_bytes(h: RobeHash, dims, batch: int, n_indices: int,
+                                     options: Optional[RobeOptions] = None) -> int:
+    need = ctypes.c_size_t(0)
+    da = _dims_array(dims)
+    _check(lib().robe_fused_mixed_workspace_bytes(ctypes.byref(h), ctypes.cast(da, ctypes.c_void_p), batch, len(dims), n_indices,
+                                                  _opt(options), ctypes.byref(need)))
+    return int(need.value)
+
+
+def robe_backward_adagrad_mixed(h: RobeHash, dims, grad_out: torch.Tensor, indices: torch.Tensor,
+                                offsets: Optional[torch.Tensor], batch: int, array: torch.Tensor, state: torch.Tensor,
+                                lr: float, eps: float, workspace: Optional[torch.Tensor] = None,
+                                options: Optional[RobeOptions] = None) -> None:
+    """Backward and Adagrad in one call for tables of different dimensions (array and state in place)."""
+    F, D = len(dims), int(sum(dims))
+    if array.numel() != h.m or state.numel() != h.m:
+        raise ValueError("array / state length differs from hash.m")
+    if grad_out.numel() != batch * D:
+        raise ValueError("grad_out has the wrong size")
+    if offsets is not None and offsets.numel() != batch * F + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    need = robe_fused_mixed_workspace_bytes(h, dims, batch, indices.numel(), options) if workspace is None else 0
+    workspace, ws_ptr, ws_len = _workspace(workspace, need, array.device)
+    da = _dims_array(dims)
+    _check(lib().robe_backward_adagrad_mixed(ctypes.byref(h), ctypes.cast(da, ctypes.c_void_p),
+                                             _dev(grad_out, torch.float32, "grad_out"), _dev(indices, torch.int64, "indices"),
+                                             _dev(offsets, torch.int64, "offsets"), indices.numel(), batch, F,
+                                             _dev(array, torch.float32, "array"), _dev(state, torch.float32, "state"),
+                                             lr, eps, ws_ptr, ws_len, _opt(options), _stream()))
 
 
 def robe_array_to_bf16(array: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

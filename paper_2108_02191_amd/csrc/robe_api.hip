@@ -416,7 +416,7 @@ struct BwdPlan {
     size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_tok_bag, off_temp, temp_bytes, bytes;
     // regions only
     robe::RegionPlan rp;
-    size_t off_head, off_src_row, off_run_tg, off_P, off_counts, off_starts, off_wg_first, off_rec, off_rec_tg, off_dir;
+    size_t off_head, off_src_row, off_run_tg, off_run_c, off_P, off_counts, off_starts, off_wg_first, off_rec, off_rec_tg, off_dir;
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -455,8 +455,10 @@ uint32_t ceil_log2(uint64_t v) { uint32_t s = 0; while ((1ull << s) < v) ++s; re
 // Decide between the direct scatter, the combine-duplicates one and the region-sorted one, and lay
 // out the workspace.  Host arithmetic only, so that the workspace queries and the calls agree.
 // need_regions: the caller (the fused step) wants the region-sorted scatter whatever the size.
+// mixed_floats: 0, or (tables of different dimensions, all multiples of Z; the hash is the widest
+// table's) the floats of grad_out, batch * sum(dims).
 BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t rows, int64_t n_indices, bool bags,
-                      const void *grad_out, bool need_regions = false)
+                      const void *grad_out, bool need_regions = false, uint64_t mixed_floats = 0)
 {
     BwdPlan pl;
     memset(&pl, 0, sizeof(pl));
@@ -522,7 +524,9 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     const uint32_t p_quota = walk / 8 ? (uint32_t)(walk / 8) : 1u;
     const uint64_t combine_blocks = (n + (uint64_t)robe::kBlock * stretch - 1) / ((uint64_t)robe::kBlock * stretch);
     const uint64_t p_rows = combine_blocks * (robe::kBlock / pl.lay.G) * p_quota;
-    if (((uint64_t)rows + p_rows) * C >= 0x7FFFFFFFull) return pl;       // 31-bit source block numbers
+    // source blocks (Z floats each): those of grad_out, then those of P
+    const uint64_t src_own = mixed_floats ? mixed_floats / h->Z : (uint64_t)rows * C;
+    if (src_own + p_rows * C >= 0x7FFFFFFFull) return pl;                // 31-bit source block numbers
 
     // Gather variant: the reduce kernel reads the sorted token list through a range table of
     // C * ((P - 1) / m + 3) entries, which must fit its LDS: large arrays, few chunks per embedding.
@@ -571,7 +575,8 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     r.NR = (uint32_t)NR;
     r.n = (uint32_t)n;
     r.rows = (uint32_t)rows;
-    r.src_blocks = (uint32_t)(((uint64_t)rows + p_rows) * C);
+    r.src_own = (uint32_t)src_own;
+    r.src_blocks = (uint32_t)(src_own + p_rows * C);
     r.p_quota = p_quota;
     r.stretch = stretch;
     r.key_mask = pl.key_top >= 31 ? (uint32_t)ROBE_PRIME : (1u << pl.key_top) - 1u;
@@ -591,6 +596,7 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     pl.off_head = off;    if (!pl.gather) off = align_up(off + n, 256);
     pl.off_src_row = off; off = align_up(off + (n + 8) * 4, 256);
     pl.off_run_tg = off;  if (h->use_sign) off = align_up(off + (n + 8) * 4, 256);
+    pl.off_run_c = off;   if (mixed_floats) off = align_up(off + (n + 8) * 4, 256);
     pl.off_P = off;       off = align_up(off + p_rows * h->d * 4, 256);
     if (pl.gather) {
         // directory buckets: about two sorted positions each, never finer than what the sort looked at
@@ -682,7 +688,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
     q.d = h->d;
     q.G = pl.lay.G;
     q.g_shift = log2u(pl.lay.G);
-    q.tables = tables;              // tables of mixed dimensions (atomic route only)
+    q.tables = tables;              // tables of mixed dimensions
     q.row_floats = sample_floats;
     const uint64_t blocks = ((uint64_t)n + robe::kBlock - 1) / robe::kBlock;   // one lane per sorted position
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);
@@ -694,6 +700,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         r.head = pl.gather ? nullptr : reinterpret_cast<uint8_t *>(ws + pl.off_head);
         r.src_row = reinterpret_cast<uint32_t *>(ws + pl.off_src_row);
         r.run_tg = reinterpret_cast<uint32_t *>(ws + pl.off_run_tg);
+        r.run_c = tables != nullptr ? reinterpret_cast<uint32_t *>(ws + pl.off_run_c) : nullptr;
         r.P = reinterpret_cast<float *>(ws + pl.off_P);
         if (pl.gather) {
             r.dir = reinterpret_cast<uint32_t *>(ws + pl.off_dir);
@@ -711,12 +718,17 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         if (int rc = probe(opt, ROBE_PROBE_COMBINE, false, stream)) return rc;
         // R1: combine runs into P, leave one record per run (a lane group walks r.stretch * G positions)
         const dim3 rgrid1((uint32_t)(((uint64_t)n + (uint64_t)robe::kBlock * r.stretch - 1) / ((uint64_t)robe::kBlock * r.stretch)));
+#define ROBE_COMBINE_ROWS_M(V_, M_)                                                                                   \
+    do {                                                                                                              \
+        if (sign && bags) robe::combine_rows_kernel<V_, true, true, M_><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);   \
+        else if (sign) robe::combine_rows_kernel<V_, true, false, M_><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
+        else if (bags) robe::combine_rows_kernel<V_, false, true, M_><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
+        else robe::combine_rows_kernel<V_, false, false, M_><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);             \
+    } while (0)
 #define ROBE_COMBINE_ROWS(V_)                                                                                         \
     do {                                                                                                              \
-        if (sign && bags) robe::combine_rows_kernel<V_, true, true><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);   \
-        else if (sign) robe::combine_rows_kernel<V_, true, false><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
-        else if (bags) robe::combine_rows_kernel<V_, false, true><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);    \
-        else robe::combine_rows_kernel<V_, false, false><<<rgrid1, block, 0, stream>>>(p, q, r, grad_out, indices, vals_out, tok_bag);             \
+        if (tables != nullptr) ROBE_COMBINE_ROWS_M(V_, true);                                                         \
+        else ROBE_COMBINE_ROWS_M(V_, false);                                                                          \
     } while (0)
         switch (pl.lay.V) {
             case 1: ROBE_COMBINE_ROWS(1); break;
@@ -726,6 +738,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
             case 8: ROBE_COMBINE_ROWS(8); break;
             default: ROBE_COMBINE_ROWS(4); break;
         }
+#undef ROBE_COMBINE_ROWS_M
 #undef ROBE_COMBINE_ROWS
         if (int rc = check_launch("backward (combine rows)")) return rc;
         if (int rc = probe(opt, ROBE_PROBE_COMBINE, true, stream)) return rc;
@@ -1016,20 +1029,22 @@ int robe_forward_mixed(const robe_hash_t *hash, const uint32_t *dims, const floa
     return launch_mixed<false>(hash, opt, dims, array, indices, offsets, n_indices, batch, n_features, out, out, stream);
 }
 
-// Backward over tables of mixed dimensions: one token sort and one combine kernel for all tables
-// (duplicates combined, atomics once per distinct token) when the scatter is large enough, every
-// dimension is a multiple of Z and the largest has a lane layout; else one direct scatter per run of
-// equal dimensions.  The plan is host arithmetic shared by the query and the call.
+// Backward over tables of mixed dimensions: one token sort for all tables when the scatter is large
+// enough (or a route is asked for), every dimension is a multiple of Z and the largest has a lane
+// layout - then either the combine kernel with float atomics, or the region route (no float atomics;
+// the reproducible option and the fused step need it); else one direct scatter per run of equal
+// dimensions.  The plan is host arithmetic shared by the queries and the calls.
 struct MixedPlan {
-    bool sorted;
+    bool sorted;            // one sort over all tables; pl says which route follows it
     BwdPlan pl;
     robe_hash_t widest;     // the hash with d = the largest dimension: lane constants and the sort's plan
     size_t off_tables, bytes;
     int64_t D;
 };
 
+// need_regions: the caller (the fused step) wants the region route whatever the size.
 static int plan_mixed(const robe_hash_t *hash, const Opt &opt, const uint32_t *dims, int64_t batch, int32_t n_features,
-                      int64_t n_indices, bool bags, const void *grad_out, MixedPlan *mp)
+                      int64_t n_indices, bool bags, const void *grad_out, bool need_regions, MixedPlan *mp)
 {
     memset(mp, 0, sizeof(*mp));
     if (dims == nullptr) return fail(ROBE_EINVAL, "dims is NULL");
@@ -1047,55 +1062,35 @@ static int plan_mixed(const robe_hash_t *hash, const Opt &opt, const uint32_t *d
     mp->D = D;
     mp->widest = *hash;
     mp->widest.d = dmax;
-    if (opt.reproducible) return ROBE_OK;                   // (the caller refuses: no route without float atomics here)
-    if (opt.bwd_route == ROBE_ROUTE_DIRECT || narrow || batch < 1 || n_indices < 1) return ROBE_OK;
-    if ((uint64_t)batch * (uint64_t)D >= 0xFFFFFFFFull) return ROBE_OK;           // 32-bit row starts in the combine kernel
-    const bool forced = opt.bwd_route == ROBE_ROUTE_COMBINE || opt.bwd_route == ROBE_ROUTE_REGIONS;
+    const bool regions = need_regions || opt.reproducible || opt.bwd_route == ROBE_ROUTE_REGIONS;
+    if ((opt.bwd_route == ROBE_ROUTE_DIRECT && !regions) || narrow || batch < 1 || n_indices < 1) return ROBE_OK;
+    if ((uint64_t)batch * (uint64_t)D >= 0xFFFFFFFFull) return ROBE_OK;           // 32-bit row starts in the combine kernels
+    const bool forced = regions || opt.bwd_route == ROBE_ROUTE_COMBINE;
     // the same size rule as robe_backward, on the average dimension
     if (!forced && (uint64_t)n_indices * (uint64_t)(D / n_features) < (1ull << 25)) return ROBE_OK;
+    const int64_t rows = batch * (int64_t)n_features;
     Opt sorted = opt;
-    sorted.bwd_route = ROBE_ROUTE_COMBINE;
-    mp->pl = plan_backward(&mp->widest, sorted, batch * (int64_t)n_features, n_indices, bags, grad_out);
-    if (!mp->pl.dedup || mp->pl.regions) return ROBE_OK;
+    sorted.bwd_route = regions ? ROBE_ROUTE_REGIONS : ROBE_ROUTE_COMBINE;
+    mp->pl = plan_backward(&mp->widest, sorted, rows, n_indices, bags, grad_out, need_regions, (uint64_t)batch * (uint64_t)D);
+    if (regions && !mp->pl.regions) {
+        if (need_regions || opt.reproducible) return ROBE_OK;     // the caller falls back, or refuses
+        sorted.bwd_route = ROBE_ROUTE_COMBINE;                    // a route was merely asked for: the next best
+        mp->pl = plan_backward(&mp->widest, sorted, rows, n_indices, bags, grad_out, false, (uint64_t)batch * (uint64_t)D);
+    }
+    if (!mp->pl.dedup) return ROBE_OK;
     mp->sorted = true;
     mp->off_tables = mp->pl.bytes;
     mp->bytes = align_up(mp->pl.bytes + (size_t)n_features * sizeof(uint2), 256);
     return ROBE_OK;
 }
 
-int robe_mixed_workspace_bytes(const robe_hash_t *hash, const uint32_t *dims, int64_t batch, int32_t n_features,
-                               int64_t n_indices, const robe_options_t *options, size_t *bytes)
+// The sorted scatter of a MixedPlan into dst (rule 0: a gradient array; rule 1, region route only:
+// Adagrad on dst = array and state).
+static int launch_mixed_sorted(const MixedPlan &mp, const Opt &opt, const uint32_t *dims, const float *grad_out,
+                               const int64_t *indices, const int64_t *offsets, int64_t n_indices, int64_t rows,
+                               int32_t n_features, float *dst, void *workspace, hipStream_t s,
+                               int rule = 0, float *state = nullptr, float lr = 0.0f, float eps = 0.0f)
 {
-    Opt opt;
-    if (int rc = check_query(hash, batch, n_features, n_indices, options, bytes, &opt)) return rc;
-    if (opt.reproducible) return fail_not_reproducible();
-    MixedPlan mp;
-    if (int rc = plan_mixed(hash, opt, dims, batch, n_features, n_indices, true, nullptr, &mp)) return rc;
-    *bytes = mp.sorted ? mp.bytes : 0;
-    return ROBE_OK;
-}
-
-int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out, const int64_t *indices,
-                        const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features,
-                        float *grad_array, void *workspace, size_t workspace_bytes,
-                        const robe_options_t *options, void *stream)
-{
-    Opt opt;
-    if (int rc = read_options(options, &opt)) return rc;
-    if (opt.reproducible) return fail_not_reproducible();
-    int64_t rows = 0;
-    if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
-    MixedPlan mp;
-    if (int rc = plan_mixed(hash, opt, dims, batch, n_features, n_indices, offsets != nullptr, grad_out, &mp)) return rc;
-    if (!mp.sorted)
-        return launch_mixed<true>(hash, opt, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
-                                  grad_out, stream);
-    if (workspace == nullptr || workspace_bytes < mp.bytes)
-        return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", mp.bytes, workspace_bytes);
-    if (!aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
-    if (grad_out == nullptr || grad_array == nullptr) return fail(ROBE_EINVAL, "grad_out or grad_array is NULL");
-    if (!aligned(grad_out, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
-    hipStream_t s = (hipStream_t)stream;
     uint2 *tables = reinterpret_cast<uint2 *>(static_cast<char *>(workspace) + mp.off_tables);
     uint32_t col = 0;
     for (int32_t f0 = 0; f0 < n_features; f0 += robe::kTableArgs) {
@@ -1111,7 +1106,43 @@ int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const flo
         if (int rc = check_launch("backward (table map)")) return rc;
     }
     return launch_dedup_backward(&mp.widest, opt, mp.pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
-                                 grad_array, workspace, s, 0, nullptr, 0.0f, 0.0f, tables, mp.D);
+                                 dst, workspace, s, rule, state, lr, eps, tables, mp.D);
+}
+
+int robe_mixed_workspace_bytes(const robe_hash_t *hash, const uint32_t *dims, int64_t batch, int32_t n_features,
+                               int64_t n_indices, const robe_options_t *options, size_t *bytes)
+{
+    Opt opt;
+    if (int rc = check_query(hash, batch, n_features, n_indices, options, bytes, &opt)) return rc;
+    MixedPlan mp;
+    if (int rc = plan_mixed(hash, opt, dims, batch, n_features, n_indices, true, nullptr, false, &mp)) return rc;
+    if (opt.reproducible && !(mp.sorted && mp.pl.regions) && batch > 0 && n_indices > 0) return fail_not_reproducible();
+    *bytes = mp.sorted ? mp.bytes : 0;
+    return ROBE_OK;
+}
+
+int robe_backward_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out, const int64_t *indices,
+                        const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features,
+                        float *grad_array, void *workspace, size_t workspace_bytes,
+                        const robe_options_t *options, void *stream)
+{
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
+    int64_t rows = 0;
+    if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
+    MixedPlan mp;
+    if (int rc = plan_mixed(hash, opt, dims, batch, n_features, n_indices, offsets != nullptr, grad_out, false, &mp)) return rc;
+    if (opt.reproducible && rows > 0 && n_indices > 0 && !(mp.sorted && mp.pl.regions)) return fail_not_reproducible();
+    if (!mp.sorted)
+        return launch_mixed<true>(hash, opt, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad_array,
+                                  grad_out, stream);
+    if (workspace == nullptr || workspace_bytes < mp.bytes)
+        return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", mp.bytes, workspace_bytes);
+    if (!aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
+    if (grad_out == nullptr || grad_array == nullptr) return fail(ROBE_EINVAL, "grad_out or grad_array is NULL");
+    if (!aligned(grad_out, 4) || !aligned(grad_array, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    return launch_mixed_sorted(mp, opt, dims, grad_out, indices, offsets, n_indices, rows, n_features, grad_array, workspace,
+                               (hipStream_t)stream);
 }
 
 // The address of `scratch` on the current device.  In host code the array's name is only a handle
@@ -1299,6 +1330,89 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const 
         rc = launch_dedup_backward(hash, opt, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, rest, s);
     else
         rc = launch_rows<true>(hash, opt, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, grad_out, s);
+    if (rc) return rc;
+    return launch_update(0, hash, array, state, grad, lr, eps, stream, false);
+}
+
+// The fused step over tables of mixed dimensions: the region route when the plan has one (and the
+// array is large, or it is asked for), else two steps through a gradient array at the front of the
+// workspace, like robe_backward_adagrad.
+static int fused_mixed_plan(const robe_hash_t *hash, const Opt &opt, const uint32_t *dims, int64_t batch, int32_t n_features,
+                            int64_t n_indices, bool bags, const void *grad_out, MixedPlan *mp, bool *fused, size_t *scratch_bytes)
+{
+    *scratch_bytes = 0;
+    *fused = false;
+    const bool want = opt.fused_route == ROBE_ROUTE_AUTO ? hash->m >= (1ull << 26) : opt.fused_route == ROBE_ROUTE_REGIONS;
+    if (opt.reproducible || want) {
+        if (int rc = plan_mixed(hash, opt, dims, batch, n_features, n_indices, bags, grad_out, true, mp)) return rc;
+        if (mp->sorted && mp->pl.regions) {
+            *fused = true;
+            return ROBE_OK;
+        }
+    }
+    Opt two = opt;
+    if (two.bwd_route == ROBE_ROUTE_REGIONS) two.bwd_route = ROBE_ROUTE_COMBINE;   // the two steps add onto a gradient array
+    if (int rc = plan_mixed(hash, two, dims, batch, n_features, n_indices, bags, grad_out, false, mp)) return rc;
+    *scratch_bytes = align_up((size_t)hash->m * 4, 256);
+    return ROBE_OK;
+}
+
+int robe_fused_mixed_workspace_bytes(const robe_hash_t *hash, const uint32_t *dims, int64_t batch, int32_t n_features,
+                                     int64_t n_indices, const robe_options_t *options, size_t *bytes)
+{
+    Opt opt;
+    if (int rc = check_query(hash, batch, n_features, n_indices, options, bytes, &opt)) return rc;
+    MixedPlan mp;
+    bool fused = false;
+    size_t scratch = 0;
+    if (int rc = fused_mixed_plan(hash, opt, dims, batch, n_features, n_indices, true, nullptr, &mp, &fused, &scratch)) return rc;
+    if (opt.reproducible && !fused && batch > 0 && n_indices > 0) return fail_not_reproducible();
+    *bytes = scratch + (mp.sorted ? mp.bytes : 0);
+    return ROBE_OK;
+}
+
+int robe_backward_adagrad_mixed(const robe_hash_t *hash, const uint32_t *dims, const float *grad_out, const int64_t *indices,
+                                const int64_t *offsets, int64_t n_indices, int64_t batch, int32_t n_features,
+                                float *array, float *state, float lr, float eps, void *workspace, size_t workspace_bytes,
+                                const robe_options_t *options, void *stream)
+{
+    int64_t rows = 0;
+    Opt opt;
+    if (int rc = read_options(options, &opt)) return rc;
+    if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
+    if (array == nullptr || state == nullptr) return fail(ROBE_EINVAL, "array or state is NULL");
+    if (!std::isfinite(lr) || !std::isfinite(eps) || !(eps > 0.0f)) return fail(ROBE_EINVAL, "need finite lr and eps > 0");
+    if (!aligned(array, 4) || !aligned(state, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    MixedPlan mp;
+    bool fused = false;
+    size_t scratch = 0;
+    if (int rc = fused_mixed_plan(hash, opt, dims, batch, n_features, n_indices, offsets != nullptr, grad_out, &mp, &fused, &scratch))
+        return rc;
+    if (rows == 0 || n_indices == 0) return ROBE_OK;      // no gradient anywhere: nothing is touched
+    if (grad_out == nullptr) return fail(ROBE_EINVAL, "grad_out is NULL");
+    if (!aligned(grad_out, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    if (opt.reproducible && !fused) return fail_not_reproducible();
+    const size_t need = scratch + (mp.sorted ? mp.bytes : 0);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need))
+        return fail(ROBE_EINVAL, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    if (need > 0 && !aligned(workspace, 256)) return fail(ROBE_EINVAL, "workspace must be 256-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    if (fused)
+        return launch_mixed_sorted(mp, opt, dims, grad_out, indices, offsets, n_indices, rows, n_features, array, workspace, s,
+                                   1, state, lr, eps);
+    // two steps through a gradient array at the front of the workspace
+    float *grad = static_cast<float *>(workspace);
+    const uint64_t m = hash->m;
+    uint64_t fill_blocks = (m + 255) / 256;
+    if (fill_blocks > 65536) fill_blocks = 65536;
+    robe::fill_u32_kernel<<<dim3((uint32_t)fill_blocks), dim3(256), 0, s>>>(reinterpret_cast<uint32_t *>(grad), (uint32_t)m, 0u);
+    if (int rc = check_launch("fused step (clear gradient)")) return rc;
+    char *rest = static_cast<char *>(workspace) + scratch;
+    int rc;
+    if (mp.sorted)
+        rc = launch_mixed_sorted(mp, opt, dims, grad_out, indices, offsets, n_indices, rows, n_features, grad, rest, s);
+    else
+        rc = launch_mixed<true>(hash, opt, dims, grad_out, indices, offsets, n_indices, batch, n_features, grad, grad_out, stream);
     if (rc) return rc;
     return launch_update(0, hash, array, state, grad, lr, eps, stream, false);
 }

@@ -55,7 +55,8 @@ struct RegionPlan {
     uint32_t NR;             // regions = ceil(m / 2^r_shift)
     uint32_t n;              // sorted token positions
     uint32_t rows;           // rows of grad_out
-    uint32_t src_blocks;     // (rows + P rows) * C: exclusive bound of a record's source block
+    uint32_t src_own;        // blocks of Z floats in grad_out: source blocks below this live there, the rest in P
+    uint32_t src_blocks;     // src_own + P rows * C: exclusive bound of a record's source block
     uint32_t bin_blocks;     // grid of R2 / R4
     uint32_t pos_per_block;  // sorted positions per workgroup in R2 / R4
     uint32_t lg_shift;       // log2 of the lanes per record in R5
@@ -71,11 +72,12 @@ struct RegionPlan {
     uint32_t *dir;
     const uint32_t *keys;    // sorted keys
     uint8_t *head;           // [n]  1: a run starts here
-    uint32_t *src_row;       // [n]  at run starts: row of grad_out, or rows + row of P
+    uint32_t *src_row;       // [n]  at run starts: the first source block of the run's row (in grad_out, or src_own + row of P * C); else kNoRun
+    uint32_t *run_c;         // [n]  at run starts: chunks of the run's embedding; NULL unless tables differ in dimension (then C is the most any has)
     uint32_t *run_tg;        // [n]  at run starts: token part of the sign hash (sign on only)
     uint32_t stretch;        // stretches of G sorted positions a lane group of R1 walks (1 .. kStretch)
     uint32_t p_quota;        // rows of P per lane group of R1
-    float *P;                // [lane groups of R1 * p_quota][d] summed rows of the runs longer than one
+    float *P;                // [lane groups of R1 * p_quota][d] summed rows of the runs longer than one (d: the widest table's)
     uint32_t *counts, *starts;   // [NR], [NR + 1]; after R3 counts holds the order of the regions for R5
     uint32_t *wg_first;      // [bin_blocks][NR]: R2 -> R4, see region_bin_kernel
     uint2 *rec;              // [<= 2 * n * C] (offset, source block | part flag)
@@ -94,33 +96,37 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *dst, uint32_t n
 // s.stretch * G copies.
 // ---------------------------------------------------------------------------------------------
 struct SortedToken {
-    uint32_t th, row, e, xlo, xhi, tg;
+    uint32_t th, sb, dd, e, xlo, xhi, tg;    // sb: first block of Z floats of its gradient row; dd: its dimension
     bool ok;
 };
 
+// Equal keys write equal slots; with the sign on the token itself must agree (g hashes it again), and
+// among tables of different dimensions the table must (two tables may share a key by collision).
 template <bool SIGN>
-__device__ __forceinline__ bool same_token(const SortedToken &a, const SortedToken &b)
+__device__ __forceinline__ bool same_token(const SortedToken &a, const SortedToken &b, bool mixed)
 {
     bool same = a.th == b.th;
+    if (mixed) same = same && a.e == b.e;
     if constexpr (SIGN) same = same && a.e == b.e && a.xlo == b.xlo && a.xhi == b.xhi;
     return same;
 }
 
 template <bool SIGN>
-__device__ __forceinline__ SortedToken shfl_token(const SortedToken &t, int from)
+__device__ __forceinline__ SortedToken shfl_token(const SortedToken &t, int from, bool mixed)
 {
     SortedToken r;
     r.th = __shfl(t.th, from);
     r.ok = __shfl((int)t.ok, from) != 0;
-    r.row = 0;
+    r.sb = 0;
+    r.dd = 0;
     r.tg = 0;
-    r.e = SIGN ? __shfl(t.e, from) : 0u;
+    r.e = (SIGN || mixed) ? __shfl(t.e, from) : 0u;
     r.xlo = SIGN ? __shfl(t.xlo, from) : 0u;
     r.xhi = SIGN ? __shfl(t.xhi, from) : 0u;
     return r;
 }
 
-template <int V, bool SIGN, bool BAGS>
+template <int V, bool SIGN, bool BAGS, bool MIXED>
 __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, RegionPlan s,
                                                               const float *__restrict__ grad_out,
                                                               const int64_t *__restrict__ indices,
@@ -139,9 +145,11 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
     const uint64_t i_first = (thread_id - grp) * s.stretch;  // first sorted position of this group's walk
 
     // the token at a sorted position (lane l of the group looks at position i0 + l)
+    constexpr bool mixed = MIXED;                       // tables of different dimensions (every one a multiple of Z): q.tables
     auto fetch = [&](uint64_t pos) -> SortedToken {
         SortedToken t;
-        t.th = t.row = t.e = t.xlo = t.xhi = t.tg = 0;
+        t.th = t.sb = t.e = t.xlo = t.xhi = t.tg = 0;
+        t.dd = q.d;
         t.ok = false;
         if (pos < n) {
             const uint32_t v = vals[pos];                  // sign off: the row itself (see robe_backward_dedup.h)
@@ -149,10 +157,15 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
             t.th = s.keys[pos];                            // also for a token that is not ok: the directory covers every position
             if (row < s.rows && t.th < kP) {               // (a key that is no residue: a position no bag of a malformed CSR wrote)
                 t.ok = true;
-                t.row = row;
+                t.sb = row * p.C;
+                if (SIGN || mixed) t.e = row % q.F;
+                if (mixed) {
+                    const uint2 tab = q.tables[t.e];
+                    t.sb = (uint32_t)(((uint64_t)(row / q.F) * (uint64_t)q.row_floats + tab.x) / p.Z);
+                    t.dd = tab.y;
+                }
                 if constexpr (SIGN) {
                     const int64_t x = indices[v];
-                    t.e = row % q.F;
                     t.xlo = (uint32_t)x;
                     t.xhi = (uint32_t)((uint64_t)x >> 32);
                     t.tg = staged_g(p, x, t.e);
@@ -176,7 +189,7 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
 
     SortedToken cur = fetch(i_first + grp);
     SortedToken carry;          // the last token of the stretch before; none before the first
-    carry.th = carry.row = carry.e = carry.xlo = carry.xhi = carry.tg = 0;
+    carry.th = carry.sb = carry.dd = carry.e = carry.xlo = carry.xhi = carry.tg = 0;
     carry.ok = false;
     if (s.dir != nullptr && i_first > 0 && i_first <= n) carry.th = s.keys[i_first - 1];   // its key only: the directory needs it
     for (uint32_t st = 0; st < s.stretch; ++st) {
@@ -191,13 +204,13 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
         }
         // does a run start here (a different token than the one before, or the walk begins), and
         // does it end here (a different token after, or the walk ends)?
-        SortedToken before = shfl_token<SIGN>(cur, (int)(base_lane + (grp ? grp - 1u : 0u)));
+        SortedToken before = shfl_token<SIGN>(cur, (int)(base_lane + (grp ? grp - 1u : 0u)), mixed);
         if (grp == 0) before = carry;
-        const bool my_head = cur.ok && (!before.ok || !same_token<SIGN>(before, cur));
-        SortedToken after = shfl_token<SIGN>(cur, (int)(base_lane + (grp + 1u < q.G ? grp + 1u : grp)));
-        const SortedToken first_of_next = shfl_token<SIGN>(nxt, (int)base_lane);
+        const bool my_head = cur.ok && (!before.ok || !same_token<SIGN>(before, cur, mixed));
+        SortedToken after = shfl_token<SIGN>(cur, (int)(base_lane + (grp + 1u < q.G ? grp + 1u : grp)), mixed);
+        const SortedToken first_of_next = shfl_token<SIGN>(nxt, (int)base_lane, mixed);
         if (grp + 1u >= q.G) after = first_of_next;
-        const bool my_end = cur.ok && (!after.ok || !same_token<SIGN>(after, cur));
+        const bool my_end = cur.ok && (!after.ok || !same_token<SIGN>(after, cur, mixed));
         bool my_single = my_head && my_end;
         // the slot of the run every position belongs to: the run of the last head at or before it (none:
         // the run left open by the stretch before), counted among this walk's multi-token runs
@@ -251,16 +264,17 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
             // a run of one reads grad_out in place; the head of a longer run gets its row of P when the run
             // ends; every other position says that no run starts there (the gather variant of R5 reads
             // this array alone to find the runs)
-            if (my_single) s.src_row[i0 + grp] = cur.row;
+            if (my_single) s.src_row[i0 + grp] = cur.sb;
             else if (!my_head) s.src_row[i0 + grp] = kNoRun;
             if constexpr (SIGN) {
                 if (my_lead) s.run_tg[i0 + grp] = cur.tg;
             }
+            if (mixed && my_lead) s.run_c[i0 + grp] = cur.dd / p.Z;
         }
 
         // runs longer than one: sum their rows into P (a run may have begun in an earlier stretch)
         for (uint32_t k0 = 0; k0 < q.G; k0 += kRowsAhead) {     // same trip count for every lane of the wavefront
-            uint32_t row[kRowsAhead], slot[kRowsAhead];
+            uint32_t sb[kRowsAhead], dd[kRowsAhead], slot[kRowsAhead];
             bool use[kRowsAhead], head[kRowsAhead], end[kRowsAhead];
             // what the loop below needs of a position, in one word: its run's slot, whether the position
             // takes part, starts a run, ends one
@@ -270,7 +284,8 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
                 const int from = (int)(base_lane + ((k0 + u) & (q.G - 1u)));
                 const bool in = k0 + u < q.G;
                 const uint32_t theirs = __shfl(mine, from);
-                row[u] = __shfl(cur.row, from);
+                sb[u] = __shfl(cur.sb, from);
+                dd[u] = mixed ? __shfl(cur.dd, from) : q.d;
                 use[u] = in && (theirs & 4u) != 0;
                 head[u] = (theirs & 2u) != 0;
                 end[u] = (theirs & 1u) != 0;
@@ -279,7 +294,7 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
             float v[kRowsAhead][V];
 #pragma unroll
             for (int u = 0; u < kRowsAhead; ++u) {
-                if (use[u]) load_row<V, false, BAGS>(grad_out + (uint64_t)row[u] * p.d, q, grp, v[u]);
+                if (use[u]) load_row_of<V, BAGS>(grad_out + (uint64_t)sb[u] * p.Z, q.G, dd[u], grp, v[u]);
             }
 #pragma unroll
             for (int u = 0; u < kRowsAhead; ++u) {
@@ -295,11 +310,11 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(Params p, Geom q, 
                 if (end[u]) {
                     const uint32_t prow = p_first + run_slot;
                     store_row<V, false>(s.P + (uint64_t)prow * p.d, q, grp, acc);
-                    if (grp == 0) s.src_row[head_pos] = s.rows + prow;
+                    if (grp == 0) s.src_row[head_pos] = s.src_own + prow * p.C;
                 }
             }
         }
-        carry = shfl_token<SIGN>(cur, (int)(base_lane + q.G - 1u));
+        carry = shfl_token<SIGN>(cur, (int)(base_lane + q.G - 1u), mixed);
         open_slot = __shfl(my_slot, (int)(base_lane + q.G - 1u));
         open_over = __shfl((int)my_over, (int)(base_lane + q.G - 1u)) != 0;
         cur = nxt;
@@ -322,7 +337,7 @@ __device__ __forceinline__ void for_each_block(const Params &p, const RegionPlan
     // (for positions that head no run the last two are read for nothing: a thread that asked for the
     // flag first and the rest after spent the sweep in two dependent trips to memory per position)
     for (uint64_t i0 = b + threadIdx.x; i0 < e; i0 += (uint64_t)kBinBlock * kBinAhead) {
-        uint32_t hd[kBinAhead], th[kBinAhead], sr[kBinAhead], tgv[kBinAhead];
+        uint32_t hd[kBinAhead], th[kBinAhead], sr[kBinAhead], tgv[kBinAhead], nc[kBinAhead];
 #pragma unroll
         for (int u = 0; u < kBinAhead; ++u) {
             const uint64_t i = i0 + (uint64_t)u * kBinBlock;
@@ -331,28 +346,33 @@ __device__ __forceinline__ void for_each_block(const Params &p, const RegionPlan
             th[u] = s.keys[at];
             sr[u] = s.src_row[at];
             tgv[u] = SIGN ? s.run_tg[at] : 0u;
+            nc[u] = s.run_c != nullptr ? s.run_c[at] : p.C;
         }
 #pragma unroll
         for (int u = 0; u < kBinAhead; ++u) {
             if (!hd[u]) continue;
-            const uint32_t src0 = sr[u] * p.C;
+            const uint32_t src0 = sr[u];
+            const uint32_t chunks = nc[u] < p.C ? nc[u] : p.C;
             uint32_t cc = 0;  // (Ch * c) mod P, built up by addition
-            for (uint32_t c = 0; c < p.C; ++c) {
+            uint32_t tgc = tgv[u];   // sign term of the chunk's element 0: the token's plus (Cg * c * Z) mod P
+            const uint32_t tg_step = SIGN ? mod_p((uint64_t)p.Cg * p.Z) : 0u;
+            for (uint32_t c = 0; c < chunks; ++c) {
                 const uint32_t o = offset_of(p, th[u], cc);
                 uint32_t r = o >> s.r_shift;
-                f(o, src0 + c, r, 0u, tgv[u]);
+                f(o, src0 + c, r, 0u, tgc);
                 // the regions the block enters after its own: normally at most one; two when the array
                 // ends in a region shorter than the block and the block passes through it to slot 0
                 uint64_t r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
                 uint64_t left = (uint64_t)o + p.Z > r_end ? (uint64_t)o + p.Z - r_end : 0u;
                 for (int hop = 0; hop < 2 && left > 0; ++hop) {
                     r = r_end == p.m ? 0u : r + 1u;
-                    f(o, src0 + c, r, kPartBit, tgv[u]);
+                    f(o, src0 + c, r, kPartBit, tgc);
                     const uint64_t r_begin = (uint64_t)r << s.r_shift;
                     r_end = ((uint64_t)(r + 1u) << s.r_shift) < p.m ? ((uint64_t)(r + 1u) << s.r_shift) : p.m;
                     left = left > r_end - r_begin ? left - (r_end - r_begin) : 0u;
                 }
                 cc = add_p(cc, p.Ch);
+                if constexpr (SIGN) tgc = add_p(tgc, tg_step);
             }
         }
     }
@@ -511,12 +531,12 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
 //                    order in which records are staged is a function of the sorted list alone, so
 //                    the reproducible variant needs no class split here.
 // ---------------------------------------------------------------------------------------------
+// tg: the sign term of the block's element 0 (the token's term plus (Cg * c * Z) mod P for chunk c)
 template <bool SIGN>
-__device__ __forceinline__ float signed_block_value(const Params &p, float v, uint32_t tg, uint32_t src, uint32_t j)
+__device__ __forceinline__ float signed_block_value(const Params &p, float v, uint32_t tg, uint32_t j)
 {
     if constexpr (SIGN) {
-        const uint32_t el = (src % p.C) * p.Z + j;
-        return apply_sign(v, sign_mask(add_p(tg, mod_p((uint64_t)p.Cg * el))));
+        return apply_sign(v, sign_mask(add_p(tg, mod_p((uint64_t)p.Cg * j))));
     } else {
         return v;
     }
@@ -671,7 +691,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
     const uint32_t R = 1u << s.r_shift;
     const uint32_t r0 = r << s.r_shift;
     const uint32_t region_len = (p.m - r0) < R ? (p.m - r0) : R;
-    const uint32_t src_own = s.rows * p.C;   // source blocks below this live in grad_out, the rest in P
+    const uint32_t src_own = s.src_own;      // source blocks below this live in grad_out, the rest in P
 
     uint2 *srt = reinterpret_cast<uint2 *>(acc + R);
     uint32_t *srt_tg = reinterpret_cast<uint32_t *>(srt + kRecBatch);
@@ -809,6 +829,13 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
                         if ((uint32_t)k < live && sr4[k] != kNoRun && th4[k] >= kr.ta && th4[k] < kr.tb) hits |= 1u << k;
+                    if (hits && s.run_c != nullptr) {          // tables of different dimensions: has the run a chunk kr.c at all?
+                        const uint4 c4 = *reinterpret_cast<const uint4 *>(s.run_c + q);
+                        const uint32_t nc4[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            if (((hits >> k) & 1u) && nc4[k] <= kr.c) hits &= ~(1u << k);
+                    }
                     if (hits) {
                         uint32_t tg4[4] = {0, 0, 0, 0};
                         if constexpr (SIGN) {
@@ -822,8 +849,8 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                             if (slot < (uint32_t)kRecBatch) {
                                 const uint32_t o = offset_of(p, th4[k], kr.cc);
                                 const bool inside = o >= r0 && o - r0 < region_len;
-                                srt[slot] = make_uint2(o, (sr4[k] * p.C + kr.c) | (inside ? 0u : kPartBit));
-                                if constexpr (SIGN) srt_tg[slot] = tg4[k];
+                                srt[slot] = make_uint2(o, (sr4[k] + kr.c) | (inside ? 0u : kPartBit));
+                                if constexpr (SIGN) srt_tg[slot] = add_p(tg4[k], mod_p((uint64_t)p.Cg * (kr.c * p.Z)));
                             }
                             ++slot;
                         }
@@ -1005,7 +1032,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                 for (int u = 0; u < kRecAhead; ++u) {
                     const uint32_t a = abase[u] + j;
                     if (a < region_len) {
-                        const float val = signed_block_value<SIGN>(p, v[u], tg[u], src[u], j);
+                        const float val = signed_block_value<SIGN>(p, v[u], tg[u], j);
                         if constexpr (SPILL) {
                             // one read-modify-write, in the slice or in the group's spill-over row
                             // (which follows acc at spill_at; a - slice_end < Z - 1)
@@ -1037,7 +1064,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                 for (uint32_t j = j0; j < p.Z; j += LG) {
                     const uint32_t a = abase + j;
                     if (a >= slice_end && a < region_len)
-                        acc[a] += signed_block_value<SIGN>(p, base[j], tgk, src, j);
+                        acc[a] += signed_block_value<SIGN>(p, base[j], tgk, j);
                 }
             }
         }

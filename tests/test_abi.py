@@ -107,6 +107,11 @@ def test_entry_points_reject_bad_arguments_without_a_gpu():
     assert b"dims[1]" in L.robe_last_error()
     assert L.robe_forward_mixed(ref, dims_ok, None, fake, None, 4, 2, 2, fake, None, None) == EINVAL
     assert L.robe_backward_mixed(ref, dims_ok, fake, fake, None, 5, 2, 2, fake, None, 0, None, None) == EINVAL
+    assert L.robe_backward_adagrad_mixed(ref, dims_ok, fake, fake, None, 5, 2, 2, fake, fake, 0.01, 1e-8, None, 0, None, None) == EINVAL
+    assert L.robe_backward_adagrad_mixed(ref, dims_bad, fake, fake, None, 4, 2, 2, fake, fake, 0.01, 1e-8, None, 0, None, None) == EINVAL
+    need = ctypes.c_size_t(7)
+    assert L.robe_fused_mixed_workspace_bytes(ref, dims_ok, 2, 2, 4, None, ctypes.byref(need)) == robe.ROBE_OK and need.value > 0
+    assert L.robe_fused_mixed_workspace_bytes(ref, dims_bad, 2, 2, 4, None, ctypes.byref(need)) == EINVAL
     assert L.robe_forward_mixed(ref, dims_ok, None, None, None, 0, 0, 2, None, None, None) == robe.ROBE_OK
     # bfloat16 array
     assert L.robe_forward_bf16(ref, None, fake, None, 4, 2, 2, fake, None, None) == EINVAL
