@@ -393,6 +393,25 @@ def main():
             if k >= 3:
                 k_ms["bwd"].append(e[0].elapsed_time(e[1]))
                 k_ms["adagrad"].append(e[1].elapsed_time(e[2]))
+    mixed_fused = None
+    if mixed and do_bwd and not args.step_only:
+        # backward + Adagrad in one call over the tables of mixed dimensions, timed beside the step
+        # (the step itself stays forward + backward, so that its line compares with earlier ones)
+        st_m = torch.zeros(w.m, dtype=torch.float32, device=dev)
+        fb = max(robe.robe_fused_mixed_workspace_bytes(h, w.dims, B, n, opt) for n in tokens)
+        fws = torch.empty(max(fb, 1), dtype=torch.uint8, device=dev)
+        ms = []
+        for k in range(3 + 5):
+            idd, offd = dev_batches[k % len(dev_batches)]
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            e[0].record(stream)
+            robe.robe_backward_adagrad_mixed(h, w.dims, Gd, idd, offd, B, Md, st_m, 0.01, 1e-8, workspace=fws, options=opt)
+            e[1].record(stream)
+            torch.cuda.synchronize()
+            if k >= 3:
+                ms.append(e[0].elapsed_time(e[1]))
+        mixed_fused = {"entry_point": "robe_backward_adagrad_mixed", "ms": round(sum(ms) / len(ms), 4), "workspace_bytes": fb}
+        del st_m, fws
     # The same step with the ids (and CSR offsets) starting in pinned host memory, as the paper times
     # its inference runs (Section 5.4: the batch is sent from RAM to the GPU inside the timed region).
     # Reported beside the headline, never as `value`.
@@ -593,6 +612,7 @@ def main():
                            "what": "ids and CSR offsets copied from pinned host memory inside every step",
                            "ms_per_step_copy_overlapped": None if h2d_overlap_ms is None else round(h2d_overlap_ms, 4),
                            "lookups_per_s_copy_overlapped": None if h2d_overlap_ms is None else tok / (h2d_overlap_ms * 1e-3)},
+        "mixed_fused": mixed_fused,
         "graph_replay": None if graph_ms is None else {
             "ms_per_step": round(graph_ms, 5), "lookups_per_s": tok / (graph_ms * 1e-3),
             "what": "the same step captured once per id batch into one HIP graph; value stays the eager figure"},
