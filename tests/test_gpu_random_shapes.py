@@ -99,14 +99,13 @@ def test_random_problems_match_the_oracle(chunk):
             ref, _ = oracle.backward(H, Gi, i_, o_, B, F, threads=1)
             assert np.array_equal(ga.cpu().numpy().astype(np.float64), ref), tag
             # the same call with the reproducible option gives the same sums (exact here) when it has a route
-            if Z <= d:
-                gr = torch.zeros(m, dtype=torch.float32, device=DEV)
-                try:
-                    robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, gr, options=repro)
-                except robe.RobeError as e:
-                    assert "reproducible" in str(e), tag      # shapes without an atomic-free route
-                else:
-                    assert np.array_equal(gr.cpu().numpy().astype(np.float64), ref), tag
+            gr = torch.zeros(m, dtype=torch.float32, device=DEV)
+            try:
+                robe.robe_backward(h, dev(Gi), dev(i_), dev(o_), B, F, gr, options=repro)
+            except robe.RobeError as e:
+                assert "reproducible" in str(e), tag          # shapes without an atomic-free route
+            else:
+                assert np.array_equal(gr.cpu().numpy().astype(np.float64), ref), tag
         # bfloat16 array: single-hot bit-exact
         Mb = oracle.to_bf16(M)
         outq = robe.robe_forward_bf16(h, dev(Mb.view(np.int16)), dev(ids), None, B, F).cpu().numpy()
@@ -128,3 +127,13 @@ def test_random_problems_match_the_oracle(chunk):
             robe.robe_backward_mixed(h, dims, dev(Gm), dev(idsb), dev(off), B, gm, options=opt)
             refm, _ = oracle.backward_mixed(H, dims, Gm, idsb, off, B)
             assert np.array_equal(gm.cpu().numpy().astype(np.float64), refm), tag
+            # the reproducible option: the region route over all tables, or a loud refusal (a table
+            # narrower than the block, a shape without that route)
+            gq = torch.zeros(m, dtype=torch.float32, device=DEV)
+            try:
+                robe.robe_backward_mixed(h, dims, dev(Gm), dev(idsb), dev(off), B, gq, options=repro)
+            except robe.RobeError as e:
+                assert "reproducible" in str(e), tag
+            else:
+                assert min(dims) >= Z or idsb.size == 0, tag      # (no tokens: nothing to do, any shape)
+                assert np.array_equal(gq.cpu().numpy().astype(np.float64), refm), tag
