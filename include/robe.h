@@ -121,6 +121,7 @@ typedef struct robe_hash_t {
  *                  every tile of 64 lookups before the atomics
  *   region_shift   log2 of the region size in floats for ROBE_ROUTE_REGIONS, 10..15
  *   key_bits       most significant bits of the 31-bit token key that the sort looks at, 8..31
+ *                  (with Z > d the key is an array offset below m: at most ceil(log2 m) bits)
  *   region_records 0 by size, 1: ROBE_ROUTE_REGIONS writes a region-sorted copy of the block records,
  *                  2: the region workgroups look their blocks up in the sorted token list instead
  *   probe_kernel, probe_begin, probe_end

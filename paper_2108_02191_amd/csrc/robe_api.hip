@@ -512,22 +512,6 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     static_assert(robe::kMaxRecordLanes <= 64 && (robe::kMaxRecordLanes & (robe::kMaxRecordLanes - 1)) == 0,
                   "a lane group of the reduce kernel is a power of two and never spans two wavefronts");
     const uint32_t grp_shift = 9 - log2u(lg);
-    // rows of P: an eighth of the positions a lane group of the combine kernel walks, for every group
-    // (a group that meets more runs of repeated tokens than that leaves the rest uncombined; on the
-    // Zipf-distributed bags of the benchmark a walk of 512 positions holds 26 such runs on average
-    // and 60 at most)
-    // (long walks combine more copies of a frequent token per record, but a small problem needs its
-    // wavefronts: halve the walk until the combine kernel has a couple of thousand workgroups)
-    uint32_t stretch = robe::kStretch;
-    while (stretch > 1 && n / ((uint64_t)robe::kBlock * stretch) < 2048) stretch >>= 1;
-    const uint64_t walk = (uint64_t)stretch * pl.lay.G;
-    const uint32_t p_quota = walk / 8 ? (uint32_t)(walk / 8) : 1u;
-    const uint64_t combine_blocks = (n + (uint64_t)robe::kBlock * stretch - 1) / ((uint64_t)robe::kBlock * stretch);
-    const uint64_t p_rows = combine_blocks * (robe::kBlock / pl.lay.G) * p_quota;
-    // source blocks (Z floats each): those of grad_out, then those of P
-    const uint64_t src_own = mixed_floats ? mixed_floats / h->Z : (uint64_t)rows * C;
-    if (src_own + p_rows * C >= 0x7FFFFFFFull) return pl;                // 31-bit source block numbers
-
     // Gather variant: the reduce kernel reads the sorted token list through a range table of
     // C * ((P - 1) / m + 3) entries, which must fit its LDS: large arrays, few chunks per embedding.
     // No record kernels, no record storage, any number of regions.  Taken by default where the region
@@ -561,14 +545,34 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     // second record), plus every run of the most frequent token (one per walk of a lane group) in one
     // region, against six tenths of the room.  (The gather variant stages its records in an order
     // that is fixed by the sorted list and needs no such split.)
-    if (opt.reproducible && !pl.gather) {
+    auto within_reproducible_bound = [&](uint64_t walk_positions) {
+        if (!opt.reproducible || pl.gather) return true;
         const uint64_t batch = h->use_sign ? robe::rec_batch<true>() : robe::rec_batch<false>();
         const uint64_t room = ((batch << robe::kMaxClassShift) * 6) / 10;
         const uint64_t R = 1ull << shift, span = R < h->m ? R : h->m;
         const uint64_t avg = (n * C * (span + h->Z) / span + NR - 1) / NR;
-        const uint64_t worst = avg + avg / 2 + 2ull * C * (n / walk + 1);
-        if (worst > room) return pl;
-    }
+        const uint64_t worst = avg + avg / 2 + 2ull * C * (n / walk_positions + 1);
+        return worst <= room;
+    };
+    // rows of P: an eighth of the positions a lane group of the combine kernel walks, for every group
+    // (a group that meets more runs of repeated tokens than that leaves the rest uncombined; on the
+    // Zipf-distributed bags of the benchmark a walk of 512 positions holds 26 such runs on average
+    // and 60 at most)
+    // (long walks combine more copies of a frequent token per record, but a small problem needs its
+    // wavefronts: halve the walk until the combine kernel has a couple of thousand workgroups)
+    // (as long as the bound above holds: it counts one run of the most frequent token per walk)
+    uint32_t stretch = robe::kStretch;
+    while (stretch > 1 && n / ((uint64_t)robe::kBlock * stretch) < 2048) stretch >>= 1;
+    while (stretch < (uint32_t)robe::kStretch && !within_reproducible_bound((uint64_t)stretch * pl.lay.G)) stretch <<= 1;
+    if (!within_reproducible_bound((uint64_t)stretch * pl.lay.G)) return pl;
+    const uint64_t walk = (uint64_t)stretch * pl.lay.G;
+    const uint32_t p_quota = walk / 8 ? (uint32_t)(walk / 8) : 1u;
+    const uint64_t combine_blocks = (n + (uint64_t)robe::kBlock * stretch - 1) / ((uint64_t)robe::kBlock * stretch);
+    const uint64_t p_rows = combine_blocks * (robe::kBlock / pl.lay.G) * p_quota;
+    // source blocks (Z floats each): those of grad_out, then those of P
+    const uint64_t src_own = mixed_floats ? mixed_floats / h->Z : (uint64_t)rows * C;
+    if (src_own + p_rows * C >= 0x7FFFFFFFull) return pl;                // 31-bit source block numbers
+
     pl.regions = true;
     robe::RegionPlan &r = pl.rp;
     r.r_shift = shift;
@@ -635,7 +639,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
                           const int64_t *offsets, int64_t n_indices, int64_t rows, uint32_t F,
                           float *grad_array, void *workspace, hipStream_t stream,
                           int rule = 0, float *state = nullptr, float lr = 0.0f, float eps = 0.0f,
-                          const uint2 *tables = nullptr, int64_t sample_floats = 0)
+                          uint2 *tables = nullptr, int64_t sample_floats = 0, const uint32_t *dims = nullptr)
 {
     const robe::Params p_keys = to_params(h);     // the caller's instance: S1 hashes the ids with it
     h = &pl.eff;                                  // everything after S1 (see plan_backward)
@@ -662,10 +666,23 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
     uint64_t key_blocks = (key_threads + 255) / 256;
     if (key_blocks > 65536) key_blocks = 65536;
     const dim3 kgrid((uint32_t)key_blocks), kblock(256);
+    // tables of mixed dimensions: the key kernel also writes the per-table map (its first kTableArgs entries)
+    robe::TableArgs tab;
+    memset(&tab, 0, sizeof(tab));
+    uint32_t n_tab = 0;
+    if (tables != nullptr && dims != nullptr) {
+        uint32_t col = 0;
+        n_tab = F < (uint32_t)robe::kTableArgs ? F : (uint32_t)robe::kTableArgs;
+        for (uint32_t k = 0; k < n_tab; ++k) {
+            tab.col[k] = col;
+            tab.dim[k] = dims[k];
+            col += dims[k];
+        }
+    }
     // sign off: the sorted value is the token's row of grad_out and positions are never needed again
-    if (bags && sign) robe::token_keys_kernel<true, false><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
-    else if (bags) robe::token_keys_kernel<true, true><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
-    else robe::token_keys_kernel<false, true><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag);
+    if (bags && sign) robe::token_keys_kernel<true, false><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag, tab, n_tab, tables);
+    else if (bags) robe::token_keys_kernel<true, true><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag, tab, n_tab, tables);
+    else robe::token_keys_kernel<false, true><<<kgrid, kblock, 0, stream>>>(p_keys, F, g_shift, indices, offsets, urows, n, keys_in, vals_in, tok_bag, tab, n_tab, tables);
     if (int rc = check_launch("backward (keys)")) return rc;
 
     // S2: sort (key, value) pairs by the top key_bits bits of the key
@@ -1092,8 +1109,10 @@ static int launch_mixed_sorted(const MixedPlan &mp, const Opt &opt, const uint32
                                int rule = 0, float *state = nullptr, float lr = 0.0f, float eps = 0.0f)
 {
     uint2 *tables = reinterpret_cast<uint2 *>(static_cast<char *>(workspace) + mp.off_tables);
+    // the per-table map: its first kTableArgs entries travel with the key kernel, the rest go here
     uint32_t col = 0;
-    for (int32_t f0 = 0; f0 < n_features; f0 += robe::kTableArgs) {
+    for (int32_t f = 0; f < n_features && f < robe::kTableArgs; ++f) col += dims[f];
+    for (int32_t f0 = robe::kTableArgs; f0 < n_features; f0 += robe::kTableArgs) {
         robe::TableArgs a;
         memset(&a, 0, sizeof(a));
         const int32_t cnt = n_features - f0 < robe::kTableArgs ? n_features - f0 : robe::kTableArgs;
@@ -1106,7 +1125,7 @@ static int launch_mixed_sorted(const MixedPlan &mp, const Opt &opt, const uint32
         if (int rc = check_launch("backward (table map)")) return rc;
     }
     return launch_dedup_backward(&mp.widest, opt, mp.pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
-                                 dst, workspace, s, rule, state, lr, eps, tables, mp.D);
+                                 dst, workspace, s, rule, state, lr, eps, tables, mp.D, dims);
 }
 
 int robe_mixed_workspace_bytes(const robe_hash_t *hash, const uint32_t *dims, int64_t batch, int32_t n_features,

@@ -54,14 +54,30 @@ __device__ __forceinline__ uint32_t sort_key(const Params &p, int64_t x, uint32_
     return wrap(offset_of(p, staged_h(p, chunk, e), 0u) + place, p.m);
 }
 
+// Tables of mixed dimensions: the per-table map (first float inside a sample, dimension) that the
+// combine kernels look rows up in, written from kernel arguments: the first kTableArgs tables by the
+// key kernel (which runs before anything reads the map), further ones kTableArgs per launch of
+// table_map_kernel.
+constexpr int kTableArgs = 64;
+struct TableArgs {
+    uint32_t col[kTableArgs], dim[kTableArgs];
+};
+
+__global__ __launch_bounds__(64) void table_map_kernel(TableArgs a, uint32_t first, uint32_t count, uint2 *__restrict__ tables)
+{
+    if (threadIdx.x < count) tables[first + threadIdx.x] = make_uint2(a.col[threadIdx.x], a.dim[threadIdx.x]);
+}
+
 template <bool BAGS, bool ROWVAL>
 __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, uint32_t g_shift,
                                                          const int64_t *__restrict__ indices,
                                                          const int64_t *__restrict__ offsets,
                                                          uint32_t rows, uint32_t n_indices,
                                                          uint32_t *__restrict__ keys, uint32_t *__restrict__ vals,
-                                                         uint32_t *__restrict__ tok_bag)
+                                                         uint32_t *__restrict__ tok_bag,
+                                                         TableArgs tab, uint32_t n_tab, uint2 *__restrict__ tables)
 {
+    if (blockIdx.x == 0 && threadIdx.x < n_tab) tables[threadIdx.x] = make_uint2(tab.col[threadIdx.x], tab.dim[threadIdx.x]);
     const uint32_t G = 1u << g_shift;
     const uint32_t lane = threadIdx.x & (G - 1u);
     const uint64_t groups = ((uint64_t)gridDim.x * 256u) >> g_shift;
@@ -106,18 +122,6 @@ __global__ __launch_bounds__(256) void token_keys_kernel(Params p, uint32_t F, u
             }
         }
     }
-}
-
-// Tables of mixed dimensions: the per-table map (first float inside a sample, dimension) that the
-// combine kernel looks rows up in, written from kernel arguments, kTableArgs tables per launch.
-constexpr int kTableArgs = 64;
-struct TableArgs {
-    uint32_t col[kTableArgs], dim[kTableArgs];
-};
-
-__global__ __launch_bounds__(64) void table_map_kernel(TableArgs a, uint32_t first, uint32_t count, uint2 *__restrict__ tables)
-{
-    if (threadIdx.x < count) tables[first + threadIdx.x] = make_uint2(a.col[threadIdx.x], a.dim[threadIdx.x]);
 }
 
 // S3.  Lane layout as in the direct scatter: G lanes per row, lane `grp` owns elements grp + k*G.

@@ -42,6 +42,7 @@ CASES = [
     (500_009, (256, 512, 128), 128),
     (100_003, (4, 16, 64, 8, 16, 2), 16),       # tables narrower than the block: 4, 2 and 8 tokens share one (Section 3.3)
     (70_001, (1, 3, 6, 12), 6),
+    (200_003, tuple(8 * (1 + k % 4) for k in range(70)), 8),      # more tables than one launch's table map holds
 ]
 ROUTES = [robe.ROUTE_DIRECT, robe.ROUTE_COMBINE, robe.ROUTE_REGIONS]
 
