@@ -409,6 +409,7 @@ struct BwdPlan {
     bool regions;        // ... and then sort the blocks by destination region instead of using float atomics
     bool spill_rows;     // ... with room in LDS for a row of Z floats per lane group of the reduce kernel
     bool gather;         // ... and the reduce kernel finds its blocks in the sorted token list (no record kernels)
+    bool window_sort;    // atomics route after a sort on few key bits: the combine kernel orders each wavefront's positions itself
     Layout lay;
     robe_hash_t eff;     // the instance the kernels after the key kernel run on: the caller's, or (Z > d) its one-chunk form
     uint32_t key_top;    // keys are below 2^key_top
@@ -505,7 +506,16 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
 
     // Region-sorted scatter on top of the combined runs.
     const bool want_regions = need_regions || (route == ROBE_ROUTE_AUTO ? regions_by_default(h, n_indices) : route == ROBE_ROUTE_REGIONS);
-    if (!want_regions) return pl;
+    if (!want_regions) {
+        // Atomics after the sort: up to 2^21 tokens, 16 key bits - two radix passes instead of three,
+        // each three launches of 5 to 10 us.  The tokens of a key bucket (2^-16 of them) then sit
+        // interleaved, and the combine kernel sorts every wavefront's 64 positions by the whole key.
+        if (!opt.key_bits && pl.key_bits > 16 && n_indices <= (1ll << 21)) {
+            pl.key_bits = 16;
+            pl.window_sort = true;
+        }
+        return pl;
+    }
     const uint64_t C = h->d / h->Z;                       // Z <= d here
     uint32_t lg = 8;  // lanes per record in the reduce kernel: at most 64 groups per workgroup, a group inside one wavefront
     while (lg < robe::kMaxRecordLanes && lg < h->Z) lg <<= 1;
@@ -706,6 +716,7 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
     q.G = pl.lay.G;
     q.g_shift = log2u(pl.lay.G);
     q.tables = tables;              // tables of mixed dimensions
+    q.window_sort = pl.window_sort ? 1u : 0u;
     q.row_floats = sample_floats;
     const uint64_t blocks = ((uint64_t)n + robe::kBlock - 1) / robe::kBlock;   // one lane per sorted position
     const dim3 grid((uint32_t)blocks), block(robe::kBlock);

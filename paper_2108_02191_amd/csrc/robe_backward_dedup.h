@@ -181,6 +181,34 @@ __global__ __launch_bounds__(kBlock) void combine_scatter_kernel(Params p, Geom 
                 }
             }
         }
+        // A coarse sort (few key bits) leaves the tokens of one key bucket interleaved.  A lane group's
+        // run never outlives its walk anyway, so putting the wavefront's 64 positions in key order
+        // here (bitonic network over the lanes; the key is made unique by the lane it came from, which
+        // also says where to fetch the rest of the token) finds the same runs a full sort would.
+        if (q.window_sort) {
+            uint64_t sk = my_ok ? (((uint64_t)my_th << 6) | lane) : ((1ull << 40) | lane);
+#pragma unroll
+            for (uint32_t kk = 2; kk <= 64u; kk <<= 1) {
+#pragma unroll
+                for (uint32_t j = kk >> 1; j > 0; j >>= 1) {
+                    const uint32_t lo = __shfl_xor((uint32_t)sk, (int)j), hi = __shfl_xor((uint32_t)(sk >> 32), (int)j);
+                    const uint64_t other = ((uint64_t)hi << 32) | lo;
+                    const bool take_min = ((lane & j) == 0) == ((lane & kk) == 0);
+                    sk = take_min ? (other < sk ? other : sk) : (other > sk ? other : sk);
+                }
+            }
+            const int from = (int)(sk & 63u);
+            my_ok = (sk >> 40) == 0;
+            my_th = my_ok ? (uint32_t)(sk >> 6) : 0u;
+            my_at = __shfl(my_at, from);
+            if (q.tables != nullptr) my_d = __shfl(my_d, from);
+            if (SIGN || q.tables != nullptr) my_e = __shfl(my_e, from);
+            if constexpr (SIGN) {
+                my_tg = __shfl(my_tg, from);
+                const uint32_t xlo = __shfl((uint32_t)my_x, from), xhi = __shfl((uint32_t)((uint64_t)my_x >> 32), from);
+                my_x = (int64_t)(((uint64_t)xhi << 32) | xlo);
+            }
+        }
         // does this position start a new run?  (a different token than the one before, or the walk begins)
         const int prev = (int)(base_lane + (grp ? grp - 1u : 0u));
         uint32_t p_th = __shfl(my_th, prev);

@@ -47,6 +47,10 @@ struct Geom {
     // first float inside a sample (.x) and its dimension (.y); d above is then the largest dimension.
     // NULL: every table has dimension d and row k starts at float k * d.
     const uint2 *tables;
+    // Sorted backward with float atomics: 1 when the sort looked at few key bits, so that tokens whose
+    // keys agree in those bits sit interleaved; the combine kernel then sorts every wavefront's 64
+    // positions by the whole key before it looks for runs.
+    uint32_t window_sort;
 };
 
 // One row of a launch: where its id (or bag bounds) and its d floats live, and its table id.
