@@ -10,7 +10,7 @@
 //               part of its offset hash, equal for equal (e, x) - and a value: its
 //               row of grad_out when the sign is off, its position when it is on.
 //               (Blocks larger than embeddings: the key is the array offset itself, see sort_key.)
-//   S2 sort     stable radix sort of (key, value) pairs (robe_radix_sort.h, or the device library's).
+//   S2 sort     stable radix sort of (key, value) pairs (robe_radix_sort.h).
 //   S3 combine  a group of G lanes walks G consecutive sorted tokens, adds the
 //               gradient rows of runs of identical tokens in registers, and issues
 //               the d atomics once per run.  A run longer than a group's walk (kWalk

@@ -17,9 +17,8 @@
 // counted for the digit, plus the lanes below it in its own round with the same digit (found with one
 // ballot per digit bit), plus what the wavefronts before it hold.
 //
-// The device library's radix sort does the same job; it is kept as an alternative.  This one is
-// shorter on launches and fill operations for the sizes met here (10^5 .. 10^7 pairs) and records
-// nothing but kernels on the stream.
+// It records nothing but kernels on the stream (no fill operations), and for the sizes met here
+// (10^5 .. 10^7 pairs) it is shorter on launches than the device library's sort.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
