@@ -488,7 +488,8 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     if (!forced && (uint64_t)n_indices * h->d < (1ull << 25)) return pl;
     // Sorting on the top 24 key bits is one radix pass cheaper; tokens that share those bits merely
     // interleave and are merged less often, which stays rare while there are far fewer tokens than 2^24.
-    pl.key_bits = opt.key_bits ? (uint32_t)opt.key_bits : (n_indices <= (1ll << 24) ? 24u : 31u);
+    // (up to 2^18 tokens 16 bits do: a key bucket then holds four tokens at most on average)
+    pl.key_bits = opt.key_bits ? (uint32_t)opt.key_bits : (n_indices <= (1ll << 18) ? 16u : (n_indices <= (1ll << 24) ? 24u : 31u));
     if (pl.key_bits > pl.key_top) pl.key_bits = pl.key_top;
 
     const size_t n = (size_t)n_indices;
@@ -510,7 +511,7 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
         // Atomics after the sort: up to 2^21 tokens, 16 key bits - two radix passes instead of three,
         // each three launches of 5 to 10 us.  The tokens of a key bucket (2^-16 of them) then sit
         // interleaved, and the combine kernel sorts every wavefront's 64 positions by the whole key.
-        if (!opt.key_bits && pl.key_bits > 16 && n_indices <= (1ll << 21)) {
+        if (!opt.key_bits && pl.key_bits >= 16 && n_indices <= (1ll << 21)) {
             pl.key_bits = 16;
             pl.window_sort = true;
         }
@@ -524,8 +525,8 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
     const uint32_t grp_shift = 9 - log2u(lg);
     // Gather variant: the reduce kernel reads the sorted token list through a range table of
     // C * ((P - 1) / m + 3) entries, which must fit its LDS: large arrays, few chunks per embedding.
-    // No record kernels, no record storage, any number of regions.  Taken by default where the region
-    // route is (arrays of 2^26 slots or more); options->region_records forces either variant.
+    // No record kernels, no record storage, any number of regions.  options->region_records asks for
+    // either variant.
     uint32_t shift = 0;
     {
         const uint32_t gshift = opt.region_shift ? (uint32_t)opt.region_shift : 13u;
@@ -533,7 +534,14 @@ BwdPlan plan_backward(const robe_hash_t *caller_hash, const Opt &opt, int64_t ro
         const uint32_t cap = h->use_sign ? robe::gather_entries_max<true>() : robe::gather_entries_max<false>();
         const bool can = R >= 2ull * h->Z && h->m >= R + h->Z && NE <= cap && gshift >= grp_shift &&
                          (1u << (gshift - grp_shift)) >= h->Z && ((h->m + R - 1) >> gshift) <= 0x7FFFFFFFull;
-        const bool want = opt.region_records == 2 || (opt.region_records == 0 && h->m >= (1ull << 26));
+        // By default on arrays of 2^26 slots or more, from 2^22 tokens on: with fewer tokens the record
+        // kernels are quicker (batch 1024 of the benchmark's bags on the 1 GB array: 0.48 against
+        // 0.51 ms; most regions then hold a handful of blocks, which a region's workgroup reads in one
+        // trip instead of looking them up in two), unless their record counts or region table do not fit.
+        // (The reproducible option keeps the lookup: its order of additions needs no bound on a region's records.)
+        const bool records_fit = pick_region_shift(h, opt.region_shift) != 0 && 3ull * n * C < 0xFFFFFFFFull;
+        const bool want = opt.region_records == 2 ||
+                          (opt.region_records == 0 && h->m >= (1ull << 26) && (n >= (1ull << 22) || !records_fit || opt.reproducible));
         if (can && want) {
             pl.gather = true;
             shift = gshift;
