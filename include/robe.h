@@ -321,6 +321,19 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out,
                           const robe_options_t *options, void *stream);
 
 /*
+ * The same with the SGD rule of robe_sgd_update (the rule the paper trains DLRM with, Appendix,
+ * hyper-parameter table): array[j] -= lr * (sum of Eq. 3 for slot j), in float32 with the product and
+ * the difference rounded on their own, for every slot that receives a gradient; the others are left
+ * bit-for-bit unchanged.  Routes, workspace (robe_fused_workspace_bytes, same options) and errors as
+ * robe_backward_adagrad; there is no state.
+ */
+int robe_backward_sgd(const robe_hash_t *hash, const float *grad_out,
+                      const int64_t *indices, const int64_t *offsets, int64_t n_indices,
+                      int64_t batch, int32_t n_features, float *array, float lr,
+                      void *workspace, size_t workspace_bytes,
+                      const robe_options_t *options, void *stream);
+
+/*
  * Tables of different embedding dimensions sharing the one array (Section 3.2, "Multiple embedding
  * tables": all tables, even with varying dimensions, share the array; the table id is an argument of
  * h and g).  Table f has dimension dims[f], a positive multiple of Z or a divisor of it; its

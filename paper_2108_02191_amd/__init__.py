@@ -60,7 +60,7 @@ ROWS_AUTO, ROWS_MEMORY, ROWS_BY_TABLE, ROWS_BY_TABLE_ALWAYS = 0, 1, 2, 3
 PROBE_NONE, PROBE_COMBINE, PROBE_REDUCE, PROBE_SORT = 0, 1, 2, 3
 
 EXPORTS = ("robe_init_hash", "robe_offsets", "robe_forward", "robe_workspace_bytes", "robe_backward",
-           "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad",
+           "robe_adagrad_update", "robe_sgd_update", "robe_fused_workspace_bytes", "robe_backward_adagrad", "robe_backward_sgd",
            "robe_forward_mixed", "robe_mixed_workspace_bytes", "robe_backward_mixed", "robe_fused_mixed_workspace_bytes",
            "robe_backward_adagrad_mixed", "robe_array_to_bf16", "robe_forward_bf16",
            "robe_sort_workspace_bytes", "robe_sort_pairs", "robe_noalloc_max_workspace_bytes", "robe_backward_noalloc",
@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.robe_backward_adagrad.restype = ctypes.c_int
         L.robe_backward_adagrad.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, vp, ctypes.c_float, ctypes.c_float,
                                             vp, ctypes.c_size_t, OP, vp]
+        L.robe_backward_sgd.restype = ctypes.c_int
+        L.robe_backward_sgd.argtypes = [HP, vp, vp, vp, i64, i64, i32, vp, ctypes.c_float, vp, ctypes.c_size_t, OP, vp]
         L.robe_forward_mixed.restype = ctypes.c_int
         L.robe_forward_mixed.argtypes = [HP, vp, vp, vp, vp, i64, i64, i32, vp, OP, vp]
         L.robe_mixed_workspace_bytes.restype = ctypes.c_int
@@ -288,6 +290,24 @@ def robe_backward_adagrad(h: RobeHash, grad_out: torch.Tensor, indices: torch.Te
                                        _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
                                        indices.numel(), batch, n_features, _dev(array, torch.float32, "array"),
                                        _dev(state, torch.float32, "state"), lr, eps, ws_ptr, ws_len, _opt(options), _stream()))
+
+
+def robe_backward_sgd(h: RobeHash, grad_out: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                      batch: int, n_features: int, array: torch.Tensor, lr: float,
+                      workspace: Optional[torch.Tensor] = None, options: Optional[RobeOptions] = None) -> None:
+    """Backward scatter-add and SGD update in one call (array updated in place)."""
+    if array.numel() != h.m:
+        raise ValueError("array length differs from hash.m")
+    if grad_out.numel() != batch * n_features * h.d:
+        raise ValueError("grad_out has the wrong size")
+    if offsets is not None and offsets.numel() != batch * n_features + 1:
+        raise ValueError("offsets must hold batch*n_features + 1 entries")
+    need = robe_fused_workspace_bytes(h, batch, n_features, indices.numel(), options) if workspace is None else 0
+    workspace, ws_ptr, ws_len = _workspace(workspace, need, array.device)
+    _check(lib().robe_backward_sgd(ctypes.byref(h), _dev(grad_out, torch.float32, "grad_out"),
+                                   _dev(indices, torch.int64, "indices"), _dev(offsets, torch.int64, "offsets"),
+                                   indices.numel(), batch, n_features, _dev(array, torch.float32, "array"),
+                                   lr, ws_ptr, ws_len, _opt(options), _stream()))
 
 
 def _dims_array(dims):

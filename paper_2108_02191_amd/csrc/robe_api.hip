@@ -652,7 +652,8 @@ int allow_lds(K kernel, size_t bytes, const char *what)
     return ROBE_OK;
 }
 
-// rule 0: grad_array += scatter.  rule 1 (regions only): Adagrad on (array = dst, state) with the scatter as gradient.
+// rule 0: grad_array += scatter.  Regions only: rule 1, Adagrad on (array = dst, state) with the scatter
+// as gradient; rule 2, SGD on array = dst (the scatter rule of the reduce kernel with the scale -lr).
 int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &pl, const float *grad_out, const int64_t *indices,
                           const int64_t *offsets, int64_t n_indices, int64_t rows, uint32_t F,
                           float *grad_array, void *workspace, hipStream_t stream,
@@ -738,7 +739,8 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
     if (pl.regions) {
         robe::RegionPlan r = pl.rp;
         r.keys = keys_out;
-        r.keep_array = (rule == 1 && h->m <= kKeepArrayMax) ? 1u : 0u;
+        r.keep_array = (rule != 0 && h->m <= kKeepArrayMax) ? 1u : 0u;
+        const float scale = rule == 2 ? -lr : (rule == 0 ? 1.0f : lr);    // what the reduce kernel gets as lr
         r.head = pl.gather ? nullptr : reinterpret_cast<uint8_t *>(ws + pl.off_head);
         r.src_row = reinterpret_cast<uint32_t *>(ws + pl.off_src_row);
         r.run_tg = reinterpret_cast<uint32_t *>(ws + pl.off_run_tg);
@@ -805,13 +807,13 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
 
         // R5: one workgroup per region
         const size_t lds_red = robe::reduce_lds_bytes(r.r_shift, sign, pl.gather, pl.spill_rows);
-        const int vec_ok = aligned(grad_array, 16) && (rule == 0 || aligned(state, 16)) ? 1 : 0;
+        const int vec_ok = aligned(grad_array, 16) && (rule != 1 || aligned(state, 16)) ? 1 : 0;
         const dim3 rgrid(r.NR), rblock(robe::kReduceBlock);
         const bool canon = opt.reproducible;
 #define ROBE_REDUCE_G(S_, R_, C_, P_, G_)                                                                             \
     do {                                                                                                              \
         if (int rc = allow_lds(robe::region_reduce_kernel<S_, R_, C_, P_, G_>, lds_red, "backward (reduce)")) return rc;  \
-        robe::region_reduce_kernel<S_, R_, C_, P_, G_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, lr, eps, vec_ok); \
+        robe::region_reduce_kernel<S_, R_, C_, P_, G_><<<rgrid, rblock, lds_red, stream>>>(p, r, grad_out, grad_array, state, scale, eps, vec_ok); \
     } while (0)
 #define ROBE_REDUCE_C(S_, R_, C_, P_)                                                                                 \
     do {                                                                                                              \
@@ -826,8 +828,8 @@ int launch_dedup_backward(const robe_hash_t *h, const Opt &opt, const BwdPlan &p
         else ROBE_REDUCE_C(S_, R_, false, false);                                                                     \
     } while (0)
         if (int rc = probe(opt, ROBE_PROBE_REDUCE, false, stream)) return rc;
-        if (sign) { if (rule) ROBE_REDUCE(true, 1); else ROBE_REDUCE(true, 0); }
-        else      { if (rule) ROBE_REDUCE(false, 1); else ROBE_REDUCE(false, 0); }
+        if (sign) { if (rule == 1) ROBE_REDUCE(true, 1); else ROBE_REDUCE(true, 0); }
+        else      { if (rule == 1) ROBE_REDUCE(false, 1); else ROBE_REDUCE(false, 0); }
 #undef ROBE_REDUCE
 #undef ROBE_REDUCE_C
 #undef ROBE_REDUCE_G
@@ -1334,18 +1336,21 @@ int robe_fused_workspace_bytes(const robe_hash_t *hash, int64_t batch, int32_t n
     return ROBE_OK;
 }
 
-int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
-                          int64_t n_indices, int64_t batch, int32_t n_features, float *array, float *state,
-                          float lr, float eps, void *workspace, size_t workspace_bytes,
-                          const robe_options_t *options, void *stream)
+// Backward and update rule in one call (rule 1: Adagrad, rule 2: SGD): the fused region route when
+// the plan has one, else two steps through a gradient array at the front of the workspace.
+static int fused_step(int rule, const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
+                      int64_t n_indices, int64_t batch, int32_t n_features, float *array, float *state,
+                      float lr, float eps, void *workspace, size_t workspace_bytes,
+                      const robe_options_t *options, void *stream)
 {
     int64_t rows = 0;
     Opt opt;
     if (int rc = read_options(options, &opt)) return rc;
     if (int rc = check_rows(hash, indices, offsets, n_indices, batch, n_features, &rows)) return rc;
-    if (array == nullptr || state == nullptr) return fail(ROBE_EINVAL, "array or state is NULL");
-    if (!std::isfinite(lr) || !std::isfinite(eps) || !(eps > 0.0f)) return fail(ROBE_EINVAL, "need finite lr and eps > 0");
-    if (!aligned(array, 4) || !aligned(state, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
+    if (array == nullptr || (rule == 1 && state == nullptr)) return fail(ROBE_EINVAL, rule == 1 ? "array or state is NULL" : "array is NULL");
+    if (!std::isfinite(lr)) return fail(ROBE_EINVAL, "need a finite lr");
+    if (rule == 1 && (!std::isfinite(eps) || !(eps > 0.0f))) return fail(ROBE_EINVAL, "need finite lr and eps > 0");
+    if (!aligned(array, 4) || (rule == 1 && !aligned(state, 4))) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
     if (rows == 0 || n_indices == 0) return ROBE_OK;      // no gradient anywhere: nothing is touched
     if (grad_out == nullptr) return fail(ROBE_EINVAL, "grad_out is NULL");
     if (!aligned(grad_out, 4)) return fail(ROBE_EINVAL, "float buffers must be 4-byte aligned");
@@ -1360,7 +1365,7 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const 
     hipStream_t s = (hipStream_t)stream;
     if (fused)
         return launch_dedup_backward(hash, opt, pl, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features,
-                                     array, workspace, s, 1, state, lr, eps);
+                                     array, workspace, s, rule, state, lr, eps);
     // two steps through a gradient array at the front of the workspace
     float *grad = static_cast<float *>(workspace);
     const uint64_t m = hash->m;
@@ -1375,7 +1380,24 @@ int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const 
     else
         rc = launch_rows<true>(hash, opt, grad_out, indices, offsets, n_indices, rows, (uint32_t)n_features, grad, grad_out, s);
     if (rc) return rc;
-    return launch_update(0, hash, array, state, grad, lr, eps, stream, false);
+    return launch_update(rule == 1 ? 0 : 1, hash, array, state, grad, lr, eps, stream, false);
+}
+
+int robe_backward_adagrad(const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
+                          int64_t n_indices, int64_t batch, int32_t n_features, float *array, float *state,
+                          float lr, float eps, void *workspace, size_t workspace_bytes,
+                          const robe_options_t *options, void *stream)
+{
+    return fused_step(1, hash, grad_out, indices, offsets, n_indices, batch, n_features, array, state, lr, eps, workspace,
+                      workspace_bytes, options, stream);
+}
+
+int robe_backward_sgd(const robe_hash_t *hash, const float *grad_out, const int64_t *indices, const int64_t *offsets,
+                      int64_t n_indices, int64_t batch, int32_t n_features, float *array, float lr,
+                      void *workspace, size_t workspace_bytes, const robe_options_t *options, void *stream)
+{
+    return fused_step(2, hash, grad_out, indices, offsets, n_indices, batch, n_features, array, nullptr, lr, 0.0f, workspace,
+                      workspace_bytes, options, stream);
 }
 
 // The fused step over tables of mixed dimensions: the region route when the plan has one (and the

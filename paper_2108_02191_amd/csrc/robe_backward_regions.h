@@ -63,7 +63,7 @@ struct RegionPlan {
     uint32_t fullest_first;  // 1: R5 takes the regions by descending size class instead of by address
     uint32_t keep_rows;      // 1: gradient rows are read more than once (bags): R5 loads them with the default cache policy
     uint32_t sparse_regions; // 1: the tokens reach a small part of the array: R5 writes back by a list of touched granules
-    uint32_t keep_array;     // 1: R5 with the Adagrad rule leaves the array in the caches for the next forward pass (small arrays)
+    uint32_t keep_array;     // 1: R5 updates the array (Adagrad, SGD) and leaves it in the caches for the next forward pass (small arrays)
     // gather variant of R5 (no R2..R4): the range table has NE = C * epc entries, epc = kmax + 3 with
     // kmax = (P - 1) / m; dir[b] is the first sorted position whose key >> dir_shift is >= b
     // (dir[buckets] = n), written by R1; NULL when R2..R4 run instead
@@ -517,7 +517,9 @@ __global__ __launch_bounds__(1024) void region_scan_kernel(RegionPlan s)
 }
 
 // ---------------------------------------------------------------------------------------------
-// R5.  RULE 0: grad_array += region.  RULE 1: Adagrad on array / state with the region as gradient.
+// R5.  RULE 0: dst += lr * region, each operation rounded on its own (lr = 1: the scatter onto a
+// gradient array; lr = minus the learning rate: SGD on the array, the gradient never in memory).
+// RULE 1: Adagrad on array / state with the region as gradient.
 //
 // Where a region's records come from:
 //   GATHER = false   from the region-sorted copy that R2..R4 wrote (s.rec).
@@ -672,7 +674,7 @@ static_assert(reduce_lds_bytes(13, false, false, true) <= 40960 && reduce_lds_by
 template <bool SIGN, int RULE, bool CANON, bool SPILL, bool GATHER>
 __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void region_reduce_kernel(Params p, RegionPlan s,
                                                                      const float *__restrict__ grad_out,
-                                                                     float *__restrict__ dst,      // RULE 0: grad_array; RULE 1: array
+                                                                     float *__restrict__ dst,      // RULE 0: grad_array, or the array (SGD); RULE 1: array
                                                                      float *__restrict__ state,    // RULE 1 only
                                                                      float lr, float eps, int vec_ok)
 {
@@ -1095,7 +1097,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             for (int u = 0; u < kWb; ++u) {
                 if (touch[u]) {
                     const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
-                    if (RULE == 1 && s.keep_array) w[u] = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
+                    if (s.keep_array) w[u] = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
                     else w[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
                     if constexpr (RULE == 1) st[u] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(state + r0 + 4u * it));
                 }
@@ -1105,8 +1107,10 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
                 if (!touch[u]) continue;
                 const uint32_t it = it0 + (uint32_t)u * kReduceBlock + threadIdx.x;
                 if constexpr (RULE == 0) {
-                    w[u] += g[u];
-                    __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) w[u][k] = __fadd_rn(w[u][k], __fmul_rn(g[u][k], lr));
+                    if (s.keep_array) *reinterpret_cast<V4 *>(dst + r0 + 4u * it) = w[u];
+                    else __builtin_nontemporal_store(w[u], reinterpret_cast<V4 *>(dst + r0 + 4u * it));
                 } else {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
@@ -1153,11 +1157,13 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
             if (it >= nvec) continue;
             const V4 g = *reinterpret_cast<const V4 *>(&acc[4u * it]);
             V4 w, st;
-            if (RULE == 1 && s.keep_array) w = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
+            if (s.keep_array) w = *reinterpret_cast<const V4 *>(dst + r0 + 4u * it);
             else w = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(dst + r0 + 4u * it));
             if constexpr (RULE == 0) {
-                w += g;
-                __builtin_nontemporal_store(w, reinterpret_cast<V4 *>(dst + r0 + 4u * it));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = __fadd_rn(w[e], __fmul_rn(g[e], lr));
+                if (s.keep_array) *reinterpret_cast<V4 *>(dst + r0 + 4u * it) = w;
+                else __builtin_nontemporal_store(w, reinterpret_cast<V4 *>(dst + r0 + 4u * it));
             } else {
                 st = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(state + r0 + 4u * it));
 #pragma unroll
@@ -1179,7 +1185,7 @@ __global__ __launch_bounds__(kReduceBlock) __attribute__((amdgpu_waves_per_eu(8,
         const float g = acc[i];
         if (g == 0.0f) continue;
         if constexpr (RULE == 0) {
-            dst[r0 + i] += g;
+            dst[r0 + i] = __fadd_rn(dst[r0 + i], __fmul_rn(g, lr));
         } else {
             float wk = dst[r0 + i], sk = state[r0 + i];
             adagrad_one(wk, sk, g, lr, eps);

@@ -91,6 +91,10 @@ def test_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.robe_backward_adagrad(ref, fake, fake, None, 4, 2, 2, fake, fake, 0.01, 1e-8, None, 0, None, None) == EINVAL  # no workspace
     assert b"workspace" in L.robe_last_error()
     assert L.robe_sgd_update(ref, None, fake, 1.0, None) == EINVAL
+    assert L.robe_backward_sgd(ref, fake, fake, None, 4, 2, 2, None, 1.0, None, 0, None, None) == EINVAL
+    assert L.robe_backward_sgd(ref, fake, fake, None, 4, 2, 2, fake, float("inf"), None, 0, None, None) == EINVAL
+    assert L.robe_backward_sgd(ref, fake, fake, None, 4, 2, 2, fake, 1.0, None, 0, None, None) == EINVAL    # no workspace
+    assert L.robe_backward_sgd(ref, None, None, None, 0, 0, 2, fake, 1.0, None, 0, None, None) == robe.ROBE_OK
     assert L.robe_sgd_update(ref, fake, fake, float("inf"), None) == EINVAL
     assert L.robe_offsets(ref, None, 3, 2, fake, None, None) == EINVAL
     assert L.robe_offsets(ref, fake, -3, 2, fake, None, None) == EINVAL

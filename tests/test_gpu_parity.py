@@ -342,6 +342,44 @@ def _check_fused(h, H, Gi, ids, off, B, F, m, shift=0, options=None):
     assert untouched.all() or not bits_equal(Mg, M0)
 
 
+@pytest.mark.parametrize("route", [robe.ROUTE_REGIONS, robe.ROUTE_TWO_STEP, robe.ROUTE_AUTO])
+@pytest.mark.parametrize("sign", [0, 1])
+@pytest.mark.parametrize("m,d,Z,records", [(1_000_003, 128, 32, 0), (2**26 + 3, 64, 32, 2), (1000, 64, 32, 0), (100_003, 16, 64, 0)])
+def test_fused_backward_sgd_matches_backward_then_sgd(m, d, Z, records, sign, route):
+    # robe_backward_sgd against oracle.backward -> oracle.sgd.  Small-integer gradients make every
+    # slot's sum exact and lr = 1 makes the product exact, so the step is the correctly rounded
+    # difference: bit for bit, on the region route (both record variants), the two-step route and
+    # whatever the library picks; then lr = 0.01 within the float32 rounding of product and difference.
+    opt = robe.options(fused_route=route, region_records=records)
+    h, H = both_hashes(29 * m + Z + sign, m, d, Z, sign)
+    F, B = 26, 200
+    rng = np.random.default_rng(m % 1000 + d)
+    ids = rng.integers(0, 3000, size=(B, F), dtype=np.int64)
+    ids[rng.random((B, F)) < 0.3] = 11
+    Gi = rng.integers(-3, 4, size=(B, F, d)).astype(np.float32)
+    g, _ = oracle.backward(H, Gi, ids, None, B, F)
+    M0 = rng.standard_normal(m).astype(np.float32)
+    for lr in (1.0, 0.01):
+        Md = to_dev(M0)
+        robe.robe_backward_sgd(h, to_dev(Gi), to_dev(ids), None, B, F, Md, lr, options=opt)
+        Mo, go = M0.copy(), g.astype(np.float32)
+        oracle.sgd(Mo, go, lr)
+        Mg = Md.cpu().numpy()
+        assert bits_equal(Mg[g == 0], M0[g == 0])
+        if lr == 1.0:
+            assert bits_equal(Mg, Mo)
+        else:
+            assert np.all(np.abs(Mg.astype(np.float64) - Mo) <= 1e-6 * (np.abs(M0) + np.abs(lr * g)) + TINY)
+    # bags
+    idsb, off = random_bags(rng, B * F, 3000, 6.0, long_bag=700)
+    gb, _ = oracle.backward(H, Gi, idsb, off, B, F)
+    Md = to_dev(M0)
+    robe.robe_backward_sgd(h, to_dev(Gi), to_dev(idsb), to_dev(off), B, F, Md, 1.0, options=opt)
+    Mo, go = M0.copy(), gb.astype(np.float32)
+    oracle.sgd(Mo, go, 1.0)
+    assert bits_equal(Md.cpu().numpy(), Mo)
+
+
 @pytest.mark.parametrize("rshift", [0, 10, 15])
 @pytest.mark.parametrize("sign", [0, 1])
 @pytest.mark.parametrize("m,d,Z", [(1_000_003, 128, 32), (100_003, 64, 8), (1000, 64, 32), (300_007, 128, 128), (70_001, 16, 1),
